@@ -1,0 +1,167 @@
+/*
+ * ddtree.h -- C ABI of the DDTree draft-tree step for AMD MI355X (gfx950).
+ *
+ * One decoding round of the paper's method (Section 4.1, steps 2-4) is
+ *     ddtree_topk -> ddtree_build -> ddtree_verify_attn (per target layer) -> ddtree_accept
+ * followed by ddtree_compact to close the round (Section 4.4, last sentence).
+ *
+ * Notation (the paper's own letters in brackets):
+ *   batch  independent sequences handled by one call
+ *   B      number of draft positions = rows of drafter logits            [L]
+ *   V      vocabulary size                                               [|V|]
+ *   N      node budget, the root not counted                             [B]
+ *   K      candidates kept per position, K = min(N, V)  (Lemma 1)        [K]
+ *   T      N + 1 verifier rows per sequence; row 0 is the root, i.e. the bonus token b
+ *   W      ceil(T / 64) 64-bit words per ancestor-mask row
+ *   L      context rows already in the KV cache of a sequence
+ *
+ * Conventions shared by every entry point
+ *   - Return value: DDTREE_OK or a negative DDTREE_ERR_* code.  Arguments are validated on
+ *     the host before anything is launched; a call that returns an error has launched nothing.
+ *   - Pointers marked [device] are device memory owned by the caller; the library never
+ *     allocates, frees or retains them.  Pointers marked [host] are read during the call only.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
+ *     work on it and never synchronise; consecutive calls on one stream are ordered.
+ *   - `workspace` [device] is scratch of at least ddtree_workspace_bytes(...) bytes, 256-byte
+ *     aligned, whose contents need not survive between calls.  Calls on different streams need
+ *     different workspaces.
+ *   - All arrays are dense, row-major, in the index order written next to them.
+ *   - Logits must be finite (the paper assumes probabilities in (0,1), Section 4.2).
+ */
+#ifndef DDTREE_H
+#define DDTREE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DDTREE_OK 0
+#define DDTREE_ERR_ARG (-1)       /* null pointer, bad shape, unsupported size or dtype */
+#define DDTREE_ERR_WORKSPACE (-2) /* workspace missing, misaligned or too small          */
+#define DDTREE_ERR_HIP (-3)       /* the HIP runtime reported a launch failure           */
+
+#define DDTREE_DTYPE_BF16 0
+#define DDTREE_DTYPE_FP32 1
+
+#define DDTREE_MAX_B 32      /* draft positions                 */
+#define DDTREE_MAX_N 1024    /* node budget                     */
+#define DDTREE_MAX_BATCH 64  /* sequences per call              */
+
+/* Library version, major * 100 + minor. */
+int ddtree_version(void);
+
+/* Static text for a return code. */
+const char *ddtree_error_string(int code);
+
+/*
+ * Scratch size, in bytes, that covers every entry point for the given problem:
+ * max_sum_L is an upper bound on the total number of cache rows over the batch.
+ * Returns 0 if the shape is not supported.  Pure host arithmetic.
+ */
+size_t ddtree_workspace_bytes(int batch, int B, int V, int N, int Hq, int Hkv, int D,
+                              int max_sum_L);
+
+/*
+ * Per-position log-probabilities and rank ordering (Section 4.3: q_i = softmax(l_i), tokens
+ * ordered so that q_i^(1) >= q_i^(2) >= ..., and the scores sigma are sums of log q; Lemma 1
+ * bounds the ranks that can matter by K).
+ *   logits    [device] fp32 [batch, B, V]
+ *   topk_tok  [device] int32 [batch, B, K]  token of rank k at position d; equal logits are
+ *                                           ranked by ascending token id
+ *   topk_lp   [device] fp32 [batch, B, K]   log q_d(topk_tok[d][k]) = logit - logsumexp(row),
+ *                                           the log-sum-exp evaluated in fp64, rounded once
+ * Requires 1 <= K <= min(V, DDTREE_MAX_N), 1 <= B <= DDTREE_MAX_B.
+ */
+int ddtree_topk(const float *logits, int batch, int B, int V, int K, int32_t *topk_tok,
+                float *topk_lp, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Best-first tree construction (Algorithm 1) plus the tensors the verifier needs
+ * (Section 4.4, first paragraph: token ids rooted at b, depth as position id, ancestor-only
+ * visibility).  Node 0 is the root; nodes 1..n_nodes are numbered in pop order, so
+ * parent[i] < i and node scores are non-increasing.  Scores are fp32 left folds of topk_lp
+ * along the rank tuple; of two equal scores the lexicographically smaller rank tuple is
+ * popped first (a prefix before its extensions).
+ *   topk_tok, topk_lp [device] as produced by ddtree_topk, [batch, B, K]
+ *   root_token  [device] int32 [batch]        the bonus token of each sequence
+ *   tokens      [device] int32 [batch, N+1]   tokens[0] = root_token
+ *   parent      [device] int32 [batch, N+1]   parent[0] = -1
+ *   depth       [device] int32 [batch, N+1]   depth[0] = 0; position id = L + depth
+ *   rank        [device] int32 [batch, N+1]   0-based rank of the node's token, rank[0] = -1
+ *                                             (nullable)
+ *   node_score  [device] fp32 [batch, N+1]    sigma of the node, node_score[0] = 0 (nullable)
+ *   ancestor_mask [device] uint64 [batch, N+1, W]  bit j of row i (word j/64, bit j%64) is set
+ *                                             iff j is the root, an ancestor of i, or i
+ *   n_nodes     [device] int32 [batch]        nodes built, = N unless fewer prefixes exist
+ * Rows past n_nodes hold tokens = parent = depth = rank = -1, score 0 and a zero mask row.
+ * Requires 1 <= N <= DDTREE_MAX_N, 1 <= K <= DDTREE_MAX_N, 1 <= B <= DDTREE_MAX_B.
+ */
+int ddtree_build(const int32_t *topk_tok, const float *topk_lp, int batch, int B, int K, int N,
+                 const int32_t *root_token, int32_t *tokens, int32_t *parent, int32_t *depth,
+                 int32_t *rank, float *node_score, uint64_t *ancestor_mask, int32_t *n_nodes,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * One layer of tree attention (Section 4.4, first paragraph): query row i of a sequence
+ * attends to all of that sequence's cache rows and to the tree rows j whose bit is set in
+ * ancestor_mask[i]; softmax(q.k * softmax_scale) weighted sum of the value rows.  Query head h
+ * reads KV head h / (Hq / Hkv).  Rows whose own mask bit is clear (padding rows) produce zeros.
+ *   q          [device] [batch*T, Hq, D]
+ *   k_cache, v_cache [device] [sum_L, Hkv, D]   sequence s owns rows kv_offset[s]..kv_offset[s+1]
+ *   k_tree, v_tree   [device] [batch*T, Hkv, D] sequence s owns rows s*T..(s+1)*T
+ *   ancestor_mask    [device] uint64 [batch, T, W]
+ *   kv_offset        [host]   int32 [batch+1], non-decreasing, kv_offset[0] >= 0
+ *   dtype      DDTREE_DTYPE_BF16 (bf16 in/out, fp32 accumulation and softmax) or
+ *              DDTREE_DTYPE_FP32 (fp32 throughout)
+ *   out        [device] [batch*T, Hq, D], same dtype as q
+ * Requires Hq % Hkv == 0, D a multiple of 8 and <= 256, T <= DDTREE_MAX_N + 1,
+ * batch <= DDTREE_MAX_BATCH.  bf16 with D = 128 runs on the matrix cores.
+ */
+int ddtree_verify_attn(const void *q, const void *k_cache, const void *v_cache,
+                       const void *k_tree, const void *v_tree, const uint64_t *ancestor_mask,
+                       const int32_t *kv_offset, int batch, int T, int Hq, int Hkv, int D,
+                       float softmax_scale, int dtype, void *out, void *workspace,
+                       size_t workspace_bytes, void *stream);
+
+/*
+ * Greedy verifier walk (Section 4.4, second paragraph; Figure 1b): posterior[i] is the argmax
+ * of the target's logits at node i (lowest id among equal maxima).  Starting at the root, the
+ * walk moves to the child of the current node whose token equals the posterior of the current
+ * node, and stops when there is none.
+ *   target_logits [device] fp32 [batch, T, V]
+ *   tokens, parent, depth [device] int32 [batch, T]   from ddtree_build
+ *   n_nodes       [device] int32 [batch]              rows past n_nodes are not read
+ *   path          [device] int32 [batch, B+1]  path[0] = 0, then the accepted node ids; unused
+ *                                              slots are -1
+ *   n_accepted    [device] int32 [batch]       accepted drafted nodes, 0..B (the accepted length
+ *                                              "including the bonus token" is n_accepted + 1)
+ *   bonus_token   [device] int32 [batch]       posterior of the last node on the path
+ *   posterior     [device] int32 [batch, T]    nullable; -1 on rows past n_nodes
+ */
+int ddtree_accept(const float *target_logits, int batch, int T, int V, const int32_t *tokens,
+                  const int32_t *parent, const int32_t *depth, const int32_t *n_nodes,
+                  int32_t *path, int32_t *n_accepted, int32_t *bonus_token, int32_t *posterior,
+                  int B, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Cache compaction (Section 4.4, last sentence): the cache keeps only the accepted path.  For
+ * every sequence s and j = 0..n_accepted[s]: cache[dst_row[s] + j] = tree[s*T + path[s][j]]
+ * (j = 0 is the root, whose key/value rows were not in the cache before this round).
+ *   k_tree, v_tree   [device] [batch*T, Hkv, D]
+ *   path             [device] int32 [batch, B+1], n_accepted [device] int32 [batch]
+ *   dst_row          [host]   int32 [batch]  first cache row to write for each sequence
+ *                                            (normally the sequence's current length)
+ *   k_cache, v_cache [device] [cache_rows, Hkv, D]; rows dst_row[s] .. dst_row[s]+B must exist
+ *   elem_bytes       2 (bf16) or 4 (fp32)
+ */
+int ddtree_compact(const void *k_tree, const void *v_tree, const int32_t *path,
+                   const int32_t *n_accepted, const int32_t *dst_row, int batch, int T, int B,
+                   int Hkv, int D, int elem_bytes, void *k_cache, void *v_cache, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DDTREE_H */

@@ -296,6 +296,9 @@ static void attn_row(const float *q, const float *k_cache, const float *v_cache,
     int hk = h / (Hq / Hkv);
     const float *qi = q + ((size_t)i * Hq + h) * D;
     int n = 0;
+    for (int c = 0; c < D; ++c) out[c] = 0.0;
+    /* every real node sees itself; a row whose own bit is clear is padding: output zero */
+    if (!((mask[(size_t)i * W + (i >> 6)] >> (i & 63)) & 1)) return;
     double mx = -INFINITY;
     for (int j = 0; j < L; ++j) {
         const float *kj = k_cache + ((size_t)j * Hkv + hk) * D;
@@ -314,8 +317,6 @@ static void attn_row(const float *q, const float *k_cache, const float *v_cache,
         w[n++] = s;
         if (s > mx) mx = s;
     }
-    for (int c = 0; c < D; ++c) out[c] = 0.0;
-    if (n == 0) return; /* padding row: no visible key, output zero */
     double Z = 0.0;
     for (int t = 0; t < n; ++t) {
         w[t] = exp(w[t] - mx);
