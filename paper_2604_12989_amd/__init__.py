@@ -1,0 +1,14 @@
+"""MI355X-native DDTree draft-tree step: Python binding over the C-ABI library libddtree.so.
+
+The binding only marshals arguments (device pointers of torch tensors, sizes, the current
+stream); every step of the path runs in the HIP kernels under csrc/.  The library must have
+been built (python -m paper_2604_12989_amd.build, or __graft_entry__.build()); there is no
+fallback path.
+"""
+from .binding import (DDTreeError, accept, build, compact, error_string, library_path, load,
+                      topk, verify_attn, version, workspace_bytes, Workspace, DTYPE_BF16,
+                      DTYPE_FP32)
+
+__all__ = ["DDTreeError", "accept", "build", "compact", "error_string", "library_path", "load",
+           "topk", "verify_attn", "version", "workspace_bytes", "Workspace", "DTYPE_BF16",
+           "DTYPE_FP32"]

@@ -1,0 +1,254 @@
+// Greedy verifier walk (paper Section 4.4, second paragraph, and Figure 1b) and cache compaction
+// (Section 4.4, last sentence).
+//
+//   argmax kernel  HBM-bound scan of the target logits: one workgroup per (row, segment),
+//                  coalesced 16-byte loads, first-maximum semantics (lowest id among equal
+//                  maxima), one (value, index) partial per segment.
+//   walk kernel    one workgroup per sequence: folds the partials into the posterior token of
+//                  every node, then decides acceptance for all nodes at once: node i is accepted
+//                  iff every node on its root path carries the token its parent's posterior
+//                  chose.  The accepted nodes form the single path the sequential walk of the
+//                  paper visits, and the deepest one yields the bonus token.
+//   compact kernel copies the accepted tree rows of K and V behind the cache.
+#include "common.hpp"
+
+namespace ddt {
+
+constexpr int kArgmaxThreads = 256;
+constexpr int kWalkThreads = 256;
+
+AcceptPlan accept_plan(int batch, int T, int V)
+{
+    AcceptPlan p{};
+    long long rows = (long long)batch * T;
+    int S = (int)((1024 + rows - 1) / rows);
+    int s_cap = V / 8192 > 0 ? V / 8192 : 1;  // keep segments at least 8192 long
+    if (S > s_cap) S = s_cap;
+    if (S < 1) S = 1;
+    int len = (V + S - 1) / S;
+    len = (len + 3) / 4 * 4;
+    p.seg_len = len;
+    p.splits = (V + len - 1) / len;
+    p.part_off = 0;
+    p.bytes = align_up((size_t)rows * p.splits * 8, 256);
+    return p;
+}
+
+struct ArgPart {
+    float val;
+    int32_t idx;
+};
+
+__device__ __forceinline__ void arg_update(float &bv, int &bi, float v, int i)
+{
+    if (v > bv || (v == bv && i < bi)) {
+        bv = v;
+        bi = i;
+    }
+}
+
+__global__ __launch_bounds__(kArgmaxThreads) void accept_argmax_kernel(
+    const float *__restrict__ logits, int T, int V, int seg_len, int splits,
+    const int32_t *__restrict__ n_nodes, ArgPart *__restrict__ part)
+{
+    __shared__ float s_v[kArgmaxThreads / 64];
+    __shared__ int s_i[kArgmaxThreads / 64];
+    const int tid = threadIdx.x;
+    const int seg = blockIdx.x, i = blockIdx.y, seq = blockIdx.z;
+    if (i > n_nodes[seq]) return;  // padding row: never read, the walk ignores its partial
+    const size_t rowi = (size_t)seq * T + i;
+    const int start = seg * seg_len;
+    const int n = min(seg_len, V - start);
+    const float *p = logits + rowi * (size_t)V + start;
+
+    float bv = -INFINITY;
+    int bi = 0x7FFFFFFF;
+    int head = (int)((4 - ((reinterpret_cast<uintptr_t>(p) >> 2) & 3)) & 3);
+    if (head > n) head = n;
+    if (tid < head) {
+        bv = p[tid];
+        bi = start + tid;
+    }
+    const int nvec = (n - head) >> 2;
+    const float4 *pv = reinterpret_cast<const float4 *>(p + head);
+    int j = tid;
+    // two independent 16-byte loads in flight per thread and iteration
+    for (; j + kArgmaxThreads < nvec; j += 2 * kArgmaxThreads) {
+        const float4 a = pv[j];
+        const float4 b = pv[j + kArgmaxThreads];
+        const int ia = start + head + 4 * j, ib = ia + 4 * kArgmaxThreads;
+        if (a.x > bv) { bv = a.x; bi = ia; }
+        if (a.y > bv) { bv = a.y; bi = ia + 1; }
+        if (a.z > bv) { bv = a.z; bi = ia + 2; }
+        if (a.w > bv) { bv = a.w; bi = ia + 3; }
+        if (b.x > bv) { bv = b.x; bi = ib; }
+        if (b.y > bv) { bv = b.y; bi = ib + 1; }
+        if (b.z > bv) { bv = b.z; bi = ib + 2; }
+        if (b.w > bv) { bv = b.w; bi = ib + 3; }
+    }
+    for (; j < nvec; j += kArgmaxThreads) {
+        const float4 a = pv[j];
+        const int ia = start + head + 4 * j;
+        if (a.x > bv) { bv = a.x; bi = ia; }
+        if (a.y > bv) { bv = a.y; bi = ia + 1; }
+        if (a.z > bv) { bv = a.z; bi = ia + 2; }
+        if (a.w > bv) { bv = a.w; bi = ia + 3; }
+    }
+    const int tail0 = head + 4 * nvec;
+    if (tid < n - tail0) {
+        const float x = p[tail0 + tid];
+        if (x > bv) { bv = x; bi = start + tail0 + tid; }
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const float ov = __shfl_xor(bv, d, 64);
+        const int oi = __shfl_xor(bi, d, 64);
+        arg_update(bv, bi, ov, oi);
+    }
+    if ((tid & 63) == 0) {
+        s_v[tid >> 6] = bv;
+        s_i[tid >> 6] = bi;
+    }
+    __syncthreads();
+    if (tid == 0) {
+#pragma unroll
+        for (int w = 1; w < kArgmaxThreads / 64; ++w) arg_update(bv, bi, s_v[w], s_i[w]);
+        ArgPart r;
+        r.val = bv;
+        r.idx = bi;
+        part[rowi * splits + seg] = r;
+    }
+}
+
+__global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(
+    const ArgPart *__restrict__ part, int T, int splits, int B, const int32_t *__restrict__ tokens,
+    const int32_t *__restrict__ parent, const int32_t *__restrict__ depth,
+    const int32_t *__restrict__ n_nodes, int32_t *__restrict__ path,
+    int32_t *__restrict__ n_accepted, int32_t *__restrict__ bonus_token,
+    int32_t *__restrict__ posterior)
+{
+    __shared__ int s_post[DDTREE_MAX_N + 1];
+    __shared__ int s_tok[DDTREE_MAX_N + 1];
+    __shared__ int s_par[DDTREE_MAX_N + 1];
+    __shared__ int s_path[DDTREE_MAX_B + 1];
+    __shared__ int s_len;
+    const int tid = threadIdx.x;
+    const int seq = blockIdx.x;
+    const int n = n_nodes[seq];
+    const size_t base = (size_t)seq * T;
+    for (int i = tid; i < T; i += kWalkThreads) {
+        int post = -1;
+        if (i <= n) {
+            const ArgPart *pp = part + (base + i) * splits;
+            float bv = pp[0].val;
+            post = pp[0].idx;
+            for (int s = 1; s < splits; ++s)
+                if (pp[s].val > bv) {  // later segments hold higher ids: strict > keeps the first
+                    bv = pp[s].val;
+                    post = pp[s].idx;
+                }
+        }
+        s_post[i] = post;
+        s_tok[i] = i <= n ? tokens[base + i] : -1;
+        s_par[i] = i <= n ? parent[base + i] : -1;
+        if (posterior) posterior[base + i] = post;
+    }
+    if (tid <= B) s_path[tid] = tid == 0 ? 0 : -1;
+    if (tid == 0) s_len = 0;
+    __syncthreads();
+    for (int i = 1 + tid; i <= n; i += kWalkThreads) {
+        bool ok = true;
+        int j = i;
+        while (j > 0 && ok) {
+            const int pj = s_par[j];
+            ok = s_tok[j] == s_post[pj];
+            j = pj;
+        }
+        if (ok) {
+            const int d = depth[base + i];
+            if (d >= 1 && d <= B) {
+                s_path[d] = i;
+                atomicMax(&s_len, d);
+            }
+        }
+    }
+    __syncthreads();
+    if (tid <= B) path[(size_t)seq * (B + 1) + tid] = s_path[tid];
+    if (tid == 0) {
+        const int len = s_len;
+        n_accepted[seq] = len;
+        bonus_token[seq] = s_post[s_path[len]];
+    }
+}
+
+struct CompactArgs {
+    int32_t dst_row[DDTREE_MAX_BATCH];
+};
+
+__global__ __launch_bounds__(256) void compact_kernel(
+    const uint32_t *__restrict__ k_tree, const uint32_t *__restrict__ v_tree,
+    const int32_t *__restrict__ path, const int32_t *__restrict__ n_accepted, CompactArgs args,
+    int T, int B, int row_words, uint32_t *__restrict__ k_cache, uint32_t *__restrict__ v_cache)
+{
+    const int j = blockIdx.x, seq = blockIdx.y;
+    if (j > n_accepted[seq]) return;
+    const int node = path[(size_t)seq * (B + 1) + j];
+    if (node < 0 || node >= T) return;
+    const size_t src = ((size_t)seq * T + node) * row_words;
+    const size_t dst = ((size_t)args.dst_row[seq] + j) * row_words;
+    for (int w = threadIdx.x; w < row_words; w += blockDim.x) {
+        k_cache[dst + w] = k_tree[src + w];
+        v_cache[dst + w] = v_tree[src + w];
+    }
+}
+
+}  // namespace ddt
+
+extern "C" int ddtree_accept(const float *target_logits, int batch, int T, int V,
+                             const int32_t *tokens, const int32_t *parent, const int32_t *depth,
+                             const int32_t *n_nodes, int32_t *path, int32_t *n_accepted,
+                             int32_t *bonus_token, int32_t *posterior, int B, void *workspace,
+                             size_t workspace_bytes, void *stream)
+{
+    using namespace ddt;
+    if (!target_logits || !tokens || !parent || !depth || !n_nodes || !path || !n_accepted ||
+        !bonus_token)
+        return DDTREE_ERR_ARG;
+    if (batch < 1 || batch > DDTREE_MAX_BATCH || T < 2 || T > DDTREE_MAX_N + 1 || V < 1 || B < 1 ||
+        B > DDTREE_MAX_B)
+        return DDTREE_ERR_ARG;
+    AcceptPlan p = accept_plan(batch, T, V);
+    if (!ws_ok(workspace, workspace_bytes, p.bytes)) return DDTREE_ERR_WORKSPACE;
+    ArgPart *part = reinterpret_cast<ArgPart *>(static_cast<char *>(workspace) + p.part_off);
+    hipStream_t st = as_stream(stream);
+    hipLaunchKernelGGL(accept_argmax_kernel, dim3(p.splits, T, batch), dim3(kArgmaxThreads), 0, st,
+                       target_logits, T, V, p.seg_len, p.splits, n_nodes, part);
+    hipLaunchKernelGGL(accept_walk_kernel, dim3(batch), dim3(kWalkThreads), 0, st, part, T, p.splits,
+                       B, tokens, parent, depth, n_nodes, path, n_accepted, bonus_token, posterior);
+    return launch_status();
+}
+
+extern "C" int ddtree_compact(const void *k_tree, const void *v_tree, const int32_t *path,
+                              const int32_t *n_accepted, const int32_t *dst_row, int batch, int T,
+                              int B, int Hkv, int D, int elem_bytes, void *k_cache, void *v_cache,
+                              void *stream)
+{
+    using namespace ddt;
+    if (!k_tree || !v_tree || !path || !n_accepted || !dst_row || !k_cache || !v_cache)
+        return DDTREE_ERR_ARG;
+    if (batch < 1 || batch > DDTREE_MAX_BATCH || T < 2 || B < 1 || B > DDTREE_MAX_B || Hkv < 1 ||
+        D < 1 || (elem_bytes != 2 && elem_bytes != 4))
+        return DDTREE_ERR_ARG;
+    const long long row_bytes = (long long)Hkv * D * elem_bytes;
+    if (row_bytes % 4 != 0) return DDTREE_ERR_ARG;
+    CompactArgs args;
+    for (int s = 0; s < batch; ++s) {
+        if (dst_row[s] < 0) return DDTREE_ERR_ARG;
+        args.dst_row[s] = dst_row[s];
+    }
+    hipLaunchKernelGGL(compact_kernel, dim3(B + 1, batch), dim3(256), 0, as_stream(stream),
+                       static_cast<const uint32_t *>(k_tree), static_cast<const uint32_t *>(v_tree),
+                       path, n_accepted, args, T, B, (int)(row_bytes / 4),
+                       static_cast<uint32_t *>(k_cache), static_cast<uint32_t *>(v_cache));
+    return launch_status();
+}

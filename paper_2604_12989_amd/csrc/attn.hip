@@ -1,0 +1,588 @@
+// Tree attention for the verifier pass (paper Section 4.4, first paragraph): every tree node
+// attends to the whole cached context and, inside the tree, only to the root, its ancestors and
+// itself (the ancestor bitmask).
+//
+// Two device paths behind ddtree_verify_attn:
+//   * attn_mfma_kernel   bf16, head_dim 128: flash-style kernel on the gfx950 matrix cores.
+//   * attn_generic_kernel  any supported shape and fp32: one workgroup per (node, head) on the
+//                        vector ALUs; used for the small fp32 configuration and odd shapes.
+//
+// MFMA kernel.  Query rows of one KV head are the (node, group-head) pairs, G = Hq/Hkv per node,
+// so one K/V tile serves G*T rows.  A workgroup (4 waves) owns 256 consecutive rows (64 per
+// wave) and a contiguous range of 64-key tiles (split-KV; partial results are merged by
+// attn_merge_kernel).  Per tile:
+//   S^T = K Q^T   v_mfma_f32_32x32x16_bf16, A = K tile from LDS (row = key), B = Q^T held in
+//                 registers for the whole kernel.  In the accumulator layout a lane then owns
+//                 one query row, so the softmax max and sum are register-local reductions.
+//   P^T           exp2 of the scaled, masked scores; the accumulator registers of S^T are, as
+//                 they stand, the B operand of the next product (no cross-lane movement), once
+//                 the V tile is stored transposed with a matching key permutation.
+//   O^T += V^T P^T
+// K tiles sit in LDS as [key][dim] (row padded by 16 B), V tiles as [dim][key'] where key' is
+// the permuted key position, both written once per tile from 16-byte global loads.
+// The ancestor mask touches only the tree tiles (the last ceil(T/64) tiles): one 64-bit word per
+// (row, tile), bit test per score.  Cache tiles carry no mask work at all.
+#include "common.hpp"
+
+namespace ddt {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+
+constexpr int kAttnThreads = 256;
+constexpr int kMT = 256;       // query rows per workgroup
+constexpr int kKT = 64;        // keys per tile
+constexpr int kHD = 128;       // head dim of the MFMA path
+constexpr int kKStride = kHD + 8;   // bf16 elements per K row in LDS (272 B)
+constexpr int kVStride = kKT + 8;   // bf16 elements per V^T row in LDS (144 B)
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct AttnArgs {
+    int32_t kv_offset[DDTREE_MAX_BATCH + 1];
+};
+
+AttnPlan attn_plan(int batch, int T, int Hq, int Hkv, int D, long long sum_L, int dtype)
+{
+    AttnPlan p{};
+    p.splits = 1;
+    p.mtiles = 0;
+    p.bytes = 0;
+    if (!(dtype == DDTREE_DTYPE_BF16 && D == kHD)) return p;  // generic path needs no scratch
+    const int G = Hq / Hkv;
+    const long long M = (long long)T * G;
+    p.mtiles = (int)((M + kMT - 1) / kMT);
+    const long long full = M / kMT > 0 ? M / kMT : 1;
+    const long long base = (long long)batch * Hkv * full;
+    int S;
+    if (base >= 512) S = 1;
+    else if (base >= 256) S = 2;
+    else S = (int)((256 + base - 1) / base);
+    // keep at least four tiles per split on average
+    const long long tiles = (sum_L / batch + T) / kKT;
+    if ((long long)S * 4 > tiles) S = (int)(tiles / 4 > 0 ? tiles / 4 : 1);
+    if (S > 32) S = 32;
+    p.splits = S;
+    if (S > 1) {
+        const size_t rows = (size_t)batch * T * Hq;
+        p.part_off = 0;
+        p.lse_off = align_up((size_t)S * rows * D * 4, 256);
+        p.bytes = align_up(p.lse_off + (size_t)S * rows * 4, 256);
+    }
+    return p;
+}
+
+// Upper bound of attn_plan(...).bytes over all sum_L: splits only shrink with shorter caches.
+static size_t attn_ws_upper(int batch, int T, int Hq, int Hkv, int D)
+{
+    AttnPlan p = attn_plan(batch, T, Hq, Hkv, D, (long long)1 << 40, DDTREE_DTYPE_BF16);
+    return p.bytes;
+}
+
+__device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xFFFFu) | (b << 16); }
+__device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xFFFF0000u); }
+__device__ __forceinline__ uint32_t f2bf_pair(float lo, float hi)
+{
+    const __bf16 a = (__bf16)lo, b = (__bf16)hi;
+    return (uint32_t)__builtin_bit_cast(unsigned short, a) |
+           ((uint32_t)__builtin_bit_cast(unsigned short, b) << 16);
+}
+
+__global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_cache,
+                      const uint16_t *__restrict__ v_cache, const uint16_t *__restrict__ k_tree,
+                      const uint16_t *__restrict__ v_tree, const uint64_t *__restrict__ mask,
+                      AttnArgs args, int T, int Hq, int Hkv, float scale_log2e, int splits,
+                      uint16_t *__restrict__ out, float *__restrict__ part, float *__restrict__ part_lse)
+{
+    __shared__ __align__(16) uint16_t sK[kKT * kKStride];
+    __shared__ __align__(16) uint16_t sVt[kHD * kVStride];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int split = blockIdx.x;
+    const int hk = blockIdx.y % Hkv, mt = blockIdx.y / Hkv;
+    const int seq = blockIdx.z;
+    const int G = Hq / Hkv;
+    const int W = (T + 63) >> 6;
+    const int M = T * G;
+    const int L0 = args.kv_offset[seq];
+    const int L = args.kv_offset[seq + 1] - L0;
+    const int m0 = mt * kMT;
+    const int last_node = min(T - 1, (m0 + kMT - 1) / G);
+    const int n_cache_tiles = (L + kKT - 1) / kKT;
+    const int n_tree_tiles = last_node / kKT + 1;
+    const int nt = n_cache_tiles + n_tree_tiles;
+    const int t_begin = (int)((long long)nt * split / splits);
+    const int t_end = (int)((long long)nt * (split + 1) / splits);
+    const bool wave_active = m0 + wave * 64 < M;
+
+    // this lane's two query rows (cb = 0, 1)
+    int node_[2], rowg_[2];
+    bool rvalid[2];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        const int r = m0 + wave * 64 + cb * 32 + l32;
+        rvalid[cb] = r < M;
+        const int node = rvalid[cb] ? r / G : 0;
+        const int g = rvalid[cb] ? r - node * G : 0;
+        node_[cb] = node;
+        rowg_[cb] = (seq * T + node) * Hq + hk * G + g;
+    }
+    // Q^T operand: lane holds Q[row][16*ks + 8*half .. +8]
+    bf16x8 qreg[2][8];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (rvalid[cb])
+                v = *reinterpret_cast<const uint4 *>(q + (size_t)rowg_[cb] * kHD + ks * 16 + half * 8);
+            qreg[cb][ks] = __builtin_bit_cast(bf16x8, v);
+        }
+
+    floatx16 o[4][2];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[db][cb][v] = 0.0f;
+    float m_run[2] = {-INFINITY, -INFINITY};
+    float l_run[2] = {0.0f, 0.0f};
+
+    // global -> register staging of one tile
+    uint4 kst[2], vst[4];
+    const int v_dg = tid & 15, v_kg = tid >> 4;  // V: 8 dims x 4 keys per thread
+    auto tile_src = [&](int t, const uint16_t *&kp, const uint16_t *&vp, int &valid) {
+        if (t < n_cache_tiles) {
+            const size_t row0 = (size_t)L0 + (size_t)t * kKT;
+            kp = k_cache + (row0 * Hkv + hk) * kHD;
+            vp = v_cache + (row0 * Hkv + hk) * kHD;
+            valid = min(kKT, L - t * kKT);
+        } else {
+            const int tb = t - n_cache_tiles;
+            const size_t row0 = (size_t)seq * T + (size_t)tb * kKT;
+            kp = k_tree + (row0 * Hkv + hk) * kHD;
+            vp = v_tree + (row0 * Hkv + hk) * kHD;
+            valid = min(kKT, T - tb * kKT);
+        }
+    };
+    auto load_tile = [&](int t) {
+        const uint16_t *kp, *vp;
+        int valid;
+        tile_src(t, kp, vp, valid);
+        const size_t rs = (size_t)Hkv * kHD;  // elements between consecutive keys
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int id = tid + r * kAttnThreads;
+            const int key = id >> 4, ch = id & 15;
+            kst[r] = key < valid ? *reinterpret_cast<const uint4 *>(kp + key * rs + ch * 8)
+                                 : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int key = v_kg * 4 + j;
+            vst[j] = key < valid ? *reinterpret_cast<const uint4 *>(vp + key * rs + v_dg * 8)
+                                 : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto store_tile = [&]() {
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int id = tid + r * kAttnThreads;
+            const int key = id >> 4, ch = id & 15;
+            *reinterpret_cast<uint4 *>(&sK[key * kKStride + ch * 8]) = kst[r];
+        }
+        // keys 4*kg .. 4*kg+3 = 16*t' + 8*u + 4*h + w  ->  position 16*t' + 8*h + 4*u + w
+        const int tq = v_kg >> 2, u = (v_kg >> 1) & 1, h = v_kg & 1;
+        const int pos = 16 * tq + 8 * h + 4 * u;
+        const uint32_t a[4] = {vst[0].x, vst[0].y, vst[0].z, vst[0].w};
+        const uint32_t b[4] = {vst[1].x, vst[1].y, vst[1].z, vst[1].w};
+        const uint32_t c[4] = {vst[2].x, vst[2].y, vst[2].z, vst[2].w};
+        const uint32_t d[4] = {vst[3].x, vst[3].y, vst[3].z, vst[3].w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int w = i >> 1;
+            uint2 val;
+            if (i & 1) {
+                val.x = pack_hi(a[w], b[w]);
+                val.y = pack_hi(c[w], d[w]);
+            } else {
+                val.x = pack_lo(a[w], b[w]);
+                val.y = pack_lo(c[w], d[w]);
+            }
+            *reinterpret_cast<uint2 *>(&sVt[(v_dg * 8 + i) * kVStride + pos]) = val;
+        }
+    };
+
+    if (t_begin < t_end) load_tile(t_begin);
+    for (int t = t_begin; t < t_end; ++t) {
+        __syncthreads();
+        store_tile();
+        __syncthreads();
+        if (t + 1 < t_end) load_tile(t + 1);
+        if (!wave_active) continue;
+
+        const bool is_tree = t >= n_cache_tiles;
+        const int tb = t - n_cache_tiles;
+        const int valid = is_tree ? min(kKT, T - tb * kKT) : min(kKT, L - t * kKT);
+
+        // ---- S^T = K Q^T ----
+        floatx16 s[2][2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) s[kb][cb][v] = 0.0f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(
+                    &sK[(kb * 32 + l32) * kKStride + ks * 16 + half * 8]);
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb)
+                    s[kb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[cb][ks], s[kb][cb], 0, 0, 0);
+            }
+
+        // ---- mask (tree tiles and ragged last cache tile only) ----
+        if (is_tree || valid < kKT) {
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) {
+                uint64_t word = ~0ull;
+                if (is_tree)
+                    word = rvalid[cb] ? mask[((size_t)seq * T + node_[cb]) * W + tb] : 0ull;
+                if (valid < kKT) word &= (1ull << valid) - 1ull;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int key = kb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+                        if (!((word >> key) & 1ull)) s[kb][cb][v] = -INFINITY;
+                    }
+            }
+        }
+
+        // ---- online softmax, per query row (one row per lane and cb) ----
+        bf16x8 pb[2][4];
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            float tmax = -INFINITY;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, s[kb][cb][v]);
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+            const float m_new = fmaxf(m_run[cb], tmax * scale_log2e);
+            const float m_use = m_new == -INFINITY ? 0.0f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m_run[cb] - m_use);
+            m_run[cb] = m_new;
+            float psum = 0.0f;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float p = __builtin_amdgcn_exp2f(fmaf(s[kb][cb][v], scale_log2e, -m_use));
+                    s[kb][cb][v] = p;
+                    psum += p;
+                }
+#pragma unroll
+                for (int t2 = 0; t2 < 2; ++t2) {
+                    uint4 pk;
+                    pk.x = f2bf_pair(s[kb][cb][8 * t2 + 0], s[kb][cb][8 * t2 + 1]);
+                    pk.y = f2bf_pair(s[kb][cb][8 * t2 + 2], s[kb][cb][8 * t2 + 3]);
+                    pk.z = f2bf_pair(s[kb][cb][8 * t2 + 4], s[kb][cb][8 * t2 + 5]);
+                    pk.w = f2bf_pair(s[kb][cb][8 * t2 + 6], s[kb][cb][8 * t2 + 7]);
+                    pb[cb][kb * 2 + t2] = __builtin_bit_cast(bf16x8, pk);
+                }
+            }
+            l_run[cb] = l_run[cb] * alpha + psum;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[db][cb][v] *= alpha;
+        }
+
+        // ---- O^T += V^T P^T ----
+#pragma unroll
+        for (int kst4 = 0; kst4 < 4; ++kst4)
+#pragma unroll
+            for (int db = 0; db < 4; ++db) {
+                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(
+                    &sVt[(db * 32 + l32) * kVStride + kst4 * 16 + half * 8]);
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb)
+                    o[db][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[cb][kst4], o[db][cb], 0, 0, 0);
+            }
+    }
+
+    if (!wave_active) return;
+    // ---- epilogue ----
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        const float l_tot = l_run[cb] + __shfl_xor(l_run[cb], 32, 64);
+        if (!rvalid[cb]) continue;
+        const int node = node_[cb];
+        const bool real = (mask[((size_t)seq * T + node) * W + (node >> 6)] >> (node & 63)) & 1ull;
+        const float inv = (real && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
+        if (splits == 1) {
+            uint16_t *dst = out + (size_t)rowg_[cb] * kHD;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const int dim = db * 32 + g4 * 8 + half * 4;
+                    uint2 val;
+                    val.x = f2bf_pair(o[db][cb][4 * g4 + 0] * inv, o[db][cb][4 * g4 + 1] * inv);
+                    val.y = f2bf_pair(o[db][cb][4 * g4 + 2] * inv, o[db][cb][4 * g4 + 3] * inv);
+                    *reinterpret_cast<uint2 *>(dst + dim) = val;
+                }
+        } else {
+            const size_t rows_total = (size_t)gridDim.z * T * Hq;
+            float *dst = part + ((size_t)split * rows_total + rowg_[cb]) * kHD;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const int dim = db * 32 + g4 * 8 + half * 4;
+                    float4 val;
+                    val.x = o[db][cb][4 * g4 + 0] * inv;
+                    val.y = o[db][cb][4 * g4 + 1] * inv;
+                    val.z = o[db][cb][4 * g4 + 2] * inv;
+                    val.w = o[db][cb][4 * g4 + 3] * inv;
+                    *reinterpret_cast<float4 *>(dst + dim) = val;
+                }
+            if (half == 0)
+                part_lse[(size_t)split * rows_total + rowg_[cb]] =
+                    inv > 0.0f ? m_run[cb] + __builtin_amdgcn_logf(l_tot) : -INFINITY;
+        }
+    }
+}
+
+// Merge of the split-KV partials: out = sum_s 2^(lse_s - max) O_s / sum_s 2^(lse_s - max).
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict__ part,
+                                                         const float *__restrict__ part_lse,
+                                                         int splits, size_t rows_total,
+                                                         uint16_t *__restrict__ out)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;  // (row, 4-dim group)
+    const size_t row = idx / (kHD / 4);
+    const int dg = (int)(idx % (kHD / 4));
+    if (row >= rows_total) return;
+    float mx = -INFINITY;
+    for (int s = 0; s < splits; ++s) mx = fmaxf(mx, part_lse[(size_t)s * rows_total + row]);
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float wsum = 0.0f;
+    if (mx > -INFINITY) {
+        for (int s = 0; s < splits; ++s) {
+            const float w = __builtin_amdgcn_exp2f(part_lse[(size_t)s * rows_total + row] - mx);
+            const float4 v =
+                *reinterpret_cast<const float4 *>(part + ((size_t)s * rows_total + row) * kHD + dg * 4);
+            acc.x += w * v.x;
+            acc.y += w * v.y;
+            acc.z += w * v.z;
+            acc.w += w * v.w;
+            wsum += w;
+        }
+    }
+    const float inv = wsum > 0.0f ? 1.0f / wsum : 0.0f;
+    uint2 val;
+    val.x = f2bf_pair(acc.x * inv, acc.y * inv);
+    val.y = f2bf_pair(acc.z * inv, acc.w * inv);
+    *reinterpret_cast<uint2 *>(out + row * kHD + dg * 4) = val;
+}
+
+// ------------------------------------------------------------------------------------------
+// Generic path: one workgroup per (node, query head); keys in tiles of 256, online softmax,
+// fp32 arithmetic with accurate expf.  IO type TIO is float or bf16 bits (uint16_t).
+// ------------------------------------------------------------------------------------------
+constexpr int kGenThreads = 256;
+
+__device__ __forceinline__ float ld_elem(const float *p) { return *p; }
+__device__ __forceinline__ float ld_elem(const uint16_t *p)
+{
+    return __uint_as_float((uint32_t)(*p) << 16);
+}
+__device__ __forceinline__ void st_elem(float *p, float v) { *p = v; }
+__device__ __forceinline__ void st_elem(uint16_t *p, float v)
+{
+    const __bf16 b = (__bf16)v;
+    *p = __builtin_bit_cast(unsigned short, b);
+}
+
+template <typename TIO>
+__global__ __launch_bounds__(kGenThreads) void attn_generic_kernel(
+    const TIO *__restrict__ q, const TIO *__restrict__ k_cache, const TIO *__restrict__ v_cache,
+    const TIO *__restrict__ k_tree, const TIO *__restrict__ v_tree,
+    const uint64_t *__restrict__ mask, AttnArgs args, int T, int Hq, int Hkv, int D, float scale,
+    TIO *__restrict__ out)
+{
+    __shared__ float s_q[256];
+    __shared__ float s_p[kGenThreads];
+    __shared__ float s_red[kGenThreads / 64];
+    const int tid = threadIdx.x;
+    const int h = blockIdx.x, i = blockIdx.y, seq = blockIdx.z;
+    const int G = Hq / Hkv, hk = h / G;
+    const int W = (T + 63) >> 6;
+    const int L0 = args.kv_offset[seq];
+    const int L = args.kv_offset[seq + 1] - L0;
+    const size_t qrow = ((size_t)seq * T + i) * Hq + h;
+    const uint64_t *mrow = mask + ((size_t)seq * T + i) * W;
+    TIO *orow = out + qrow * D;
+    const bool real = (mrow[i >> 6] >> (i & 63)) & 1ull;
+    if (!real) {
+        if (tid < D) st_elem(orow + tid, 0.0f);
+        return;
+    }
+    if (tid < D) s_q[tid] = ld_elem(q + qrow * D + tid);
+    __syncthreads();
+    float m_run = -INFINITY, l_run = 0.0f, acc = 0.0f;
+    const int total = L + T;
+    for (int j0 = 0; j0 < total; j0 += kGenThreads) {
+        const int j = j0 + tid;
+        float s = -INFINITY;
+        const TIO *krow = nullptr;
+        if (j < L) {
+            krow = k_cache + ((size_t)(L0 + j) * Hkv + hk) * D;
+        } else if (j < total) {
+            const int jt = j - L;
+            if ((mrow[jt >> 6] >> (jt & 63)) & 1ull)
+                krow = k_tree + (((size_t)seq * T + jt) * Hkv + hk) * D;
+        }
+        if (krow) {
+            float dot = 0.0f;
+            for (int c = 0; c < D; ++c) dot = fmaf(s_q[c], ld_elem(krow + c), dot);
+            s = dot * scale;
+        }
+        // tile max
+        float tmax = s;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) tmax = fmaxf(tmax, __shfl_xor(tmax, d, 64));
+        if ((tid & 63) == 0) s_red[tid >> 6] = tmax;
+        __syncthreads();
+        tmax = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+        __syncthreads();
+        const float m_new = fmaxf(m_run, tmax);
+        if (m_new == -INFINITY) continue;  // nothing visible yet (uniform across the workgroup)
+        const float alpha = expf(m_run - m_new);
+        const float p = s == -INFINITY ? 0.0f : expf(s - m_new);
+        s_p[tid] = p;
+        float psum = p;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) psum += __shfl_xor(psum, d, 64);
+        if ((tid & 63) == 0) s_red[tid >> 6] = psum;
+        __syncthreads();
+        psum = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+        l_run = l_run * alpha + psum;
+        m_run = m_new;
+        if (tid < D) {
+            acc *= alpha;
+            const int cnt = min(kGenThreads, total - j0);
+            for (int t = 0; t < cnt; ++t) {
+                const float pt = s_p[t];
+                if (pt == 0.0f) continue;
+                const int jj = j0 + t;
+                const TIO *vrow = jj < L ? v_cache + ((size_t)(L0 + jj) * Hkv + hk) * D
+                                         : v_tree + (((size_t)seq * T + (jj - L)) * Hkv + hk) * D;
+                acc = fmaf(pt, ld_elem(vrow + tid), acc);
+            }
+        }
+        __syncthreads();
+    }
+    if (tid < D) st_elem(orow + tid, l_run > 0.0f ? acc / l_run : 0.0f);
+}
+
+}  // namespace ddt
+
+extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void *v_cache,
+                                  const void *k_tree, const void *v_tree,
+                                  const uint64_t *ancestor_mask, const int32_t *kv_offset, int batch,
+                                  int T, int Hq, int Hkv, int D, float softmax_scale, int dtype,
+                                  void *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    using namespace ddt;
+    if (!q || !k_tree || !v_tree || !ancestor_mask || !kv_offset || !out) return DDTREE_ERR_ARG;
+    if (batch < 1 || batch > DDTREE_MAX_BATCH || T < 1 || T > DDTREE_MAX_N + 1 || Hq < 1 || Hkv < 1 ||
+        Hq % Hkv != 0 || D < 8 || D > 256 || D % 8 != 0)
+        return DDTREE_ERR_ARG;
+    if (dtype != DDTREE_DTYPE_BF16 && dtype != DDTREE_DTYPE_FP32) return DDTREE_ERR_ARG;
+    if (!(softmax_scale > 0.0f) || !(softmax_scale < 1e30f)) return DDTREE_ERR_ARG;
+    AttnArgs args;
+    if (kv_offset[0] < 0) return DDTREE_ERR_ARG;
+    for (int s = 0; s <= batch; ++s) {
+        if (s > 0 && kv_offset[s] < kv_offset[s - 1]) return DDTREE_ERR_ARG;
+        args.kv_offset[s] = kv_offset[s];
+    }
+    const long long sum_L = (long long)kv_offset[batch] - kv_offset[0];
+    if (kv_offset[batch] > 0 && (!k_cache || !v_cache)) return DDTREE_ERR_ARG;
+    hipStream_t st = as_stream(stream);
+
+    if (dtype == DDTREE_DTYPE_BF16 && D == kHD) {
+        AttnPlan p = attn_plan(batch, T, Hq, Hkv, D, sum_L, dtype);
+        if (!ws_ok(workspace, workspace_bytes, p.bytes)) return DDTREE_ERR_WORKSPACE;
+        float *part = p.splits > 1 ? reinterpret_cast<float *>(static_cast<char *>(workspace) + p.part_off) : nullptr;
+        float *lse = p.splits > 1 ? reinterpret_cast<float *>(static_cast<char *>(workspace) + p.lse_off) : nullptr;
+        hipLaunchKernelGGL(attn_mfma_kernel, dim3(p.splits, p.mtiles * Hkv, batch), dim3(kAttnThreads), 0,
+                           st, static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(k_cache),
+                           static_cast<const uint16_t *>(v_cache), static_cast<const uint16_t *>(k_tree),
+                           static_cast<const uint16_t *>(v_tree), ancestor_mask, args, T, Hq, Hkv,
+                           softmax_scale * kLog2e, p.splits, static_cast<uint16_t *>(out), part, lse);
+        if (p.splits > 1) {
+            const size_t rows = (size_t)batch * T * Hq;
+            const size_t threads = rows * (kHD / 4);
+            hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                               part, lse, p.splits, rows, static_cast<uint16_t *>(out));
+        }
+        return launch_status();
+    }
+    if (dtype == DDTREE_DTYPE_FP32)
+        hipLaunchKernelGGL(attn_generic_kernel<float>, dim3(Hq, T, batch), dim3(kGenThreads), 0, st,
+                           static_cast<const float *>(q), static_cast<const float *>(k_cache),
+                           static_cast<const float *>(v_cache), static_cast<const float *>(k_tree),
+                           static_cast<const float *>(v_tree), ancestor_mask, args, T, Hq, Hkv, D,
+                           softmax_scale, static_cast<float *>(out));
+    else
+        hipLaunchKernelGGL(attn_generic_kernel<uint16_t>, dim3(Hq, T, batch), dim3(kGenThreads), 0, st,
+                           static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(k_cache),
+                           static_cast<const uint16_t *>(v_cache), static_cast<const uint16_t *>(k_tree),
+                           static_cast<const uint16_t *>(v_tree), ancestor_mask, args, T, Hq, Hkv, D,
+                           softmax_scale, static_cast<uint16_t *>(out));
+    return launch_status();
+}
+
+// ------------------------------------------------------------------------------------------
+// Library-level entry points that belong to no single stage.
+// ------------------------------------------------------------------------------------------
+extern "C" int ddtree_version(void) { return 100; }
+
+extern "C" const char *ddtree_error_string(int code)
+{
+    switch (code) {
+    case DDTREE_OK: return "ok";
+    case DDTREE_ERR_ARG: return "bad argument (null pointer, shape, size or dtype)";
+    case DDTREE_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case DDTREE_ERR_HIP: return "HIP runtime error at launch";
+    default: return "unknown error code";
+    }
+}
+
+extern "C" size_t ddtree_workspace_bytes(int batch, int B, int V, int N, int Hq, int Hkv, int D,
+                                         int max_sum_L)
+{
+    using namespace ddt;
+    (void)max_sum_L;
+    if (batch < 1 || batch > DDTREE_MAX_BATCH || B < 1 || B > DDTREE_MAX_B || V < 1 || N < 1 ||
+        N > DDTREE_MAX_N || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || D < 8 || D > 256 || D % 8 != 0)
+        return 0;
+    const int K = N < V ? N : V;
+    const int T = N + 1;
+    TopkPlan tp = topk_plan(batch, B, V, K);
+    if (!tp.ok) return 0;
+    size_t need = tp.bytes;
+    const size_t a = attn_ws_upper(batch, T, Hq, Hkv, D);
+    if (a > need) need = a;
+    const size_t c = accept_plan(batch, T, V).bytes;
+    if (c > need) need = c;
+    return need < 256 ? 256 : need;
+}

@@ -1,0 +1,307 @@
+// Best-first draft-tree construction (paper Algorithm 1) and the tensors compiled from the
+// tree for the verifier (Section 4.4: token ids, depth as position id, ancestor-only mask).
+//
+// One workgroup per sequence; the pops are inherently serial (pop i+1 depends on the pushes of
+// pop i), so a single wavefront runs them and the other three wait at a barrier, then all
+// 256 threads write the outputs and the ancestor bitmask.
+//
+// Frontier layout.  Algorithm 1's heap holds, at any time, exactly one candidate per node that
+// is already in the tree (root included): that node's next unused child rank.  Popping the
+// candidate of node p with rank c creates node n = (p, c); "push next sibling" is c -> c+1 in
+// p's entry and "push first child" is a fresh entry for n.  So the frontier is an array indexed
+// by node id, with no free list.  Entry e lives in lane e % 64, register slot e / 64, and stays
+// in registers for the whole run; a pop is a lane-local max followed by a DPP wave max.
+// The log-probabilities a popped entry needs next (ranks c+1 and c+2 of its row) are prefetched
+// into the entry, so no LDS access sits on the pop-to-pop dependency chain.
+//
+// Ties (equal fp32 scores) are resolved as the boundary specifies: the lexicographically
+// smaller rank tuple first, a prefix before its extensions.  They are rare and take a slow
+// path that walks parent links in LDS.
+#include "common.hpp"
+
+namespace ddt {
+
+constexpr int kBuildThreads = 256;
+
+__device__ __forceinline__ uint32_t pack_node(int parent, int rank, int depth)
+{
+    return (uint32_t)parent | ((uint32_t)rank << 11) | ((uint32_t)depth << 21);
+}
+__device__ __forceinline__ int node_parent(uint32_t x) { return (int)(x & 0x7FFu); }
+__device__ __forceinline__ int node_rank(uint32_t x) { return (int)((x >> 11) & 0x3FFu); }
+__device__ __forceinline__ int node_depth(uint32_t x) { return (int)(x >> 21); }
+
+// Rank-tuple order of two frontier candidates (parent node, child rank); true if a goes first.
+// s_node[j] describes tree node j (root: parent field unused, depth 0).
+__device__ bool tuple_before(const uint32_t *s_node, int pa, int ra, int pb, int rb)
+{
+    int da = node_depth(s_node[pa]) + 1, db = node_depth(s_node[pb]) + 1;
+    const int da0 = da, db0 = db;
+    while (da > db) {
+        ra = node_rank(s_node[pa]);
+        pa = node_parent(s_node[pa]);
+        --da;
+    }
+    while (db > da) {
+        rb = node_rank(s_node[pb]);
+        pb = node_parent(s_node[pb]);
+        --db;
+    }
+    while (pa != pb) {
+        ra = node_rank(s_node[pa]);
+        pa = node_parent(s_node[pa]);
+        rb = node_rank(s_node[pb]);
+        pb = node_parent(s_node[pb]);
+    }
+    if (ra != rb) return ra < rb;
+    return da0 < db0;
+}
+
+template <int NSLOT>
+__global__ __launch_bounds__(kBuildThreads) void build_kernel(
+    const int32_t *__restrict__ topk_tok, const float *__restrict__ topk_lp, int B, int K, int N,
+    const int32_t *__restrict__ root_token, int32_t *__restrict__ tokens,
+    int32_t *__restrict__ parent, int32_t *__restrict__ depth, int32_t *__restrict__ rank,
+    float *__restrict__ node_score, uint64_t *__restrict__ ancestor_mask,
+    int32_t *__restrict__ n_nodes)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int Kp = K + 3;
+    const int T = N + 1;
+    float *s_lp = reinterpret_cast<float *>(smem);                     // [B][Kp], -inf padded
+    uint32_t *s_node = reinterpret_cast<uint32_t *>(s_lp + B * Kp);     // [T]
+    float *s_score = reinterpret_cast<float *>(s_node + T);             // [T]
+    uint16_t *s_chain = reinterpret_cast<uint16_t *>(s_score + T);      // [B+1][kBuildThreads]
+    __shared__ int s_built;
+
+    const int tid = threadIdx.x;
+    const int seq = blockIdx.x;
+    const float *lp = topk_lp + (size_t)seq * B * K;
+    const int32_t *tk = topk_tok + (size_t)seq * B * K;
+
+    for (int i = tid; i < B * Kp; i += kBuildThreads) {
+        int d = i / Kp, k = i - d * Kp;
+        s_lp[i] = k < K ? lp[d * K + k] : -INFINITY;
+    }
+    if (tid == 0) {
+        s_node[0] = pack_node(0, 0, 0);
+        s_score[0] = 0.0f;
+    }
+    __syncthreads();
+
+    if (tid < kWave) {
+        const int lane = tid;
+        // lane d holds the first three log-probabilities of row d (depth d+1), -inf past the
+        // last row: what a fresh entry for a node at depth d needs
+        const float lp0 = lane < B ? s_lp[lane * Kp + 0] : -INFINITY;
+        const float lp1 = lane < B ? s_lp[lane * Kp + 1] : -INFINITY;
+        const float lp2 = lane < B ? s_lp[lane * Kp + 2] : -INFINITY;
+        float cand[NSLOT], nsc[NSLOT], nlp1[NSLOT], nlp2[NSLOT];
+        int meta[NSLOT];  // (current child rank << 8) | row of the children
+#pragma unroll
+        for (int s = 0; s < NSLOT; ++s) {
+            cand[s] = -INFINITY;
+            nsc[s] = 0.0f;
+            nlp1[s] = -INFINITY;
+            nlp2[s] = -INFINITY;
+            meta[s] = 0;
+        }
+        if (lane == 0) {  // the root's entry: candidate = rank 0 of row 0
+            cand[0] = lp0;
+            nlp1[0] = lp1;
+            nlp2[0] = lp2;
+        }
+        int n = 0;
+        while (n < N) {
+            float lb = cand[0];
+#pragma unroll
+            for (int s = 1; s < NSLOT; ++s) lb = fmaxf(lb, cand[s]);
+            const float wm = wave_max_f32(lb);
+            if (wm == -INFINITY) break;  // frontier empty: fewer than N prefixes exist
+            // which entries hold the maximum (one compare per slot, masks are wave-uniform)
+            unsigned long long eq[NSLOT];
+            int matches = 0;
+#pragma unroll
+            for (int s = 0; s < NSLOT; ++s) {
+                eq[s] = __ballot(cand[s] == wm);
+                matches += __popcll(eq[s]);
+            }
+            int ws = 0, wl = 0;
+            if (matches == 1) {
+#pragma unroll
+                for (int s = 0; s < NSLOT; ++s)
+                    if (eq[s]) {
+                        ws = s;
+                        wl = __ffsll((long long)eq[s]) - 1;
+                    }
+            } else {
+                // slow path: several candidates share the best score
+                int bp = -1, bc = 0;
+#pragma unroll
+                for (int s = 0; s < NSLOT; ++s) {
+                    unsigned long long mm = eq[s];
+                    while (mm) {
+                        const int l = __ffsll((long long)mm) - 1;
+                        mm &= mm - 1;
+                        const int p = s * 64 + l;
+                        const int c = __builtin_amdgcn_readlane(meta[s], l) >> 8;
+                        if (bp < 0 || tuple_before(s_node, p, c, bp, bc)) {
+                            bp = p;
+                            bc = c;
+                            ws = s;
+                            wl = l;
+                        }
+                    }
+                }
+            }
+            // the popped entry, read from its owner lane
+            float NS = 0.0f, NL = 0.0f;
+            int M = 0;
+#pragma unroll
+            for (int s = 0; s < NSLOT; ++s)
+                if (ws == s) {
+                    NS = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(nsc[s]), wl));
+                    NL = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(nlp1[s]), wl));
+                    M = __builtin_amdgcn_readlane(meta[s], wl);
+                }
+            const int p = ws * 64 + wl;
+            const int c = M >> 8, row = M & 0xFF;
+            const int d = row + 1;  // depth of the new node
+            ++n;
+            if (lane == 0) {
+                s_node[n] = pack_node(p, c, d);
+                s_score[n] = wm;
+            }
+            // next sibling: score(parent node) + lp[row][c+1]   (-inf once c+1 == K)
+            const float sib = NS + NL;
+            // first child: score(new node) + lp[d][0]            (-inf once d == B)
+            const float ch = wm + __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lp0), d));
+            const float c1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lp1), d));
+            const float c2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lp2), d));
+            const int sn = n >> 6, ln = n & 63;
+#pragma unroll
+            for (int s = 0; s < NSLOT; ++s) {
+                if (ws == s && lane == wl) {
+                    cand[s] = sib;
+                    nlp1[s] = nlp2[s];
+                    nlp2[s] = s_lp[row * Kp + min(c + 3, Kp - 1)];
+                    meta[s] = M + 256;
+                }
+                if (sn == s && lane == ln) {
+                    cand[s] = ch;
+                    nsc[s] = wm;
+                    nlp1[s] = c1;
+                    nlp2[s] = c2;
+                    meta[s] = d;  // rank 0, children read row d
+                }
+            }
+        }
+        if (lane == 0) s_built = n;
+    }
+    __syncthreads();
+    const int built = s_built;
+    const int W = (T + 63) / 64;
+    if (tid == 0) n_nodes[seq] = built;
+
+    for (int i0 = 0; i0 < T; i0 += kBuildThreads) {
+        const int i = i0 + tid;
+        if (i >= T) break;
+        const size_t o = (size_t)seq * T + i;
+        uint64_t *mrow = ancestor_mask + o * W;
+        if (i > built) {
+            tokens[o] = -1;
+            parent[o] = -1;
+            depth[o] = -1;
+            if (rank) rank[o] = -1;
+            if (node_score) node_score[o] = 0.0f;
+            for (int w = 0; w < W; ++w) mrow[w] = 0ull;
+            continue;
+        }
+        const uint32_t nd = s_node[i];
+        const int d = i == 0 ? 0 : node_depth(nd);
+        if (i == 0) {
+            tokens[o] = root_token[seq];
+            parent[o] = -1;
+            depth[o] = 0;
+            if (rank) rank[o] = -1;
+            if (node_score) node_score[o] = 0.0f;
+        } else {
+            tokens[o] = tk[(d - 1) * K + node_rank(nd)];
+            parent[o] = node_parent(nd);
+            depth[o] = d;
+            if (rank) rank[o] = node_rank(nd);
+            if (node_score) node_score[o] = s_score[i];
+        }
+        // ancestors of i (itself first, the root last): d + 1 ids, kept in this thread's
+        // column of s_chain, then folded into the W mask words
+        int j = i;
+        for (int t = 0; t <= d; ++t) {
+            s_chain[t * kBuildThreads + tid] = (uint16_t)j;
+            j = node_parent(s_node[j]);
+        }
+        for (int w = 0; w < W; ++w) {
+            uint64_t word = 0ull;
+            for (int t = 0; t <= d; ++t) {
+                const int a = s_chain[t * kBuildThreads + tid];
+                if ((a >> 6) == w) word |= 1ull << (a & 63);
+            }
+            mrow[w] = word;
+        }
+    }
+}
+
+static size_t build_lds_bytes(int B, int K, int N)
+{
+    return (size_t)B * (K + 3) * 4 + (size_t)(N + 1) * 8 + (size_t)(B + 1) * kBuildThreads * 2;
+}
+
+template <int NSLOT>
+static int launch_build(const int32_t *topk_tok, const float *topk_lp, int batch, int B, int K, int N,
+                        const int32_t *root_token, int32_t *tokens, int32_t *parent, int32_t *depth,
+                        int32_t *rank, float *node_score, uint64_t *ancestor_mask, int32_t *n_nodes,
+                        hipStream_t st)
+{
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(build_kernel<NSLOT>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024) != hipSuccess)
+            return DDTREE_ERR_HIP;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(build_kernel<NSLOT>, dim3(batch), dim3(kBuildThreads), build_lds_bytes(B, K, N),
+                       st, topk_tok, topk_lp, B, K, N, root_token, tokens, parent, depth, rank,
+                       node_score, ancestor_mask, n_nodes);
+    return launch_status();
+}
+
+}  // namespace ddt
+
+extern "C" int ddtree_build(const int32_t *topk_tok, const float *topk_lp, int batch, int B, int K,
+                            int N, const int32_t *root_token, int32_t *tokens, int32_t *parent,
+                            int32_t *depth, int32_t *rank, float *node_score,
+                            uint64_t *ancestor_mask, int32_t *n_nodes, void *workspace,
+                            size_t workspace_bytes, void *stream)
+{
+    using namespace ddt;
+    (void)workspace;
+    (void)workspace_bytes;
+    if (!topk_tok || !topk_lp || !root_token || !tokens || !parent || !depth || !ancestor_mask ||
+        !n_nodes)
+        return DDTREE_ERR_ARG;
+    if (batch < 1 || batch > DDTREE_MAX_BATCH || B < 1 || B > DDTREE_MAX_B || K < 1 ||
+        K > DDTREE_MAX_N || N < 1 || N > DDTREE_MAX_N)
+        return DDTREE_ERR_ARG;
+    if (build_lds_bytes(B, K, N) > 150 * 1024) return DDTREE_ERR_ARG;
+    hipStream_t st = as_stream(stream);
+    const int slots = (N + 1 + 63) / 64;
+#define DDT_BUILD(S)                                                                              \
+    return launch_build<S>(topk_tok, topk_lp, batch, B, K, N, root_token, tokens, parent, depth, \
+                           rank, node_score, ancestor_mask, n_nodes, st)
+    if (slots <= 1) DDT_BUILD(1);
+    if (slots <= 2) DDT_BUILD(2);
+    if (slots <= 3) DDT_BUILD(3);
+    if (slots <= 5) DDT_BUILD(5);
+    if (slots <= 9) DDT_BUILD(9);
+    DDT_BUILD(17);
+#undef DDT_BUILD
+}

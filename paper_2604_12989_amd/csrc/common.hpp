@@ -1,0 +1,92 @@
+// Shared device/host helpers for the gfx950 kernels of the DDTree draft-tree step.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "ddtree.h"
+
+namespace ddt {
+
+constexpr int kWave = 64;
+
+inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+inline int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? DDTREE_OK : DDTREE_ERR_HIP;
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+inline bool ws_ok(const void *ws, size_t have, size_t need)
+{
+    return need == 0 || (ws != nullptr && (reinterpret_cast<uintptr_t>(ws) & 255u) == 0 && have >= need);
+}
+
+// ---- layout of the top-K scratch, shared by the host sizing code and the kernels ----
+struct TopkPlan {
+    int chunks;     // chunks per logits row
+    int chunk_len;  // elements per chunk (multiple of 4), last chunk may be shorter
+    int kc;         // candidates kept per chunk = min(K, chunk_len)
+    size_t cand_off, stat_off, bytes;
+    bool ok;
+};
+constexpr int kTopkChunkMax = 12288;      // keys held in LDS by one chunk workgroup
+constexpr int kTopkMergeMaxCand = 14336;  // u64 candidates held in LDS by the merge workgroup
+TopkPlan topk_plan(int batch, int B, int V, int K);
+
+// ---- layout of the attention scratch ----
+struct AttnPlan {
+    int splits;       // key-range splits per (sequence, kv head, row tile)
+    int mtiles;       // row tiles per (sequence, kv head)
+    size_t part_off, lse_off, bytes;
+};
+AttnPlan attn_plan(int batch, int T, int Hq, int Hkv, int D, long long sum_L, int dtype);
+
+// ---- layout of the accept scratch ----
+struct AcceptPlan {
+    int splits;  // segments per logits row
+    int seg_len; // elements per segment (multiple of 4)
+    size_t part_off, bytes;
+};
+AcceptPlan accept_plan(int batch, int T, int V);
+
+#if defined(__HIPCC__)
+// Order-preserving map from finite floats to unsigned integers (-0 is folded onto +0).
+__device__ __forceinline__ uint32_t float_key(float x)
+{
+    uint32_t b = __float_as_uint(x);
+    if (b == 0x80000000u) b = 0u;
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float key_float(uint32_t k)
+{
+    uint32_t b = (k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k;
+    return __uint_as_float(b);
+}
+
+// Wave-wide max of a float over all 64 lanes via DPP, returned uniformly.
+// All 64 lanes must be active.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp_f(float old, float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL,
+                                                      ROW_MASK, 0xF, false));
+}
+__device__ __forceinline__ float wave_max_f32(float v)
+{
+    v = fmaxf(v, dpp_f<0xB1>(v, v));   // quad_perm [1,0,3,2]
+    v = fmaxf(v, dpp_f<0x4E>(v, v));   // quad_perm [2,3,0,1]
+    v = fmaxf(v, dpp_f<0x141>(v, v));  // row_half_mirror
+    v = fmaxf(v, dpp_f<0x140>(v, v));  // row_mirror: every lane of a 16-lane row holds the row max
+    v = fmaxf(v, dpp_f<0x142, 0xA>(v, v));  // row_bcast15 into rows 1 and 3
+    v = fmaxf(v, dpp_f<0x143, 0xC>(v, v));  // row_bcast31 into rows 2 and 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+__device__ __forceinline__ int lane_id() { return __lane_id(); }
+#endif
+
+}  // namespace ddt

@@ -1,0 +1,389 @@
+"""GPU parity: every stage of the HIP library against the CPU oracle, element by element, on
+the same seeded inputs.  Bit-exact for tokens / tree / mask / walk; log-probabilities within
+2 ulp (fp64 log-sum-exp on both sides, different summation order); attention within 1e-2
+(bf16) or 1e-5 (fp32) max-abs on unit-variance inputs."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+import ddtree_inputs as di  # noqa: E402
+import oracle  # noqa: E402
+
+if torch.cuda.is_available():
+    from tests import gpu_util as gu  # noqa: E402
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests selected but no GPU is visible")
+
+
+def ulp_diff(a, b):
+    ia = a.view(np.int32).astype(np.int64)
+    ib = b.view(np.int32).astype(np.int64)
+    ia = np.where(ia < 0, -(ia & 0x7FFFFFFF), ia)
+    ib = np.where(ib < 0, -(ib & 0x7FFFFFFF), ib)
+    return np.abs(ia - ib)
+
+
+# ------------------------------------------------------------------------------- top-K
+TOPK_CASES = [
+    ("tiny_config1", dict(B=8, V=1024, K=16, seed=di.config_seed(1))),
+    ("odd_V_unaligned_rows", dict(B=5, V=50001, K=64, seed=7)),
+    ("K_equals_V", dict(B=3, V=300, K=300, seed=8)),
+    ("one_chunk_short_tail", dict(B=2, V=12290, K=100, seed=9)),
+    ("wide_K", dict(B=2, V=40000, K=1024, seed=10)),
+]
+
+
+@pytest.mark.parametrize("name,c", TOPK_CASES, ids=[n for n, _ in TOPK_CASES])
+def test_topk_matches_oracle(name, c):
+    x = di.draft_logits(c["seed"], c["B"], c["V"])
+    tok_o, lp_o = oracle.topk(x, c["K"])
+    tok_g, lp_g = gu.gpu_topk(x, c["K"])
+    assert np.array_equal(tok_g[0], tok_o)
+    assert ulp_diff(lp_g[0], lp_o).max() <= 2
+    print(f"{name}: lp bit-exact rate {np.mean(lp_g[0] == lp_o):.6f}")
+
+
+def test_topk_duplicates_and_flat_rows():
+    rng = np.random.default_rng(3)
+    V = 30000
+    x = np.round(rng.standard_normal((6, V)) * 4).astype(np.float32) / 4  # heavy duplication
+    x[1] = 2.5                                                          # one value everywhere
+    x[2, :] = -1.0
+    x[2, [29999, 17, 4000]] = 0.0                                       # ties at the top
+    x[3] = np.where(np.arange(V) % 2 == 0, 1.0, -1.0)                   # half the row ties at K
+    x[4] = -np.arange(V, dtype=np.float32)                              # strictly decreasing
+    x[5] = np.arange(V, dtype=np.float32) * 1e-3                        # strictly increasing
+    for K in (1, 7, 256):
+        tok_o, lp_o = oracle.topk(x, K)
+        tok_g, lp_g = gu.gpu_topk(x, K)
+        assert np.array_equal(tok_g[0], tok_o), K
+        assert ulp_diff(lp_g[0], lp_o).max() <= 2
+
+
+def test_topk_batched():
+    xs = np.stack([di.draft_logits(11, 4, 20000, batch_index=b) for b in range(3)])
+    tok_g, lp_g = gu.gpu_topk(xs, 32)
+    for b in range(3):
+        tok_o, lp_o = oracle.topk(xs[b], 32)
+        assert np.array_equal(tok_g[b], tok_o)
+        assert ulp_diff(lp_g[b], lp_o).max() <= 2
+
+
+# ------------------------------------------------------------------------------- build
+def _peaked_logits(seed, B, V, spike):
+    x = di.draft_logits(seed, B, V)
+    rng = np.random.default_rng(seed)
+    x[np.arange(B), rng.integers(0, V, B)] += spike
+    return x
+
+
+def _check_build(tok, lp, N, root=5):
+    o = oracle.build_tree(tok, lp, N, root)
+    g = gu.gpu_build(tok, lp, N, root)
+    assert int(g["n_nodes"][0]) == o["n_nodes"]
+    for key, okey in (("tokens", "tokens"), ("parent", "parent"), ("depth", "depth"),
+                      ("rank", "rank")):
+        assert np.array_equal(g[key][0], o[okey]), key
+    assert np.array_equal(g["node_score"][0].view(np.uint32), o["score"].view(np.uint32))
+    m = oracle.ancestor_mask(o["parent"], o["n_nodes"], T=N + 1)
+    assert np.array_equal(g["ancestor_mask"][0], m)
+    return o
+
+
+@pytest.mark.parametrize("N", [1, 2, 16, 63, 64, 65, 128, 256, 512, 1024])
+def test_build_matches_oracle_on_workload_logits(N):
+    x = di.draft_logits(di.config_seed(2), 16, 20000)
+    K = min(N, 20000)
+    tok, lp = oracle.topk(x, K)
+    _check_build(tok, lp, N)
+
+
+@pytest.mark.parametrize("spike,N", [(6.0, 64), (9.0, 256), (12.0, 256), (14.0, 512), (20.0, 100)])
+def test_build_deep_trees(spike, N):
+    x = _peaked_logits(21, 16, 8192, spike)
+    tok, lp = oracle.topk(x, min(N, 8192))
+    o = _check_build(tok, lp, N)
+    print(f"spike {spike}: max depth {o['depth'].max()}")
+
+
+def test_build_exact_ties_and_dry_heap():
+    rng = np.random.default_rng(5)
+    for trial in range(20):
+        B, K = int(rng.integers(1, 6)), int(rng.integers(1, 7))
+        lp = (-np.sort(rng.integers(0, 6, size=(B, K)), axis=1) / 4.0).astype(np.float32)
+        tok = rng.permutation(B * K).astype(np.int32).reshape(B, K)
+        total = sum(K ** d for d in range(1, B + 1))
+        for N in {1, min(total, 40), min(total + 3, 70)}:
+            _check_build(tok, lp, N)
+
+
+def test_build_batched():
+    toks, lps = [], []
+    for b in range(4):
+        x = _peaked_logits(30 + b, 8, 4096, 5.0 + 3 * b)
+        t, l = oracle.topk(x, 96)
+        toks.append(t); lps.append(l)
+    g = gu.gpu_build(np.stack(toks), np.stack(lps), 96, [1, 2, 3, 4])
+    for b in range(4):
+        o = oracle.build_tree(toks[b], lps[b], 96, b + 1)
+        assert np.array_equal(g["tokens"][b], o["tokens"])
+        assert np.array_equal(g["parent"][b], o["parent"])
+        assert np.array_equal(g["ancestor_mask"][b],
+                              oracle.ancestor_mask(o["parent"], o["n_nodes"], T=97))
+
+
+# ------------------------------------------------------------------------------- attention
+def _random_tree(rng, T, n_nodes=None, chainy=0.5):
+    n = T - 1 if n_nodes is None else n_nodes
+    par = np.full(T, -1, np.int32)
+    for i in range(1, n + 1):
+        par[i] = i - 1 if rng.random() < chainy else rng.integers(0, i)
+    return par, n
+
+
+def _attn_case(seed, T, L, Hq, Hkv, D, dtype, n_nodes=None):
+    rng = np.random.default_rng(seed)
+    par, n = _random_tree(rng, T, n_nodes)
+    mask = oracle.ancestor_mask(par, n, T=T)
+    q, kc, vc, kt, vt = di.attn_tensors(seed, T, L, Hq, Hkv, D, dtype)
+    return q, kc, vc, kt, vt, mask
+
+
+ATTN_BF16 = [(17, 128, 4, 1, 1), (65, 100, 8, 2, 2), (257, 333, 8, 2, 3), (129, 1000, 16, 2, 4),
+             (257, 0, 4, 4, 5), (64, 64, 32, 8, 6), (513, 2048, 8, 2, 7), (40, 4100, 32, 8, 8)]
+
+
+@pytest.mark.parametrize("T,L,Hq,Hkv,seed", ATTN_BF16)
+def test_attn_bf16_mfma_matches_oracle(T, L, Hq, Hkv, seed):
+    D = 128
+    q, kc, vc, kt, vt, mask = _attn_case(seed, T, L, Hq, Hkv, D, "bf16")
+    ref = oracle.verify_attn(q, kc, vc, kt, vt, mask)
+    got = gu.gpu_attn(q, kc, vc, kt, vt, mask[None], [0, L], 1, T, "bf16")[0]
+    err = np.abs(got - ref).max()
+    print(f"T={T} L={L}: max abs err {err:.2e}, rms(ref) {np.sqrt((ref ** 2).mean()):.3f}")
+    assert err < 1e-2
+
+
+def test_attn_fp32_config1():
+    c = di.CONFIGS[1]
+    T = c["N"] + 1
+    q, kc, vc, kt, vt, mask = _attn_case(di.config_seed(1), T, c["L"], c["Hq"], c["Hkv"], c["D"],
+                                         "fp32")
+    ref = oracle.verify_attn(q, kc, vc, kt, vt, mask)
+    got = gu.gpu_attn(q, kc, vc, kt, vt, mask[None], [0, c["L"]], 1, T, "fp32")[0]
+    assert np.abs(got - ref).max() < 1e-5
+
+
+@pytest.mark.parametrize("dtype,D,tol", [("fp32", 64, 1e-5), ("fp32", 128, 1e-5), ("bf16", 64, 1e-2),
+                                         ("fp32", 40, 1e-5)])
+def test_attn_generic_path(dtype, D, tol):
+    T, L, Hq, Hkv = 70, 300, 6, 3
+    q, kc, vc, kt, vt, mask = _attn_case(12, T, L, Hq, Hkv, D, dtype)
+    ref = oracle.verify_attn(q, kc, vc, kt, vt, mask)
+    got = gu.gpu_attn(q, kc, vc, kt, vt, mask[None], [0, L], 1, T, dtype)[0]
+    assert np.abs(got - ref).max() < tol
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_attn_mask_leak_adversarial(dtype):
+    """A wrongly visible non-ancestor (or a wrongly hidden ancestor) must move the output by
+    O(10..100): keys aligned with the query carry large values."""
+    T, L, Hq, Hkv, D = 200, 70, 4, 2, 128
+    rng = np.random.default_rng(99)
+    par, n = _random_tree(rng, T, chainy=0.3)
+    mask = oracle.ancestor_mask(par, n, T=T)
+    q, kc, vc, kt, vt = di.attn_tensors(99, T, L, Hq, Hkv, D, dtype)
+    rnd = di.round_to_bf16 if dtype == "bf16" else (lambda a: a.astype(np.float32))
+    # every tree key is strongly aligned with the queries of head 0 of its KV group for a
+    # different node: the key of node j points along q[(j * 7 + 3) % T]
+    for j in range(T):
+        tgt = (j * 7 + 3) % T
+        for hk in range(Hkv):
+            kt[j, hk] = rnd(3.0 * q[tgt, hk * (Hq // Hkv)])
+    vt[:] = rnd((100.0 * np.sign(vt) + vt).astype(np.float32))
+    ref = oracle.verify_attn(q, kc, vc, kt, vt, mask)
+    got = gu.gpu_attn(q, kc, vc, kt, vt, mask[None], [0, L], 1, T, dtype)[0]
+    # values are +-100: bf16 probabilities (8 mantissa bits) leave ~0.5 absolute; a leak is O(100)
+    atol = 1.0 if dtype == "bf16" else 1e-2
+    assert np.abs(got - ref).max() <= atol
+    # the construction is sensitive: one wrongly visible key in the oracle moves the row by O(100)
+    for j in range(1, T):
+        i = (j * 7 + 3) % T
+        if i != j and not (int(mask[i, j >> 6]) >> (j & 63)) & 1:
+            break
+    mask2 = mask.copy()
+    mask2[i, j >> 6] |= np.uint64(1) << np.uint64(j & 63)
+    moved = oracle.verify_attn(q, kc, vc, kt, vt, mask2, pairs=[[i, 0]])
+    assert np.abs(moved[0] - ref[i, 0]).max() > 50.0
+
+
+def test_attn_chain_tree_and_no_cache():
+    T, Hq, Hkv, D = 130, 4, 2, 128
+    q, kc, vc, kt, vt = di.attn_tensors(5, T, 0, Hq, Hkv, D, "bf16")
+    mask = oracle.ancestor_mask(np.arange(-1, T - 1, dtype=np.int32), T - 1)
+    ref = oracle.verify_attn(q, kc, vc, kt, vt, mask)
+    got = gu.gpu_attn(q, kc, vc, kt, vt, mask[None], [0, 0], 1, T, "bf16")[0]
+    assert np.abs(got - ref).max() < 1e-2
+    # the root sees only itself: its output is its own value row, exactly
+    for h in range(Hq):
+        assert np.array_equal(got[0, h], vt[0, h // 2])
+
+
+def test_attn_padding_rows_are_zero():
+    T, L, Hq, Hkv, D = 80, 50, 4, 2, 128
+    q, kc, vc, kt, vt, mask = _attn_case(6, T, L, Hq, Hkv, D, "bf16", n_nodes=40)
+    ref = oracle.verify_attn(q, kc, vc, kt, vt, mask)
+    got = gu.gpu_attn(q, kc, vc, kt, vt, mask[None], [0, L], 1, T, "bf16")[0]
+    assert not got[41:].any() and not ref[41:].any()
+    assert np.abs(got - ref).max() < 1e-2
+
+
+def test_attn_batched_ragged():
+    batch, T, Hq, Hkv, D = 3, 33, 16, 2, 128
+    Ls = [130, 0, 517]
+    off = np.concatenate([[0], np.cumsum(Ls)]).astype(np.int32)
+    qs, kcs, vcs, kts, vts, ms, refs = [], [], [], [], [], [], []
+    for b in range(batch):
+        q, kc, vc, kt, vt, mask = _attn_case(40 + b, T, Ls[b], Hq, Hkv, D, "bf16")
+        refs.append(oracle.verify_attn(q, kc, vc, kt, vt, mask))
+        qs.append(q); kcs.append(kc); vcs.append(vc); kts.append(kt); vts.append(vt); ms.append(mask)
+    got = gu.gpu_attn(np.concatenate(qs), np.concatenate(kcs), np.concatenate(vcs),
+                      np.concatenate(kts), np.concatenate(vts), np.stack(ms), off, batch, T, "bf16")
+    for b in range(batch):
+        assert np.abs(got[b] - refs[b]).max() < 1e-2
+
+
+# ------------------------------------------------------------------------------- accept
+def _tree_for_accept(seed, B, V, N, spike):
+    x = _peaked_logits(seed, B, V, spike)
+    tok, lp = oracle.topk(x, min(N, V))
+    return tok, oracle.build_tree(tok, lp, N, root_token=3)
+
+
+@pytest.mark.parametrize("V,N,spike,p", [(1024, 16, 6.0, 0.8), (151936, 64, 12.0, 0.9),
+                                         (50001, 200, 10.0, 1.0), (30000, 40, 8.0, 0.0)])
+def test_accept_matches_oracle(V, N, spike, p):
+    B = 8
+    tok, tree = _tree_for_accept(50, B, V, N, spike)
+    plant = di.planted_tokens(51, tree["depth"], tok[:, 0], B, p=p)
+    x = di.target_logits(51, N + 1, V, plant)
+    o = oracle.accept(x, tree["tokens"], tree["parent"], tree["n_nodes"], B)
+    g = gu.gpu_accept(x, tree["tokens"], tree["parent"], tree["depth"], [tree["n_nodes"]], B)
+    assert np.array_equal(g["posterior"][0], o["posterior"])
+    assert int(g["n_accepted"][0]) == o["n_accepted"]
+    assert np.array_equal(g["path"][0], o["path"])
+    assert int(g["bonus_token"][0]) == o["bonus"]
+    print(f"V={V} N={N}: accepted {o['n_accepted']}")
+
+
+def test_accept_branches_with_rank_above_zero_and_ties():
+    B, V, N = 8, 5000, 60
+    tok, tree = _tree_for_accept(60, B, V, N, 5.0)
+    rng = np.random.default_rng(61)
+    # plant, at every node, the token of one of its children (any rank) when it has children
+    plant = np.full(N + 1, -1, np.int64)
+    for i in range(tree["n_nodes"] + 1):
+        kids = [c for c in range(1, tree["n_nodes"] + 1) if tree["parent"][c] == i]
+        if kids:
+            plant[i] = tree["tokens"][rng.choice(kids)]
+    x = di.target_logits(61, N + 1, V, plant)
+    x[5, :] = 0.0
+    x[5, [4000, 77, 900]] = 3.0                       # tie: lowest id wins
+    o = oracle.accept(x, tree["tokens"], tree["parent"], tree["n_nodes"], B)
+    g = gu.gpu_accept(x, tree["tokens"], tree["parent"], tree["depth"], [tree["n_nodes"]], B)
+    assert o["posterior"][5] == 77
+    assert np.array_equal(g["posterior"][0], o["posterior"])
+    assert np.array_equal(g["path"][0], o["path"]) and int(g["bonus_token"][0]) == o["bonus"]
+    assert o["n_accepted"] >= 2
+
+
+def test_accept_batched_with_padding_rows():
+    B, V, N = 4, 3000, 30
+    toks, trees, xs = [], [], []
+    rng = np.random.default_rng(7)
+    for b in range(3):
+        K = 2 if b == 1 else 30            # b == 1: only 2+4+8+16 = 30 prefixes... use N=30 anyway
+        xl = _peaked_logits(70 + b, B, V, 7.0)
+        tok, lp = oracle.topk(xl, K)
+        tree = oracle.build_tree(tok, lp, N, root_token=b)
+        if b == 2:
+            tree = oracle.build_tree(tok[:, :1], lp[:, :1], N, root_token=b)  # chain of 4, rest padding
+        plant = di.planted_tokens(80 + b, tree["depth"], tok[:, 0], B, p=0.9)
+        xs.append(di.target_logits(80 + b, N + 1, V, plant, batch_index=b))
+        trees.append(tree)
+    g = gu.gpu_accept(np.stack(xs), np.stack([t["tokens"] for t in trees]),
+                      np.stack([t["parent"] for t in trees]), np.stack([t["depth"] for t in trees]),
+                      [t["n_nodes"] for t in trees], B)
+    for b in range(3):
+        o = oracle.accept(xs[b], trees[b]["tokens"], trees[b]["parent"], trees[b]["n_nodes"], B)
+        assert np.array_equal(g["posterior"][b], o["posterior"])
+        assert np.array_equal(g["path"][b], o["path"])
+        assert int(g["n_accepted"][b]) == o["n_accepted"] and int(g["bonus_token"][b]) == o["bonus"]
+
+
+def test_compact_matches_oracle():
+    import paper_2604_12989_amd as dd
+    batch, T, B, Hkv, D = 2, 20, 6, 2, 128
+    rng = np.random.default_rng(9)
+    kt = di.round_to_bf16(rng.standard_normal((batch * T, Hkv, D)).astype(np.float32))
+    vt = di.round_to_bf16(rng.standard_normal((batch * T, Hkv, D)).astype(np.float32))
+    rows = 64
+    kc = np.zeros((rows, Hkv, D), np.float32); vc = np.zeros((rows, Hkv, D), np.float32)
+    path = np.array([[0, 3, 7, 12, -1, -1, -1], [0, -1, -1, -1, -1, -1, -1]], np.int32)
+    nacc = np.array([3, 0], np.int32)
+    dst = [10, 40]
+    kcd, vcd = gu.bf16_dev(kc), gu.bf16_dev(vc)
+    dd.compact(gu.bf16_dev(kt), gu.bf16_dev(vt), gu.to_dev(path), gu.to_dev(nacc), dst, batch, T, B,
+               Hkv, D, kcd, vcd)
+    torch.cuda.synchronize()
+    for b in range(batch):
+        oracle.compact(kt[b * T:(b + 1) * T], path[b], int(nacc[b]), kc, dst[b])
+        oracle.compact(vt[b * T:(b + 1) * T], path[b], int(nacc[b]), vc, dst[b])
+    assert np.array_equal(kcd.float().cpu().numpy(), kc)
+    assert np.array_equal(vcd.float().cpu().numpy(), vc)
+
+
+# ------------------------------------------------------------------------------- end to end
+@pytest.mark.parametrize("config", [1, 2])
+def test_end_to_end_chain(config):
+    """topk -> build -> attention -> accept on the GPU, each stage fed by the GPU's own previous
+    stage, against the oracle chain from the same logits."""
+    c = di.CONFIGS[config]
+    seed = di.config_seed(config)
+    B, V, N = c["B"], c["V"], c["N"]
+    K, T = min(N, V), N + 1
+    x = di.draft_logits(seed, B, V)
+    tok_o, lp_o = oracle.topk(x, K)
+    tree = oracle.build_tree(tok_o, lp_o, N, root_token=11)
+    mask_o = oracle.ancestor_mask(tree["parent"], tree["n_nodes"], T=T)
+    plant = di.planted_tokens(seed, tree["depth"], tok_o[:, 0], B)
+    tl = di.target_logits(seed, T, V, plant)
+    acc_o = oracle.accept(tl, tree["tokens"], tree["parent"], tree["n_nodes"], B)
+
+    tok_g, lp_g = gu.gpu_topk(x, K)
+    assert np.array_equal(tok_g[0], tok_o)
+    g = gu.gpu_build(tok_g[0], lp_g[0], N, 11)
+    # the tree from the GPU's own log-probabilities must equal the oracle tree built from them
+    o2 = oracle.build_tree(tok_g[0], lp_g[0], N, root_token=11)
+    for key in ("tokens", "parent", "depth"):
+        assert np.array_equal(g[key][0], o2[key])
+    same_lp = np.array_equal(lp_g[0], lp_o)
+    print(f"config {config}: lp bit-exact {same_lp}")
+    if same_lp:
+        assert np.array_equal(g["tokens"][0], tree["tokens"])
+        assert np.array_equal(g["ancestor_mask"][0], mask_o)
+    q, kc, vc, kt, vt = di.attn_tensors(seed, T, c["L"], c["Hq"], c["Hkv"], c["D"], c["dtype"])
+    ref = oracle.verify_attn(q, kc, vc, kt, vt, g["ancestor_mask"][0])
+    got = gu.gpu_attn(q, kc, vc, kt, vt, g["ancestor_mask"], [0, c["L"]], 1, T, c["dtype"])[0]
+    assert np.abs(got - ref).max() < (1e-5 if c["dtype"] == "fp32" else 1e-2)
+    ga = gu.gpu_accept(tl, g["tokens"][0], g["parent"][0], g["depth"][0], g["n_nodes"], B)
+    if same_lp:
+        assert np.array_equal(ga["path"][0], acc_o["path"])
+        assert int(ga["n_accepted"][0]) == acc_o["n_accepted"]
+        assert int(ga["bonus_token"][0]) == acc_o["bonus"]
