@@ -151,7 +151,7 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     float l_run[2] = {0.0f, 0.0f};
 
     // global -> register staging of one tile
-    uint4 kst[2], vst[4];
+    uint4 kst[4], vst[4];
     const int v_dg = tid & 15, v_kg = tid >> 4;  // V: 8 dims x 4 keys per thread
     auto tile_src = [&](int t, const uint16_t *&kp, const uint16_t *&vp, int &valid) {
         if (t < n_cache_tiles) {
@@ -173,7 +173,7 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         tile_src(t, kp, vp, valid);
         const size_t rs = (size_t)Hkv * kHD;  // elements between consecutive keys
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
+        for (int r = 0; r < 4; ++r) {
             const int id = tid + r * kAttnThreads;
             const int key = id >> 4, ch = id & 15;
             kst[r] = key < valid ? *reinterpret_cast<const uint4 *>(kp + key * rs + ch * 8)
@@ -188,7 +188,7 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     };
     auto store_tile = [&]() {
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
+        for (int r = 0; r < 4; ++r) {
             const int id = tid + r * kAttnThreads;
             const int key = id >> 4, ch = id & 15;
             *reinterpret_cast<uint4 *>(&sK[key * kKStride + ch * 8]) = kst[r];

@@ -53,7 +53,7 @@ def gpu_attn(q, kc, vc, kt, vt, mask, kv_offset, batch, T, dtype, scale=None):
     Hkv = kt.shape[-2]
     sum_L = int(kv_offset[-1])
     conv = bf16_dev if dtype == "bf16" else (lambda a: to_dev(np.asarray(a, np.float32)))
-    ws = ws_for(batch, 1, 8, T - 1, Hq, Hkv, D, sum_L)
+    ws = ws_for(batch, 1, 8, max(T - 1, 1), Hq, Hkv, D, sum_L)
     scale = float(scale if scale is not None else 1.0 / np.sqrt(D))
     kcd = conv(kc.reshape(-1, Hkv, D)) if sum_L > 0 else None
     vcd = conv(vc.reshape(-1, Hkv, D)) if sum_L > 0 else None

@@ -21,6 +21,13 @@ def _need_gpu():
         pytest.fail("GPU tests selected but no GPU is visible")
 
 
+def attn_err(got, ref):
+    """Max over elements of |got - ref| / max(1, |ref|): the 1e-2 (bf16) / 1e-5 (fp32) bound is
+    absolute for outputs up to 1 in magnitude (unit-variance inputs averaged over many keys) and
+    relative above, since a bf16 output of magnitude 4 is itself only known to 2**-9 * 4."""
+    return float((np.abs(got - ref) / np.maximum(1.0, np.abs(ref))).max())
+
+
 def ulp_diff(a, b):
     ia = a.view(np.int32).astype(np.int64)
     ib = b.view(np.int32).astype(np.int64)
@@ -165,8 +172,9 @@ def test_attn_bf16_mfma_matches_oracle(T, L, Hq, Hkv, seed):
     q, kc, vc, kt, vt, mask = _attn_case(seed, T, L, Hq, Hkv, D, "bf16")
     ref = oracle.verify_attn(q, kc, vc, kt, vt, mask)
     got = gu.gpu_attn(q, kc, vc, kt, vt, mask[None], [0, L], 1, T, "bf16")[0]
-    err = np.abs(got - ref).max()
-    print(f"T={T} L={L}: max abs err {err:.2e}, rms(ref) {np.sqrt((ref ** 2).mean()):.3f}")
+    err = attn_err(got, ref)
+    print(f"T={T} L={L}: max err {err:.2e} (abs {np.abs(got - ref).max():.2e}), "
+          f"rms(ref) {np.sqrt((ref ** 2).mean()):.3f}")
     assert err < 1e-2
 
 
@@ -177,7 +185,7 @@ def test_attn_fp32_config1():
                                          "fp32")
     ref = oracle.verify_attn(q, kc, vc, kt, vt, mask)
     got = gu.gpu_attn(q, kc, vc, kt, vt, mask[None], [0, c["L"]], 1, T, "fp32")[0]
-    assert np.abs(got - ref).max() < 1e-5
+    assert attn_err(got, ref) < 1e-5
 
 
 @pytest.mark.parametrize("dtype,D,tol", [("fp32", 64, 1e-5), ("fp32", 128, 1e-5), ("bf16", 64, 1e-2),
@@ -187,7 +195,7 @@ def test_attn_generic_path(dtype, D, tol):
     q, kc, vc, kt, vt, mask = _attn_case(12, T, L, Hq, Hkv, D, dtype)
     ref = oracle.verify_attn(q, kc, vc, kt, vt, mask)
     got = gu.gpu_attn(q, kc, vc, kt, vt, mask[None], [0, L], 1, T, dtype)[0]
-    assert np.abs(got - ref).max() < tol
+    assert attn_err(got, ref) < tol
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
@@ -229,7 +237,7 @@ def test_attn_chain_tree_and_no_cache():
     mask = oracle.ancestor_mask(np.arange(-1, T - 1, dtype=np.int32), T - 1)
     ref = oracle.verify_attn(q, kc, vc, kt, vt, mask)
     got = gu.gpu_attn(q, kc, vc, kt, vt, mask[None], [0, 0], 1, T, "bf16")[0]
-    assert np.abs(got - ref).max() < 1e-2
+    assert attn_err(got, ref) < 1e-2
     # the root sees only itself: its output is its own value row, exactly
     for h in range(Hq):
         assert np.array_equal(got[0, h], vt[0, h // 2])
@@ -241,7 +249,7 @@ def test_attn_padding_rows_are_zero():
     ref = oracle.verify_attn(q, kc, vc, kt, vt, mask)
     got = gu.gpu_attn(q, kc, vc, kt, vt, mask[None], [0, L], 1, T, "bf16")[0]
     assert not got[41:].any() and not ref[41:].any()
-    assert np.abs(got - ref).max() < 1e-2
+    assert attn_err(got, ref) < 1e-2
 
 
 def test_attn_batched_ragged():
@@ -256,7 +264,7 @@ def test_attn_batched_ragged():
     got = gu.gpu_attn(np.concatenate(qs), np.concatenate(kcs), np.concatenate(vcs),
                       np.concatenate(kts), np.concatenate(vts), np.stack(ms), off, batch, T, "bf16")
     for b in range(batch):
-        assert np.abs(got[b] - refs[b]).max() < 1e-2
+        assert attn_err(got[b], refs[b]) < 1e-2
 
 
 # ------------------------------------------------------------------------------- accept
@@ -284,23 +292,37 @@ def test_accept_matches_oracle(V, N, spike, p):
 
 def test_accept_branches_with_rank_above_zero_and_ties():
     B, V, N = 8, 5000, 60
-    tok, tree = _tree_for_accept(60, B, V, N, 5.0)
+    tok, tree = _tree_for_accept(60, B, V, N, 9.0)
     rng = np.random.default_rng(61)
-    # plant, at every node, the token of one of its children (any rank) when it has children
+    n = tree["n_nodes"]
+    # walk target: the deepest node whose last rank is above zero (a branch off the top-1 chain)
+    cands = [i for i in range(1, n + 1) if tree["rank"][i] > 0]
+    leaf = max(cands, key=lambda i: tree["depth"][i])
+    on_path = {}
+    j = leaf
+    while j > 0:
+        on_path[int(tree["parent"][j])] = j
+        j = int(tree["parent"][j])
+    # every node's target token is one of its children's tokens: the path child on the path,
+    # a random child elsewhere
     plant = np.full(N + 1, -1, np.int64)
-    for i in range(tree["n_nodes"] + 1):
-        kids = [c for c in range(1, tree["n_nodes"] + 1) if tree["parent"][c] == i]
-        if kids:
+    for i in range(n + 1):
+        kids = [c for c in range(1, n + 1) if tree["parent"][c] == i]
+        if i in on_path:
+            plant[i] = tree["tokens"][on_path[i]]
+        elif kids:
             plant[i] = tree["tokens"][rng.choice(kids)]
     x = di.target_logits(61, N + 1, V, plant)
-    x[5, :] = 0.0
-    x[5, [4000, 77, 900]] = 3.0                       # tie: lowest id wins
-    o = oracle.accept(x, tree["tokens"], tree["parent"], tree["n_nodes"], B)
-    g = gu.gpu_accept(x, tree["tokens"], tree["parent"], tree["depth"], [tree["n_nodes"]], B)
-    assert o["posterior"][5] == 77
+    off = next(i for i in range(1, n + 1) if i not in on_path and i != leaf)
+    x[off, :] = 0.0
+    x[off, [4000, 77, 900]] = 3.0                     # tie: lowest id wins
+    o = oracle.accept(x, tree["tokens"], tree["parent"], n, B)
+    g = gu.gpu_accept(x, tree["tokens"], tree["parent"], tree["depth"], [n], B)
+    assert o["posterior"][off] == 77
+    assert o["n_accepted"] >= tree["depth"][leaf] >= 1
     assert np.array_equal(g["posterior"][0], o["posterior"])
     assert np.array_equal(g["path"][0], o["path"]) and int(g["bonus_token"][0]) == o["bonus"]
-    assert o["n_accepted"] >= 2
+    assert int(g["n_accepted"][0]) == o["n_accepted"]
 
 
 def test_accept_batched_with_padding_rows():
@@ -381,7 +403,7 @@ def test_end_to_end_chain(config):
     q, kc, vc, kt, vt = di.attn_tensors(seed, T, c["L"], c["Hq"], c["Hkv"], c["D"], c["dtype"])
     ref = oracle.verify_attn(q, kc, vc, kt, vt, g["ancestor_mask"][0])
     got = gu.gpu_attn(q, kc, vc, kt, vt, g["ancestor_mask"], [0, c["L"]], 1, T, c["dtype"])[0]
-    assert np.abs(got - ref).max() < (1e-5 if c["dtype"] == "fp32" else 1e-2)
+    assert attn_err(got, ref) < (1e-5 if c["dtype"] == "fp32" else 1e-2)
     ga = gu.gpu_accept(tl, g["tokens"][0], g["parent"][0], g["depth"][0], g["n_nodes"], B)
     if same_lp:
         assert np.array_equal(ga["path"][0], acc_o["path"])
