@@ -161,6 +161,29 @@ int ddtree_compact(const void *k_tree, const void *v_tree, const int32_t *path,
                    const int32_t *n_accepted, const int32_t *dst_row, int batch, int T, int B,
                    int Hkv, int D, int elem_bytes, void *k_cache, void *v_cache, void *stream);
 
+/*
+ * Kernel timing hook for benchmarks (no passage of the paper: measurement only).  While a
+ * kernel's bit is set in kernel_mask, every launch of that kernel is bracketed by a pair of HIP
+ * events recorded on the launch stream, up to `capacity` launches per kernel; the events are
+ * created here, never inside the hot calls.  kernel_mask = 0 switches the hook off and destroys
+ * the events.  ddtree_profile_read copies the elapsed milliseconds of the recorded launches of
+ * one kernel to host memory and returns how many there were (or a negative error); the caller
+ * must have synchronised the stream(s) first.  ddtree_profile_reset forgets recorded launches.
+ * Not thread-safe; meant for a single benchmarking thread.
+ */
+#define DDTREE_KERNEL_TOPK_CHUNK 0
+#define DDTREE_KERNEL_TOPK_MERGE 1
+#define DDTREE_KERNEL_BUILD 2
+#define DDTREE_KERNEL_ATTN 3
+#define DDTREE_KERNEL_ATTN_MERGE 4
+#define DDTREE_KERNEL_ACCEPT_ARGMAX 5
+#define DDTREE_KERNEL_ACCEPT_WALK 6
+#define DDTREE_KERNEL_ATTN_GENERIC 7
+#define DDTREE_KERNEL_COUNT 8
+int ddtree_profile_enable(unsigned kernel_mask, int capacity);
+int ddtree_profile_reset(void);
+int ddtree_profile_read(int kernel_id, float *ms_out /* [host] */, int max_records);
+
 #ifdef __cplusplus
 }
 #endif

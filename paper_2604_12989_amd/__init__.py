@@ -7,8 +7,8 @@ fallback path.
 """
 from .binding import (DDTreeError, accept, build, compact, error_string, library_path, load,
                       topk, verify_attn, version, workspace_bytes, Workspace, DTYPE_BF16,
-                      DTYPE_FP32)
+                      DTYPE_FP32, KERNELS, profile_enable, profile_read, profile_reset)
 
 __all__ = ["DDTreeError", "accept", "build", "compact", "error_string", "library_path", "load",
            "topk", "verify_attn", "version", "workspace_bytes", "Workspace", "DTYPE_BF16",
-           "DTYPE_FP32"]
+           "DTYPE_FP32", "KERNELS", "profile_enable", "profile_read", "profile_reset"]

@@ -28,7 +28,13 @@ _SIGNATURES = {
     "ddtree_accept": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _sz,
                            _vp]),
     "ddtree_compact": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp]),
+    "ddtree_profile_enable": (_i, [ctypes.c_uint, _i]),
+    "ddtree_profile_reset": (_i, []),
+    "ddtree_profile_read": (_i, [_i, _vp, _i]),
 }
+
+KERNELS = {"topk_chunk": 0, "topk_merge": 1, "build": 2, "attn": 3, "attn_merge": 4,
+           "accept_argmax": 5, "accept_walk": 6, "attn_generic": 7}
 
 
 class DDTreeError(RuntimeError):
@@ -68,6 +74,33 @@ def _check(code: int, what: str):
         raise DDTreeError(f"{what} failed: {error_string(code)} ({code})")
 
 
+def _call(name, args, result, defer):
+    """Run the C entry point now, or (defer=True) return a zero-argument callable that runs it
+    with the arguments marshalled once: tight loops then pay one ctypes call per stage."""
+    fn = getattr(load(), name)
+    if not defer:
+        _check(fn(*args), name)
+        return result
+
+    # the callable holds raw pointers: the caller keeps the tensors alive while it is in use
+    keep = (args, result)
+
+    def run():
+        rc = fn(*keep[0])
+        if rc != 0:
+            _check(rc, name)
+        return keep[1]
+
+    return run
+
+
+def _keepalive(fn, *objs):
+    def run():
+        return fn()
+    run.keep = objs
+    return run
+
+
 def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
@@ -105,7 +138,7 @@ def _ws(ws):
     return ctypes.c_void_p(ws.ptr), ws.nbytes
 
 
-def topk(logits, K, ws, topk_tok=None, topk_lp=None):
+def topk(logits, K, ws, topk_tok=None, topk_lp=None, defer=False):
     """logits fp32 [batch,B,V] (or [B,V]) -> (topk_tok int32, topk_lp fp32) [batch,B,K]."""
     _dev(logits, torch.float32, "logits")
     x = logits if logits.dim() == 3 else logits.unsqueeze(0)
@@ -115,12 +148,11 @@ def topk(logits, K, ws, topk_tok=None, topk_lp=None):
     if topk_lp is None:
         topk_lp = torch.empty((batch, B, K), dtype=torch.float32, device=x.device)
     p, n = _ws(ws)
-    _check(load().ddtree_topk(_ptr(x), batch, B, V, K, _ptr(topk_tok), _ptr(topk_lp), p, n,
-                              _stream()), "ddtree_topk")
-    return topk_tok, topk_lp
+    args = (_ptr(x), batch, B, V, K, _ptr(topk_tok), _ptr(topk_lp), p, n, _stream())
+    return _call("ddtree_topk", args, (topk_tok, topk_lp), defer)
 
 
-def build(topk_tok, topk_lp, N, root_token, ws=None, out=None):
+def build(topk_tok, topk_lp, N, root_token, ws=None, out=None, defer=False):
     """Returns dict(tokens, parent, depth, rank, node_score, ancestor_mask, n_nodes)."""
     _dev(topk_tok, torch.int32, "topk_tok")
     _dev(topk_lp, torch.float32, "topk_lp")
@@ -137,16 +169,15 @@ def build(topk_tok, topk_lp, N, root_token, ws=None, out=None):
                    ancestor_mask=torch.empty((batch, T, W), dtype=torch.int64, device=dev),
                    n_nodes=torch.empty((batch,), dtype=torch.int32, device=dev))
     p, n = _ws(ws)
-    _check(load().ddtree_build(_ptr(topk_tok), _ptr(topk_lp), batch, B, K, N, _ptr(root_token),
-                               _ptr(out["tokens"]), _ptr(out["parent"]), _ptr(out["depth"]),
-                               _ptr(out.get("rank")), _ptr(out.get("node_score")),
-                               _ptr(out["ancestor_mask"]), _ptr(out["n_nodes"]), p, n, _stream()),
-           "ddtree_build")
-    return out
+    args = (_ptr(topk_tok), _ptr(topk_lp), batch, B, K, N, _ptr(root_token), _ptr(out["tokens"]),
+            _ptr(out["parent"]), _ptr(out["depth"]), _ptr(out.get("rank")),
+            _ptr(out.get("node_score")), _ptr(out["ancestor_mask"]), _ptr(out["n_nodes"]), p, n,
+            _stream())
+    return _call("ddtree_build", args, out, defer)
 
 
 def verify_attn(q, k_cache, v_cache, k_tree, v_tree, ancestor_mask, kv_offset, batch, T, Hq, Hkv,
-                D, softmax_scale, dtype, ws, out=None):
+                D, softmax_scale, dtype, ws, out=None, defer=False):
     """q [batch*T,Hq,D]; k/v_cache [sum_L,Hkv,D]; k/v_tree [batch*T,Hkv,D]; mask int64 [batch,T,W];
     kv_offset: host int32 sequence of batch+1 entries."""
     tdt = torch.bfloat16 if dtype == DTYPE_BF16 else torch.float32
@@ -162,15 +193,15 @@ def verify_attn(q, k_cache, v_cache, k_tree, v_tree, ancestor_mask, kv_offset, b
     if out is None:
         out = torch.empty_like(q)
     p, n = _ws(ws)
-    _check(load().ddtree_verify_attn(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_tree),
-                                     _ptr(v_tree), _ptr(ancestor_mask),
-                                     off.ctypes.data_as(ctypes.c_void_p), batch, T, Hq, Hkv, D,
-                                     ctypes.c_float(softmax_scale), dtype, _ptr(out), p, n,
-                                     _stream()), "ddtree_verify_attn")
-    return out
+    args = (_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_tree), _ptr(v_tree), _ptr(ancestor_mask),
+            off.ctypes.data_as(ctypes.c_void_p), batch, T, Hq, Hkv, D, ctypes.c_float(softmax_scale),
+            dtype, _ptr(out), p, n, _stream())
+    run = _call("ddtree_verify_attn", args, out, defer)
+    return _keepalive(run, off) if defer else run
 
 
-def accept(target_logits, tokens, parent, depth, n_nodes, B, ws, out=None, want_posterior=True):
+def accept(target_logits, tokens, parent, depth, n_nodes, B, ws, out=None, want_posterior=True,
+           defer=False):
     """target_logits fp32 [batch,T,V] -> dict(path [batch,B+1], n_accepted, bonus_token, posterior)."""
     _dev(target_logits, torch.float32, "target_logits")
     batch, T, V = target_logits.shape
@@ -182,11 +213,10 @@ def accept(target_logits, tokens, parent, depth, n_nodes, B, ws, out=None, want_
                    posterior=(torch.empty((batch, T), dtype=torch.int32, device=dev)
                               if want_posterior else None))
     p, n = _ws(ws)
-    _check(load().ddtree_accept(_ptr(target_logits), batch, T, V, _ptr(tokens), _ptr(parent),
-                                _ptr(depth), _ptr(n_nodes), _ptr(out["path"]),
-                                _ptr(out["n_accepted"]), _ptr(out["bonus_token"]),
-                                _ptr(out.get("posterior")), B, p, n, _stream()), "ddtree_accept")
-    return out
+    args = (_ptr(target_logits), batch, T, V, _ptr(tokens), _ptr(parent), _ptr(depth),
+            _ptr(n_nodes), _ptr(out["path"]), _ptr(out["n_accepted"]), _ptr(out["bonus_token"]),
+            _ptr(out.get("posterior")), B, p, n, _stream())
+    return _call("ddtree_accept", args, out, defer)
 
 
 def compact(k_tree, v_tree, path, n_accepted, dst_row, batch, T, B, Hkv, D, k_cache, v_cache):
@@ -198,3 +228,24 @@ def compact(k_tree, v_tree, path, n_accepted, dst_row, batch, T, B, Hkv, D, k_ca
                                  dst.ctypes.data_as(ctypes.c_void_p), batch, T, B, Hkv, D,
                                  k_tree.element_size(), _ptr(k_cache), _ptr(v_cache), _stream()),
            "ddtree_compact")
+
+
+def profile_enable(kernels, capacity):
+    """Time every launch of the named kernels (see KERNELS) with HIP events; [] switches it off."""
+    mask = 0
+    for k in kernels:
+        mask |= 1 << KERNELS[k]
+    _check(load().ddtree_profile_enable(mask, int(capacity)), "ddtree_profile_enable")
+
+
+def profile_reset():
+    _check(load().ddtree_profile_reset(), "ddtree_profile_reset")
+
+
+def profile_read(kernel, max_records=1 << 16):
+    """Elapsed milliseconds of the recorded launches of one kernel (synchronise first)."""
+    buf = np.empty(max_records, np.float32)
+    n = load().ddtree_profile_read(KERNELS[kernel], buf.ctypes.data_as(ctypes.c_void_p), max_records)
+    if n < 0:
+        _check(n, "ddtree_profile_read")
+    return buf[:n].copy()

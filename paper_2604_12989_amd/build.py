@@ -9,7 +9,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
 LIB = os.path.join(_HERE, "libddtree.so")
-SOURCES = ["topk.hip", "build.hip", "attn.hip", "accept.hip"]
+SOURCES = ["api.hip", "topk.hip", "build.hip", "attn.hip", "accept.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -221,9 +221,9 @@ extern "C" int ddtree_accept(const float *target_logits, int batch, int T, int V
     if (!ws_ok(workspace, workspace_bytes, p.bytes)) return DDTREE_ERR_WORKSPACE;
     ArgPart *part = reinterpret_cast<ArgPart *>(static_cast<char *>(workspace) + p.part_off);
     hipStream_t st = as_stream(stream);
-    hipLaunchKernelGGL(accept_argmax_kernel, dim3(p.splits, T, batch), dim3(kArgmaxThreads), 0, st,
+    DDT_LAUNCH(DDTREE_KERNEL_ACCEPT_ARGMAX, st, accept_argmax_kernel, dim3(p.splits, T, batch), dim3(kArgmaxThreads), 0, st,
                        target_logits, T, V, p.seg_len, p.splits, n_nodes, part);
-    hipLaunchKernelGGL(accept_walk_kernel, dim3(batch), dim3(kWalkThreads), 0, st, part, T, p.splits,
+    DDT_LAUNCH(DDTREE_KERNEL_ACCEPT_WALK, st, accept_walk_kernel, dim3(batch), dim3(kWalkThreads), 0, st, part, T, p.splits,
                        B, tokens, parent, depth, n_nodes, path, n_accepted, bonus_token, posterior);
     return launch_status();
 }

@@ -72,7 +72,7 @@ AttnPlan attn_plan(int batch, int T, int Hq, int Hkv, int D, long long sum_L, in
 }
 
 // Upper bound of attn_plan(...).bytes over all sum_L: splits only shrink with shorter caches.
-static size_t attn_ws_upper(int batch, int T, int Hq, int Hkv, int D)
+size_t attn_ws_upper(int batch, int T, int Hq, int Hkv, int D)
 {
     AttnPlan p = attn_plan(batch, T, Hq, Hkv, D, (long long)1 << 40, DDTREE_DTYPE_BF16);
     return p.bytes;
@@ -523,7 +523,7 @@ extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void
         if (!ws_ok(workspace, workspace_bytes, p.bytes)) return DDTREE_ERR_WORKSPACE;
         float *part = p.splits > 1 ? reinterpret_cast<float *>(static_cast<char *>(workspace) + p.part_off) : nullptr;
         float *lse = p.splits > 1 ? reinterpret_cast<float *>(static_cast<char *>(workspace) + p.lse_off) : nullptr;
-        hipLaunchKernelGGL(attn_mfma_kernel, dim3(p.splits, p.mtiles * Hkv, batch), dim3(kAttnThreads), 0,
+        DDT_LAUNCH(DDTREE_KERNEL_ATTN, st, attn_mfma_kernel, dim3(p.splits, p.mtiles * Hkv, batch), dim3(kAttnThreads), 0,
                            st, static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(k_cache),
                            static_cast<const uint16_t *>(v_cache), static_cast<const uint16_t *>(k_tree),
                            static_cast<const uint16_t *>(v_tree), ancestor_mask, args, T, Hq, Hkv,
@@ -531,19 +531,19 @@ extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void
         if (p.splits > 1) {
             const size_t rows = (size_t)batch * T * Hq;
             const size_t threads = rows * (kHD / 4);
-            hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+            DDT_LAUNCH(DDTREE_KERNEL_ATTN_MERGE, st, attn_merge_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
                                part, lse, p.splits, rows, static_cast<uint16_t *>(out));
         }
         return launch_status();
     }
     if (dtype == DDTREE_DTYPE_FP32)
-        hipLaunchKernelGGL(attn_generic_kernel<float>, dim3(Hq, T, batch), dim3(kGenThreads), 0, st,
+        DDT_LAUNCH(DDTREE_KERNEL_ATTN_GENERIC, st, attn_generic_kernel<float>, dim3(Hq, T, batch), dim3(kGenThreads), 0, st,
                            static_cast<const float *>(q), static_cast<const float *>(k_cache),
                            static_cast<const float *>(v_cache), static_cast<const float *>(k_tree),
                            static_cast<const float *>(v_tree), ancestor_mask, args, T, Hq, Hkv, D,
                            softmax_scale, static_cast<float *>(out));
     else
-        hipLaunchKernelGGL(attn_generic_kernel<uint16_t>, dim3(Hq, T, batch), dim3(kGenThreads), 0, st,
+        DDT_LAUNCH(DDTREE_KERNEL_ATTN_GENERIC, st, attn_generic_kernel<uint16_t>, dim3(Hq, T, batch), dim3(kGenThreads), 0, st,
                            static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(k_cache),
                            static_cast<const uint16_t *>(v_cache), static_cast<const uint16_t *>(k_tree),
                            static_cast<const uint16_t *>(v_tree), ancestor_mask, args, T, Hq, Hkv, D,
@@ -551,38 +551,3 @@ extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void
     return launch_status();
 }
 
-// ------------------------------------------------------------------------------------------
-// Library-level entry points that belong to no single stage.
-// ------------------------------------------------------------------------------------------
-extern "C" int ddtree_version(void) { return 100; }
-
-extern "C" const char *ddtree_error_string(int code)
-{
-    switch (code) {
-    case DDTREE_OK: return "ok";
-    case DDTREE_ERR_ARG: return "bad argument (null pointer, shape, size or dtype)";
-    case DDTREE_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
-    case DDTREE_ERR_HIP: return "HIP runtime error at launch";
-    default: return "unknown error code";
-    }
-}
-
-extern "C" size_t ddtree_workspace_bytes(int batch, int B, int V, int N, int Hq, int Hkv, int D,
-                                         int max_sum_L)
-{
-    using namespace ddt;
-    (void)max_sum_L;
-    if (batch < 1 || batch > DDTREE_MAX_BATCH || B < 1 || B > DDTREE_MAX_B || V < 1 || N < 1 ||
-        N > DDTREE_MAX_N || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || D < 8 || D > 256 || D % 8 != 0)
-        return 0;
-    const int K = N < V ? N : V;
-    const int T = N + 1;
-    TopkPlan tp = topk_plan(batch, B, V, K);
-    if (!tp.ok) return 0;
-    size_t need = tp.bytes;
-    const size_t a = attn_ws_upper(batch, T, Hq, Hkv, D);
-    if (a > need) need = a;
-    const size_t c = accept_plan(batch, T, V).bytes;
-    if (c > need) need = c;
-    return need < 256 ? 256 : need;
-}

@@ -268,7 +268,7 @@ static int launch_build(const int32_t *topk_tok, const float *topk_lp, int batch
             return DDTREE_ERR_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL(build_kernel<NSLOT>, dim3(batch), dim3(kBuildThreads), build_lds_bytes(B, K, N),
+    DDT_LAUNCH(DDTREE_KERNEL_BUILD, st, build_kernel<NSLOT>, dim3(batch), dim3(kBuildThreads), build_lds_bytes(B, K, N),
                        st, topk_tok, topk_lp, B, K, N, root_token, tokens, parent, depth, rank,
                        node_score, ancestor_mask, n_nodes);
     return launch_status();

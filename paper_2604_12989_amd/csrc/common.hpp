@@ -53,6 +53,38 @@ struct AcceptPlan {
 };
 AcceptPlan accept_plan(int batch, int T, int V);
 
+// ---- optional event timing around kernel launches (see ddtree_profile_enable) ----
+struct Profiler {
+    unsigned mask = 0;
+    int capacity = 0;
+    int count[DDTREE_KERNEL_COUNT] = {};
+    hipEvent_t *start[DDTREE_KERNEL_COUNT] = {};
+    hipEvent_t *stop[DDTREE_KERNEL_COUNT] = {};
+};
+Profiler &profiler();
+// Records the start event if launches of kernel `id` are being timed; returns the slot or -1.
+inline int profile_begin(int id, hipStream_t st)
+{
+    Profiler &p = profiler();
+    if (!(p.mask & (1u << id)) || p.count[id] >= p.capacity) return -1;
+    const int slot = p.count[id];
+    (void)hipEventRecord(p.start[id][slot], st);
+    return slot;
+}
+inline void profile_end(int id, int slot, hipStream_t st)
+{
+    if (slot < 0) return;
+    Profiler &p = profiler();
+    (void)hipEventRecord(p.stop[id][slot], st);
+    p.count[id] = slot + 1;
+}
+#define DDT_LAUNCH(id, st, ...)                        \
+    do {                                               \
+        const int _slot = ::ddt::profile_begin(id, st); \
+        hipLaunchKernelGGL(__VA_ARGS__);               \
+        ::ddt::profile_end(id, _slot, st);             \
+    } while (0)
+
 #if defined(__HIPCC__)
 // Order-preserving map from finite floats to unsigned integers (-0 is folded onto +0).
 __device__ __forceinline__ uint32_t float_key(float x)

@@ -363,9 +363,9 @@ extern "C" int ddtree_topk(const float *logits, int batch, int B, int V, int K, 
         attr_set = true;
     }
     hipStream_t st = as_stream(stream);
-    hipLaunchKernelGGL(topk_chunk_kernel, dim3(p.chunks, B, batch), dim3(kChunkThreads), lds_chunk, st,
+    DDT_LAUNCH(DDTREE_KERNEL_TOPK_CHUNK, st, topk_chunk_kernel, dim3(p.chunks, B, batch), dim3(kChunkThreads), lds_chunk, st,
                        logits, V, K, p.chunk_len, p.kc, p.chunks, cand, stat);
-    hipLaunchKernelGGL(topk_merge_kernel, dim3(B, batch), dim3(kMergeThreads), lds_merge, st, cand,
+    DDT_LAUNCH(DDTREE_KERNEL_TOPK_MERGE, st, topk_merge_kernel, dim3(B, batch), dim3(kMergeThreads), lds_merge, st, cand,
                        stat, K, p.kc, p.chunks, topk_tok, topk_lp);
     return launch_status();
 }
