@@ -15,11 +15,13 @@
 //                 registers for the whole kernel.  In the accumulator layout a lane then owns
 //                 one query row, so the softmax max and sum are register-local reductions.
 //   P^T           exp2 of the scaled, masked scores; the accumulator registers of S^T are, as
-//                 they stand, the B operand of the next product (no cross-lane movement), once
-//                 the V tile is stored transposed with a matching key permutation.
-//   O^T += V^T P^T
-// K tiles sit in LDS as [key][dim] (row padded by 16 B), V tiles as [dim][key'] where key' is
-// the permuted key position, both written once per tile from 16-byte global loads.
+//                 they stand, the B operand of the next product (no cross-lane movement).
+//   O^T += V^T P^T  A = V^T, gathered from the row-major V tile in LDS by the transposing
+//                 LDS read, in the key order the P^T registers happen to have.
+// The running maximum is a lagging reference: accumulators are rescaled only when a row's
+// maximum grows by more than 2^8, so the steady state has no rescale work at all.
+// K and V tiles sit in LDS as [key][dim], rows padded (272 B / 288 B) so that the 16-byte K
+// reads and the transposing V reads are free of bank conflicts.
 // The ancestor mask touches only the tree tiles (the last ceil(T/64) tiles): one 64-bit word per
 // (row, tile), bit test per score.  Cache tiles carry no mask work at all.
 #include "common.hpp"
@@ -34,7 +36,7 @@ constexpr int kMT = 256;       // query rows per workgroup
 constexpr int kKT = 64;        // keys per tile
 constexpr int kHD = 128;       // head dim of the MFMA path
 constexpr int kKStride = kHD + 8;   // bf16 elements per K row in LDS (272 B)
-constexpr int kVStride = kKT + 8;   // bf16 elements per V^T row in LDS (144 B)
+constexpr int kVStride = kHD + 16;  // bf16 elements per V row in LDS (288 B)
 constexpr float kLog2e = 1.4426950408889634f;
 
 struct AttnArgs {
@@ -87,6 +89,22 @@ __device__ __forceinline__ uint32_t f2bf_pair(float lo, float hi)
            ((uint32_t)__builtin_bit_cast(unsigned short, b) << 16);
 }
 
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short shortx4;
+
+// LDS transpose read (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane 4*j + r points
+// at four consecutive 16-bit elements; afterwards lane i of the group holds, for j = 0..3, element
+// i % 4 of what lane 4*j + i / 4 pointed at.  With lane 4*j + r pointing at V[key_j][d0 + 4*r ..],
+// lane i receives V[key_0..3][d0 + i]: a column of the row-major V tile, which is what the A
+// operand (V^T) of the second product needs.
+__device__ __forceinline__ uint2 lds_read_tr16(const uint16_t *p)
+{
+    const shortx4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) shortx4 *)(p));
+    return __builtin_bit_cast(uint2, t);
+}
+
+constexpr float kRescaleThreshold = 8.0f;  // log2 units: stale running max tolerated up to 2^8
+
 __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_cache,
                       const uint16_t *__restrict__ v_cache, const uint16_t *__restrict__ k_tree,
@@ -95,7 +113,7 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                       uint16_t *__restrict__ out, float *__restrict__ part, float *__restrict__ part_lse)
 {
     __shared__ __align__(16) uint16_t sK[kKT * kKStride];
-    __shared__ __align__(16) uint16_t sVt[kHD * kVStride];
+    __shared__ __align__(16) uint16_t sV[kKT * kVStride];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
@@ -147,80 +165,55 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) o[db][cb][v] = 0.0f;
-    float m_run[2] = {-INFINITY, -INFINITY};
+    float m_run[2] = {-INFINITY, -INFINITY};  // reference maximum (may lag the true one)
     float l_run[2] = {0.0f, 0.0f};
 
-    // global -> register staging of one tile
+    // global -> register -> LDS staging: thread owns chunk (key = tid/16 + 16*r, 16-byte column tid%16)
+    const int st_key = tid >> 4, st_ch = tid & 15;
+    const size_t rs = (size_t)Hkv * kHD;  // elements between consecutive keys in global memory
     uint4 kst[4], vst[4];
-    const int v_dg = tid & 15, v_kg = tid >> 4;  // V: 8 dims x 4 keys per thread
-    auto tile_src = [&](int t, const uint16_t *&kp, const uint16_t *&vp, int &valid) {
-        if (t < n_cache_tiles) {
-            const size_t row0 = (size_t)L0 + (size_t)t * kKT;
-            kp = k_cache + (row0 * Hkv + hk) * kHD;
-            vp = v_cache + (row0 * Hkv + hk) * kHD;
-            valid = min(kKT, L - t * kKT);
-        } else {
-            const int tb = t - n_cache_tiles;
-            const size_t row0 = (size_t)seq * T + (size_t)tb * kKT;
-            kp = k_tree + (row0 * Hkv + hk) * kHD;
-            vp = v_tree + (row0 * Hkv + hk) * kHD;
-            valid = min(kKT, T - tb * kKT);
-        }
-    };
-    auto load_tile = [&](int t) {
-        const uint16_t *kp, *vp;
-        int valid;
-        tile_src(t, kp, vp, valid);
-        const size_t rs = (size_t)Hkv * kHD;  // elements between consecutive keys
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int id = tid + r * kAttnThreads;
-            const int key = id >> 4, ch = id & 15;
-            kst[r] = key < valid ? *reinterpret_cast<const uint4 *>(kp + key * rs + ch * 8)
-                                 : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int key = v_kg * 4 + j;
-            vst[j] = key < valid ? *reinterpret_cast<const uint4 *>(vp + key * rs + v_dg * 8)
-                                 : make_uint4(0, 0, 0, 0);
-        }
-    };
-    auto store_tile = [&]() {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int id = tid + r * kAttnThreads;
-            const int key = id >> 4, ch = id & 15;
-            *reinterpret_cast<uint4 *>(&sK[key * kKStride + ch * 8]) = kst[r];
-        }
-        // keys 4*kg .. 4*kg+3 = 16*t' + 8*u + 4*h + w  ->  position 16*t' + 8*h + 4*u + w
-        const int tq = v_kg >> 2, u = (v_kg >> 1) & 1, h = v_kg & 1;
-        const int pos = 16 * tq + 8 * h + 4 * u;
-        const uint32_t a[4] = {vst[0].x, vst[0].y, vst[0].z, vst[0].w};
-        const uint32_t b[4] = {vst[1].x, vst[1].y, vst[1].z, vst[1].w};
-        const uint32_t c[4] = {vst[2].x, vst[2].y, vst[2].z, vst[2].w};
-        const uint32_t d[4] = {vst[3].x, vst[3].y, vst[3].z, vst[3].w};
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int w = i >> 1;
-            uint2 val;
-            if (i & 1) {
-                val.x = pack_hi(a[w], b[w]);
-                val.y = pack_hi(c[w], d[w]);
-            } else {
-                val.x = pack_lo(a[w], b[w]);
-                val.y = pack_lo(c[w], d[w]);
-            }
-            *reinterpret_cast<uint2 *>(&sVt[(v_dg * 8 + i) * kVStride + pos]) = val;
-        }
-    };
+#define DDT_LOAD_TILE(t_)                                                                       \
+    do {                                                                                        \
+        const int tt = (t_);                                                                    \
+        const uint16_t *kp, *vp;                                                                \
+        int valid_;                                                                             \
+        if (tt < n_cache_tiles) {                                                               \
+            const size_t row0 = (size_t)L0 + (size_t)tt * kKT;                                  \
+            kp = k_cache + (row0 * Hkv + hk) * kHD;                                             \
+            vp = v_cache + (row0 * Hkv + hk) * kHD;                                             \
+            valid_ = min(kKT, L - tt * kKT);                                                    \
+        } else {                                                                                \
+            const size_t row0 = (size_t)seq * T + (size_t)(tt - n_cache_tiles) * kKT;           \
+            kp = k_tree + (row0 * Hkv + hk) * kHD;                                              \
+            vp = v_tree + (row0 * Hkv + hk) * kHD;                                              \
+            valid_ = min(kKT, T - (tt - n_cache_tiles) * kKT);                                  \
+        }                                                                                       \
+        _Pragma("unroll") for (int r = 0; r < 4; ++r) {                                         \
+            const int key = st_key + 16 * r;                                                    \
+            const bool ok = key < valid_;                                                       \
+            kst[r] = ok ? *reinterpret_cast<const uint4 *>(kp + key * rs + st_ch * 8)           \
+                        : make_uint4(0, 0, 0, 0);                                               \
+            vst[r] = ok ? *reinterpret_cast<const uint4 *>(vp + key * rs + st_ch * 8)           \
+                        : make_uint4(0, 0, 0, 0);                                               \
+        }                                                                                       \
+    } while (0)
 
-    if (t_begin < t_end) load_tile(t_begin);
+    // per-lane LDS read bases (elements)
+    const int k_base = l32 * kKStride + half * 8;
+    const int lm = lane & 15, dim16 = (lane >> 4) & 1;
+    const int v_base = (4 * half + (lm >> 2)) * kVStride + 16 * dim16 + 4 * (lm & 3);
+
+    if (t_begin < t_end) DDT_LOAD_TILE(t_begin);
     for (int t = t_begin; t < t_end; ++t) {
         __syncthreads();
-        store_tile();
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int key = st_key + 16 * r;
+            *reinterpret_cast<uint4 *>(&sK[key * kKStride + st_ch * 8]) = kst[r];
+            *reinterpret_cast<uint4 *>(&sV[key * kVStride + st_ch * 8]) = vst[r];
+        }
         __syncthreads();
-        if (t + 1 < t_end) load_tile(t + 1);
+        if (t + 1 < t_end) DDT_LOAD_TILE(t + 1);
         if (!wave_active) continue;
 
         const bool is_tree = t >= n_cache_tiles;
@@ -240,13 +233,13 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
                 const bf16x8 a = *reinterpret_cast<const bf16x8 *>(
-                    &sK[(kb * 32 + l32) * kKStride + ks * 16 + half * 8]);
+                    &sK[k_base + kb * 32 * kKStride + ks * 16]);
 #pragma unroll
                 for (int cb = 0; cb < 2; ++cb)
                     s[kb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[cb][ks], s[kb][cb], 0, 0, 0);
             }
 
-        // ---- mask (tree tiles and ragged last cache tile only) ----
+        // ---- mask (tree tiles and a ragged last cache tile only) ----
         if (is_tree || valid < kKT) {
 #pragma unroll
             for (int cb = 0; cb < 2; ++cb) {
@@ -264,20 +257,38 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             }
         }
 
-        // ---- online softmax, per query row (one row per lane and cb) ----
-        bf16x8 pb[2][4];
+        // ---- online softmax, one query row per lane and cb, lazily rescaled ----
+        float m_new[2];
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
-            float tmax = -INFINITY;
+            float tmax = s[0][cb][0];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, s[kb][cb][v]);
             tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-            const float m_new = fmaxf(m_run[cb], tmax * scale_log2e);
-            const float m_use = m_new == -INFINITY ? 0.0f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(m_run[cb] - m_use);
-            m_run[cb] = m_new;
+            m_new[cb] = fmaxf(m_run[cb], tmax * scale_log2e);
+        }
+        // The running reference is only moved when some row's maximum grew by more than the
+        // threshold (always the case on a row's first visible key); otherwise exp2 arguments
+        // stay below the threshold and nothing has to be rescaled.
+        if (__builtin_expect(__any((m_new[0] > m_run[0] + kRescaleThreshold) | (m_new[1] > m_run[1] + kRescaleThreshold)), 0)) {
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) {
+                const float m_use = m_new[cb] == -INFINITY ? 0.0f : m_new[cb];
+                const float alpha = __builtin_amdgcn_exp2f(m_run[cb] - m_use);  // 0 when m_run = -inf
+                m_run[cb] = m_new[cb];
+                l_run[cb] *= alpha;
+#pragma unroll
+                for (int db = 0; db < 4; ++db)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) o[db][cb][v] *= alpha;
+            }
+        }
+        bf16x8 pb[2][4];
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            const float m_use = m_run[cb] == -INFINITY ? 0.0f : m_run[cb];
             float psum = 0.0f;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
@@ -297,25 +308,25 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                     pb[cb][kb * 2 + t2] = __builtin_bit_cast(bf16x8, pk);
                 }
             }
-            l_run[cb] = l_run[cb] * alpha + psum;
-#pragma unroll
-            for (int db = 0; db < 4; ++db)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) o[db][cb][v] *= alpha;
+            l_run[cb] += psum;
         }
 
-        // ---- O^T += V^T P^T ----
+        // ---- O^T += V^T P^T.  Element j of the P^T operand of k-step kst is key
+        //      16*kst + 8*(j/4) + 4*half + j%4; the two transpose reads fetch exactly those keys ----
 #pragma unroll
         for (int kst4 = 0; kst4 < 4; ++kst4)
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(
-                    &sVt[(db * 32 + l32) * kVStride + kst4 * 16 + half * 8]);
+                const uint16_t *vp = &sV[v_base + kst4 * 16 * kVStride + db * 32];
+                const uint2 lo = lds_read_tr16(vp);
+                const uint2 hi = lds_read_tr16(vp + 8 * kVStride);
+                const bf16x8 a = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
 #pragma unroll
                 for (int cb = 0; cb < 2; ++cb)
                     o[db][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[cb][kst4], o[db][cb], 0, 0, 0);
             }
     }
+#undef DDT_LOAD_TILE
 
     if (!wave_active) return;
     // ---- epilogue ----

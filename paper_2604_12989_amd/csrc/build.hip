@@ -11,8 +11,8 @@
 // p's entry and "push first child" is a fresh entry for n.  So the frontier is an array indexed
 // by node id, with no free list.  Entry e lives in lane e % 64, register slot e / 64, and stays
 // in registers for the whole run; a pop is a lane-local max followed by a DPP wave max.
-// The log-probabilities a popped entry needs next (ranks c+1 and c+2 of its row) are prefetched
-// into the entry, so no LDS access sits on the pop-to-pop dependency chain.
+// The log-probability a popped entry needs next (rank c+1 of its row) is prefetched into the
+// entry one pop ahead, so no LDS access sits on the pop-to-pop dependency chain.
 //
 // Ties (equal fp32 scores) are resolved as the boundary specifies: the lexicographically
 // smaller rank tuple first, a prefix before its extensions.  They are rare and take a slow
@@ -91,108 +91,115 @@ __global__ __launch_bounds__(kBuildThreads) void build_kernel(
 
     if (tid < kWave) {
         const int lane = tid;
-        // lane d holds the first three log-probabilities of row d (depth d+1), -inf past the
-        // last row: what a fresh entry for a node at depth d needs
+        // lane d holds the first two log-probabilities of row d (children of a node at depth
+        // d), -inf past the last row: what a fresh entry for a node at depth d needs
         const float lp0 = lane < B ? s_lp[lane * Kp + 0] : -INFINITY;
         const float lp1 = lane < B ? s_lp[lane * Kp + 1] : -INFINITY;
-        const float lp2 = lane < B ? s_lp[lane * Kp + 2] : -INFINITY;
-        float cand[NSLOT], nsc[NSLOT], nlp1[NSLOT], nlp2[NSLOT];
-        int meta[NSLOT];  // (current child rank << 8) | row of the children
+        // Scores are sums of log-probabilities, hence never positive: for such floats a larger
+        // value has the smaller bit pattern, so "best candidate" is an unsigned minimum and
+        // -inf (0xFF800000) marks an empty entry.
+        constexpr uint32_t kEmpty = 0xFF800000u;
+        uint32_t cand[NSLOT];   // candidate score bits of the entry (node) in this lane and slot
+        float nsc[NSLOT];       // score of the entry's node
+        float nlp1[NSLOT];      // lp[row][c+1], prefetched: the increment of the next sibling
+        int meta[NSLOT];        // (c << 8) | row: current child rank and the children's row
 #pragma unroll
         for (int s = 0; s < NSLOT; ++s) {
-            cand[s] = -INFINITY;
+            cand[s] = kEmpty;
             nsc[s] = 0.0f;
             nlp1[s] = -INFINITY;
-            nlp2[s] = -INFINITY;
             meta[s] = 0;
         }
         if (lane == 0) {  // the root's entry: candidate = rank 0 of row 0
-            cand[0] = lp0;
+            cand[0] = __float_as_uint(lp0);
             nlp1[0] = lp1;
-            nlp2[0] = lp2;
         }
         int n = 0;
-        while (n < N) {
-            float lb = cand[0];
+        bool done = false;
 #pragma unroll
-            for (int s = 1; s < NSLOT; ++s) lb = fmaxf(lb, cand[s]);
-            const float wm = wave_max_f32(lb);
-            if (wm == -INFINITY) break;  // frontier empty: fewer than N prefixes exist
-            // which entries hold the maximum (one compare per slot, masks are wave-uniform)
-            unsigned long long eq[NSLOT];
-            int matches = 0;
+        for (int sn = 0; sn < NSLOT; ++sn) {  // register slot that receives the new nodes
+            for (int j = sn == 0 ? 1 : 0; j < 64 && !done; ++j) {
+                if (n >= N) {
+                    done = true;
+                    break;
+                }
+                uint32_t lb = cand[0];
 #pragma unroll
-            for (int s = 0; s < NSLOT; ++s) {
-                eq[s] = __ballot(cand[s] == wm);
-                matches += __popcll(eq[s]);
-            }
-            int ws = 0, wl = 0;
-            if (matches == 1) {
+                for (int s = 1; s < NSLOT; ++s) lb = min(lb, cand[s]);
+                const uint32_t wmb = wave_min_u32(lb);
+                if (wmb == kEmpty) {  // frontier empty: fewer than N prefixes exist
+                    done = true;
+                    break;
+                }
+                // which entries hold the best score (one compare per slot, wave-uniform masks)
+                unsigned long long eq[NSLOT];
+                int matches = 0;
+#pragma unroll
+                for (int s = 0; s < NSLOT; ++s) {
+                    eq[s] = __ballot(cand[s] == wmb);
+                    matches += __popcll(eq[s]);
+                }
+                int ws = 0, wl = 0;
 #pragma unroll
                 for (int s = 0; s < NSLOT; ++s)
                     if (eq[s]) {
                         ws = s;
                         wl = __ffsll((long long)eq[s]) - 1;
                     }
-            } else {
-                // slow path: several candidates share the best score
-                int bp = -1, bc = 0;
+                if (matches != 1) {
+                    // slow path: several candidates share the best score
+                    int bp = -1, bc = 0;
+#pragma unroll 1
+                    for (int s = 0; s < NSLOT; ++s) {
+                        unsigned long long mm = eq[s];
+                        while (mm) {
+                            const int l = __ffsll((long long)mm) - 1;
+                            mm &= mm - 1;
+                            const int p = s * 64 + l;
+                            int ms = 0;
 #pragma unroll
-                for (int s = 0; s < NSLOT; ++s) {
-                    unsigned long long mm = eq[s];
-                    while (mm) {
-                        const int l = __ffsll((long long)mm) - 1;
-                        mm &= mm - 1;
-                        const int p = s * 64 + l;
-                        const int c = __builtin_amdgcn_readlane(meta[s], l) >> 8;
-                        if (bp < 0 || tuple_before(s_node, p, c, bp, bc)) {
-                            bp = p;
-                            bc = c;
-                            ws = s;
-                            wl = l;
+                            for (int s2 = 0; s2 < NSLOT; ++s2)
+                                if (s2 == s) ms = __builtin_amdgcn_readlane(meta[s2], l);
+                            const int c = ms >> 8;
+                            if (bp < 0 || tuple_before(s_node, p, c, bp, bc)) {
+                                bp = p;
+                                bc = c;
+                                ws = s;
+                                wl = l;
+                            }
                         }
                     }
                 }
-            }
-            // the popped entry, read from its owner lane
-            float NS = 0.0f, NL = 0.0f;
-            int M = 0;
+                // pop: the winner lane updates its own entry in place (next sibling), the other
+                // lanes only need the entry's meta word
+                int M = 0;
+                const bool me = lane == wl;
 #pragma unroll
-            for (int s = 0; s < NSLOT; ++s)
-                if (ws == s) {
-                    NS = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(nsc[s]), wl));
-                    NL = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(nlp1[s]), wl));
-                    M = __builtin_amdgcn_readlane(meta[s], wl);
+                for (int s = 0; s < NSLOT; ++s)
+                    if (ws == s) {
+                        M = __builtin_amdgcn_readlane(meta[s], wl);
+                        if (me) {
+                            // next sibling: score(parent node) + lp[row][c+1]  (-inf once c+1 == K)
+                            cand[s] = __float_as_uint(nsc[s] + nlp1[s]);
+                            nlp1[s] = s_lp[(meta[s] & 0xFF) * Kp + (meta[s] >> 8) + 2];
+                            meta[s] += 256;
+                        }
+                    }
+                const int c = M >> 8, d = (M & 0xFF) + 1;  // rank and depth of the new node
+                const float wm = __uint_as_float(wmb);
+                ++n;
+                if (lane == 0) {
+                    s_node[n] = pack_node(ws * 64 + wl, c, d);
+                    s_score[n] = wm;
                 }
-            const int p = ws * 64 + wl;
-            const int c = M >> 8, row = M & 0xFF;
-            const int d = row + 1;  // depth of the new node
-            ++n;
-            if (lane == 0) {
-                s_node[n] = pack_node(p, c, d);
-                s_score[n] = wm;
-            }
-            // next sibling: score(parent node) + lp[row][c+1]   (-inf once c+1 == K)
-            const float sib = NS + NL;
-            // first child: score(new node) + lp[d][0]            (-inf once d == B)
-            const float ch = wm + __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lp0), d));
-            const float c1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lp1), d));
-            const float c2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lp2), d));
-            const int sn = n >> 6, ln = n & 63;
-#pragma unroll
-            for (int s = 0; s < NSLOT; ++s) {
-                if (ws == s && lane == wl) {
-                    cand[s] = sib;
-                    nlp1[s] = nlp2[s];
-                    nlp2[s] = s_lp[row * Kp + min(c + 3, Kp - 1)];
-                    meta[s] = M + 256;
-                }
-                if (sn == s && lane == ln) {
-                    cand[s] = ch;
-                    nsc[s] = wm;
-                    nlp1[s] = c1;
-                    nlp2[s] = c2;
-                    meta[s] = d;  // rank 0, children read row d
+                // first child of the new node: score + lp[d][0]   (-inf once d == B)
+                const float ch = wm + __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lp0), d));
+                const float c1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lp1), d));
+                if (lane == j) {  // node n = sn * 64 + j lives in this lane's slot sn
+                    cand[sn] = __float_as_uint(ch);
+                    nsc[sn] = wm;
+                    nlp1[sn] = c1;
+                    meta[sn] = d;  // rank 0, children read row d
                 }
             }
         }

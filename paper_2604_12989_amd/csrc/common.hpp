@@ -118,6 +118,23 @@ __device__ __forceinline__ float wave_max_f32(float v)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
+// Wave-wide minimum of an unsigned value over all 64 lanes (all lanes must be active).
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ uint32_t dpp_u(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, ROW_MASK, 0xF, false);
+}
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v)
+{
+    v = min(v, dpp_u<0xB1>(v));
+    v = min(v, dpp_u<0x4E>(v));
+    v = min(v, dpp_u<0x141>(v));
+    v = min(v, dpp_u<0x140>(v));
+    v = min(v, dpp_u<0x142, 0xA>(v));
+    v = min(v, dpp_u<0x143, 0xC>(v));
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
 __device__ __forceinline__ int lane_id() { return __lane_id(); }
 #endif
 
