@@ -12,7 +12,7 @@ DTYPE_BF16 = 0
 DTYPE_FP32 = 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libddtree.so")
+_LIB_PATH = os.environ.get("DDTREE_LIB", os.path.join(_HERE, "libddtree.so"))
 _lib = None
 
 _vp, _sz, _i = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int

@@ -30,6 +30,8 @@ namespace ddt {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kAttnThreads = 256;
 constexpr int kMT = 256;       // query rows per workgroup
@@ -38,6 +40,8 @@ constexpr int kHD = 128;       // head dim of the MFMA path
 constexpr int kKStride = kHD + 8;   // bf16 elements per K row in LDS (272 B)
 constexpr int kVStride = kHD + 16;  // bf16 elements per V row in LDS (288 B)
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kAttnStages = 2;
+constexpr int kAttnLdsBytes = kAttnStages * 2 * kKT * kHD * 2;  // stages x {K, V} x 16 KB
 
 struct AttnArgs {
     int32_t kv_offset[DDTREE_MAX_BATCH + 1];
@@ -89,18 +93,81 @@ __device__ __forceinline__ uint32_t f2bf_pair(float lo, float hi)
            ((uint32_t)__builtin_bit_cast(unsigned short, b) << 16);
 }
 
-typedef __attribute__((__vector_size__(4 * sizeof(short)))) short shortx4;
-
+// Reads of the K/V tiles are written as asm.  The tiles are filled by LDS-DMA
+// (global_load_lds); the compiler cannot tell which stage a given LDS read touches and would
+// wait for every outstanding tile load before each read, serialising prefetch and compute.  With
+// asm reads the waits are placed by hand: s_waitcnt vmcnt(0) + barrier once per tile for the
+// DMA, lds_wait() below for the reads.
+__device__ __forceinline__ u32x4 lds_rd128(uint32_t addr)
+{
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+    return v;
+}
+__device__ __forceinline__ u32x4 lds_rd128_8k(uint32_t addr)
+{
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1 offset:8192" : "=v"(v) : "v"(addr) : "memory");
+    return v;
+}
 // LDS transpose read (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane 4*j + r points
 // at four consecutive 16-bit elements; afterwards lane i of the group holds, for j = 0..3, element
 // i % 4 of what lane 4*j + i / 4 pointed at.  With lane 4*j + r pointing at V[key_j][d0 + 4*r ..],
 // lane i receives V[key_0..3][d0 + i]: a column of the row-major V tile, which is what the A
 // operand (V^T) of the second product needs.
-__device__ __forceinline__ uint2 lds_read_tr16(const uint16_t *p)
+__device__ __forceinline__ u32x2 lds_rdtr(uint32_t addr)
 {
-    const shortx4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (__attribute__((address_space(3))) shortx4 *)(p));
-    return __builtin_bit_cast(uint2, t);
+    u32x2 v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+    return v;
+}
+__device__ __forceinline__ u32x2 lds_rdtr_2k(uint32_t addr)
+{
+    u32x2 v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:2048" : "=v"(v) : "v"(addr) : "memory");
+    return v;
+}
+// Wait until every LDS read issued so far has returned; the operands tie the wait to the
+// registers it protects so that their uses cannot be scheduled above it.
+__device__ __forceinline__ void lds_wait(u32x4 &a, u32x4 &b)
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b) : : "memory");
+}
+__device__ __forceinline__ void lds_wait8(u32x2 (&v)[4][2])
+{
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[1][0]), "+v"(v[1][1]), "+v"(v[2][0]),
+                   "+v"(v[2][1]), "+v"(v[3][0]), "+v"(v[3][1])
+                 :
+                 : "memory");
+}
+
+// acc *= alpha when flag != 0 (flag is wave-uniform), in place in the accumulator registers.
+// The branch lives inside the asm so that, for the compiler, the accumulators flow straight
+// through: a C++ "if" around a VALU update makes it keep a second copy of all of them.
+__device__ __forceinline__ void scale_acc_if(floatx16 &acc, float alpha, int flag)
+{
+    float e0 = acc[0], e1 = acc[1], e2 = acc[2], e3 = acc[3], e4 = acc[4], e5 = acc[5], e6 = acc[6],
+          e7 = acc[7], e8 = acc[8], e9 = acc[9], e10 = acc[10], e11 = acc[11], e12 = acc[12],
+          e13 = acc[13], e14 = acc[14], e15 = acc[15];
+    float tmp;
+#define DDT_SC(n) "v_accvgpr_read_b32 %16, %" #n "\n\ts_nop 0\n\tv_mul_f32 %16, %16, %17\n\ts_nop 0\n\tv_accvgpr_write_b32 %" #n ", %16\n\t"
+    asm volatile("s_cmp_eq_u32 %18, 0\n\t"
+                 "s_cbranch_scc1 ddt_skip_%=\n\t"
+                 "s_nop 15\n\ts_nop 7\n\t"  // let matrix results land before reading them
+                 DDT_SC(0) DDT_SC(1) DDT_SC(2) DDT_SC(3) DDT_SC(4) DDT_SC(5) DDT_SC(6) DDT_SC(7)
+                 DDT_SC(8) DDT_SC(9) DDT_SC(10) DDT_SC(11) DDT_SC(12) DDT_SC(13) DDT_SC(14) DDT_SC(15)
+                 "s_nop 7\n"
+                 "ddt_skip_%=:"
+                 : "+a"(e0), "+a"(e1), "+a"(e2), "+a"(e3), "+a"(e4), "+a"(e5), "+a"(e6), "+a"(e7),
+                   "+a"(e8), "+a"(e9), "+a"(e10), "+a"(e11), "+a"(e12), "+a"(e13), "+a"(e14),
+                   "+a"(e15), "=&v"(tmp)
+                 : "v"(alpha), "s"(__builtin_amdgcn_readfirstlane(flag))
+                 : "scc");
+#undef DDT_SC
+    acc[0] = e0; acc[1] = e1; acc[2] = e2; acc[3] = e3; acc[4] = e4; acc[5] = e5; acc[6] = e6;
+    acc[7] = e7; acc[8] = e8; acc[9] = e9; acc[10] = e10; acc[11] = e11; acc[12] = e12;
+    acc[13] = e13; acc[14] = e14; acc[15] = e15;
 }
 
 constexpr float kRescaleThreshold = 8.0f;  // log2 units: stale running max tolerated up to 2^8
@@ -112,8 +179,13 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                       AttnArgs args, int T, int Hq, int Hkv, float scale_log2e, int splits,
                       uint16_t *__restrict__ out, float *__restrict__ part, float *__restrict__ part_lse)
 {
-    __shared__ __align__(16) uint16_t sK[kKT * kKStride];
-    __shared__ __align__(16) uint16_t sV[kKT * kVStride];
+    // LDS: kStages stages of {K tile, V tile}, each tile 64 keys x 256 B, filled by direct
+    // global->LDS loads (64 lanes x 16 B land contiguously, so a wave instruction fills 4 rows).
+    // Bank conflicts are avoided by swizzling the 16-byte column index per row: K stores column c
+    // of key r at position c ^ (r & 7), V at position c ^ (2 * (r & 3)).
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int kTileBytes = kKT * kHD * 2;      // 16 KB
+    constexpr int kStageBytes = 2 * kTileBytes;    // K then V
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
@@ -156,6 +228,8 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             if (rvalid[cb])
                 v = *reinterpret_cast<const uint4 *>(q + (size_t)rowg_[cb] * kHD + ks * 16 + half * 8);
             qreg[cb][ks] = __builtin_bit_cast(bf16x8, v);
+            // the query operand is only ever read by MFMA: park it in the accumulator file
+            asm volatile("" : "+a"(qreg[cb][ks]));
         }
 
     floatx16 o[4][2];
@@ -165,56 +239,71 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) o[db][cb][v] = 0.0f;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) asm volatile("" : "+a"(o[db][cb]));
     float m_run[2] = {-INFINITY, -INFINITY};  // reference maximum (may lag the true one)
     float l_run[2] = {0.0f, 0.0f};
 
-    // global -> register -> LDS staging: thread owns chunk (key = tid/16 + 16*r, 16-byte column tid%16)
-    const int st_key = tid >> 4, st_ch = tid & 15;
+    // ---- tile loads: wave w, instruction i fills rows 4*(4*i + w) .. +3 of the K and V tiles;
+    //      lane -> (row in block = lane / 16, position = lane % 16) ----
     const size_t rs = (size_t)Hkv * kHD;  // elements between consecutive keys in global memory
-    uint4 kst[4], vst[4];
-#define DDT_LOAD_TILE(t_)                                                                       \
-    do {                                                                                        \
-        const int tt = (t_);                                                                    \
-        const uint16_t *kp, *vp;                                                                \
-        int valid_;                                                                             \
-        if (tt < n_cache_tiles) {                                                               \
-            const size_t row0 = (size_t)L0 + (size_t)tt * kKT;                                  \
-            kp = k_cache + (row0 * Hkv + hk) * kHD;                                             \
-            vp = v_cache + (row0 * Hkv + hk) * kHD;                                             \
-            valid_ = min(kKT, L - tt * kKT);                                                    \
-        } else {                                                                                \
-            const size_t row0 = (size_t)seq * T + (size_t)(tt - n_cache_tiles) * kKT;           \
-            kp = k_tree + (row0 * Hkv + hk) * kHD;                                              \
-            vp = v_tree + (row0 * Hkv + hk) * kHD;                                              \
-            valid_ = min(kKT, T - (tt - n_cache_tiles) * kKT);                                  \
-        }                                                                                       \
-        _Pragma("unroll") for (int r = 0; r < 4; ++r) {                                         \
-            const int key = st_key + 16 * r;                                                    \
-            const bool ok = key < valid_;                                                       \
-            kst[r] = ok ? *reinterpret_cast<const uint4 *>(kp + key * rs + st_ch * 8)           \
-                        : make_uint4(0, 0, 0, 0);                                               \
-            vst[r] = ok ? *reinterpret_cast<const uint4 *>(vp + key * rs + st_ch * 8)           \
-                        : make_uint4(0, 0, 0, 0);                                               \
-        }                                                                                       \
-    } while (0)
-
-    // per-lane LDS read bases (elements)
-    const int k_base = l32 * kKStride + half * 8;
-    const int lm = lane & 15, dim16 = (lane >> 4) & 1;
-    const int v_base = (4 * half + (lm >> 2)) * kVStride + 16 * dim16 + 4 * (lm & 3);
-
-    if (t_begin < t_end) DDT_LOAD_TILE(t_begin);
-    for (int t = t_begin; t < t_end; ++t) {
-        __syncthreads();
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int key = st_key + 16 * r;
-            *reinterpret_cast<uint4 *>(&sK[key * kKStride + st_ch * 8]) = kst[r];
-            *reinterpret_cast<uint4 *>(&sV[key * kVStride + st_ch * 8]) = vst[r];
+    const int ld_r4 = lane >> 4, ld_pos = lane & 15;
+    auto issue_tile = [&](int tt, int stage) {
+        const uint16_t *kp, *vp;
+        int valid_;
+        if (tt < n_cache_tiles) {
+            const size_t row0 = (size_t)L0 + (size_t)tt * kKT;
+            kp = k_cache + (row0 * Hkv + hk) * kHD;
+            vp = v_cache + (row0 * Hkv + hk) * kHD;
+            valid_ = min(kKT, L - tt * kKT);
+        } else {
+            const size_t row0 = (size_t)seq * T + (size_t)(tt - n_cache_tiles) * kKT;
+            kp = k_tree + (row0 * Hkv + hk) * kHD;
+            vp = v_tree + (row0 * Hkv + hk) * kHD;
+            valid_ = min(kKT, T - (tt - n_cache_tiles) * kKT);
         }
-        __syncthreads();
-        if (t + 1 < t_end) DDT_LOAD_TILE(t + 1);
-        if (!wave_active) continue;
+        unsigned char *st = smem + stage * kStageBytes;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int blk = 4 * i + wave;
+            const int r = 4 * blk + ld_r4;
+            const int rsrc = min(r, valid_ - 1);  // rows past the end re-read a valid row (finite data)
+            const int ck = ld_pos ^ (r & 7);
+            const int cv = ld_pos ^ (2 * (r & 3));
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(kp + rsrc * rs + ck * 8),
+                (__attribute__((address_space(3))) void *)(st + blk * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(vp + rsrc * rs + cv * 8),
+                (__attribute__((address_space(3))) void *)(st + kTileBytes + blk * 1024), 16, 0, 0);
+        }
+    };
+
+    // per-lane LDS read offsets (bytes, relative to the tile), one per compile-time column group
+    int k_off[8];  // K: row l32 (+32*kb), column 2*ks + half
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) k_off[ks] = l32 * 256 + (((2 * ks + half) ^ (l32 & 7)) << 4);
+    const int lm = lane & 15, dim16 = (lane >> 4) & 1;
+    const int vj = lm >> 2, vr = lm & 3;
+    int v_off[4];  // V: row 4*half + vj (+16*kstep, +8), column 4*db + 2*dim16 + vr/2, 8-byte half vr%2
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+        v_off[db] = (4 * half + vj) * 256 + (((4 * db + 2 * dim16 + (vr >> 1)) ^ (2 * vj)) << 4) + 8 * (vr & 1);
+
+    const uint32_t lds_base =
+        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+
+    if (t_begin < t_end) issue_tile(t_begin, 0);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    for (int t = t_begin; t < t_end; ++t) {
+        const int stage = (t - t_begin) & 1;
+        if (t + 1 < t_end) issue_tile(t + 1, stage ^ 1);
+        if (wave_active) {
+        const uint32_t sK_addr = lds_base + stage * kStageBytes;
+        const uint32_t sV_addr = sK_addr + kTileBytes;
 
         const bool is_tree = t >= n_cache_tiles;
         const int tb = t - n_cache_tiles;
@@ -228,16 +317,27 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) s[kb][cb][v] = 0.0f;
+        {
+            u32x4 ka[2][2];  // [buffer][kb]: operands of k-step ks + 1 are in flight during step ks
+            ka[0][0] = lds_rd128(sK_addr + k_off[0]);
+            ka[0][1] = lds_rd128_8k(sK_addr + k_off[0]);
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
+            for (int ks = 0; ks < 8; ++ks) {
+                const int cur = ks & 1;
+                lds_wait(ka[cur][0], ka[cur][1]);
+                if (ks + 1 < 8) {
+                    ka[cur ^ 1][0] = lds_rd128(sK_addr + k_off[ks + 1]);
+                    ka[cur ^ 1][1] = lds_rd128_8k(sK_addr + k_off[ks + 1]);
+                }
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(
-                    &sK[k_base + kb * 32 * kKStride + ks * 16]);
+                for (int kb = 0; kb < 2; ++kb) {
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, ka[cur][kb]);
 #pragma unroll
-                for (int cb = 0; cb < 2; ++cb)
-                    s[kb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[cb][ks], s[kb][cb], 0, 0, 0);
+                    for (int cb = 0; cb < 2; ++cb)
+                        s[kb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[cb][ks], s[kb][cb], 0, 0, 0);
+                }
             }
+        }
 
         // ---- mask (tree tiles and a ragged last cache tile only) ----
         if (is_tree || valid < kKT) {
@@ -272,18 +372,17 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         // The running reference is only moved when some row's maximum grew by more than the
         // threshold (always the case on a row's first visible key); otherwise exp2 arguments
         // stay below the threshold and nothing has to be rescaled.
-        if (__builtin_expect(__any((m_new[0] > m_run[0] + kRescaleThreshold) | (m_new[1] > m_run[1] + kRescaleThreshold)), 0)) {
+        const int resc = __any((m_new[0] > m_run[0] + kRescaleThreshold) |
+                               (m_new[1] > m_run[1] + kRescaleThreshold));
 #pragma unroll
-            for (int cb = 0; cb < 2; ++cb) {
-                const float m_use = m_new[cb] == -INFINITY ? 0.0f : m_new[cb];
-                const float alpha = __builtin_amdgcn_exp2f(m_run[cb] - m_use);  // 0 when m_run = -inf
-                m_run[cb] = m_new[cb];
-                l_run[cb] *= alpha;
+        for (int cb = 0; cb < 2; ++cb) {
+            const float m_tgt = resc ? m_new[cb] : m_run[cb];
+            const float m_use = m_tgt == -INFINITY ? 0.0f : m_tgt;
+            const float alpha = __builtin_amdgcn_exp2f(m_run[cb] - m_use);  // exactly 1 when kept
+            m_run[cb] = m_tgt;
+            l_run[cb] *= alpha;
 #pragma unroll
-                for (int db = 0; db < 4; ++db)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) o[db][cb][v] *= alpha;
-            }
+            for (int db = 0; db < 4; ++db) scale_acc_if(o[db][cb], alpha, resc);
         }
         bf16x8 pb[2][4];
 #pragma unroll
@@ -313,20 +412,38 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 
         // ---- O^T += V^T P^T.  Element j of the P^T operand of k-step kst is key
         //      16*kst + 8*(j/4) + 4*half + j%4; the two transpose reads fetch exactly those keys ----
-#pragma unroll
-        for (int kst4 = 0; kst4 < 4; ++kst4)
+        {
+            u32x2 va[2][4][2];  // [buffer][db][low / high four keys]
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
-                const uint16_t *vp = &sV[v_base + kst4 * 16 * kVStride + db * 32];
-                const uint2 lo = lds_read_tr16(vp);
-                const uint2 hi = lds_read_tr16(vp + 8 * kVStride);
-                const bf16x8 a = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
-#pragma unroll
-                for (int cb = 0; cb < 2; ++cb)
-                    o[db][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[cb][kst4], o[db][cb], 0, 0, 0);
+                va[0][db][0] = lds_rdtr(sV_addr + v_off[db]);
+                va[0][db][1] = lds_rdtr_2k(sV_addr + v_off[db]);
             }
+#pragma unroll
+            for (int kst4 = 0; kst4 < 4; ++kst4) {
+                const int cur = kst4 & 1;
+                lds_wait8(va[cur]);
+                if (kst4 + 1 < 4) {
+#pragma unroll
+                    for (int db = 0; db < 4; ++db) {
+                        va[cur ^ 1][db][0] = lds_rdtr(sV_addr + v_off[db] + (kst4 + 1) * 4096);
+                        va[cur ^ 1][db][1] = lds_rdtr_2k(sV_addr + v_off[db] + (kst4 + 1) * 4096);
+                    }
+                }
+#pragma unroll
+                for (int db = 0; db < 4; ++db) {
+                    const bf16x8 a = __builtin_bit_cast(
+                        bf16x8, (u32x4){va[cur][db][0].x, va[cur][db][0].y, va[cur][db][1].x, va[cur][db][1].y});
+#pragma unroll
+                    for (int cb = 0; cb < 2; ++cb)
+                        o[db][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[cb][kst4], o[db][cb], 0, 0, 0);
+                }
+            }
+        }
+        }
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
     }
-#undef DDT_LOAD_TILE
 
     if (!wave_active) return;
     // ---- epilogue ----
@@ -534,8 +651,15 @@ extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void
         if (!ws_ok(workspace, workspace_bytes, p.bytes)) return DDTREE_ERR_WORKSPACE;
         float *part = p.splits > 1 ? reinterpret_cast<float *>(static_cast<char *>(workspace) + p.part_off) : nullptr;
         float *lse = p.splits > 1 ? reinterpret_cast<float *>(static_cast<char *>(workspace) + p.lse_off) : nullptr;
-        DDT_LAUNCH(DDTREE_KERNEL_ATTN, st, attn_mfma_kernel, dim3(p.splits, p.mtiles * Hkv, batch), dim3(kAttnThreads), 0,
-                           st, static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(k_cache),
+        static bool attr_set = false;
+        if (!attr_set) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(attn_mfma_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsBytes) != hipSuccess)
+                return DDTREE_ERR_HIP;
+            attr_set = true;
+        }
+        DDT_LAUNCH(DDTREE_KERNEL_ATTN, st, attn_mfma_kernel, dim3(p.splits, p.mtiles * Hkv, batch), dim3(kAttnThreads),
+                           kAttnLdsBytes, st, static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(k_cache),
                            static_cast<const uint16_t *>(v_cache), static_cast<const uint16_t *>(k_tree),
                            static_cast<const uint16_t *>(v_tree), ancestor_mask, args, T, Hq, Hkv,
                            softmax_scale * kLog2e, p.splits, static_cast<uint16_t *>(out), part, lse);
