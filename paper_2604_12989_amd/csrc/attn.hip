@@ -18,8 +18,9 @@
 //                 they stand, the B operand of the next product (no cross-lane movement).
 //   O^T += V^T P^T  A = V^T, gathered from the row-major V tile in LDS by the transposing
 //                 LDS read, in the key order the P^T registers happen to have.
-// The running maximum is a lagging reference: accumulators are rescaled only when a row's
-// maximum grows by more than 2^8, so the steady state has no rescale work at all.
+// The softmax reference of a row is fixed by its first visible key, so the accumulators are
+// never rescaled; a row whose scores outgrow its reference by more than 2^64 (rare) makes the
+// workgroup redo its key range once with the true row maxima as references.
 // K and V tiles sit in LDS as [key][dim], rows padded (272 B / 288 B) so that the 16-byte K
 // reads and the transposing V reads are free of bank conflicts.
 // The ancestor mask touches only the tree tiles (the last ceil(T/64) tiles): one 64-bit word per
@@ -40,8 +41,13 @@ constexpr int kHD = 128;       // head dim of the MFMA path
 constexpr int kKStride = kHD + 8;   // bf16 elements per K row in LDS (272 B)
 constexpr int kVStride = kHD + 16;  // bf16 elements per V row in LDS (288 B)
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr int kAttnStages = 2;
-constexpr int kAttnLdsBytes = kAttnStages * 2 * kKT * kHD * 2;  // stages x {K, V} x 16 KB
+constexpr int kAttnStages = 3;
+constexpr int kKRowBytes = 272;                  // K tile row in LDS: 256 B + 16 B pad (17 chunks)
+constexpr int kVRowBytes = 288;                  // V tile row in LDS: 256 B + 32 B pad (18 chunks)
+constexpr int kKTileBytes = kKT * kKRowBytes;    // 17408 = 17 DMA blocks of 1 KB
+constexpr int kVTileBytes = kKT * kVRowBytes;    // 18432 = 18 DMA blocks of 1 KB
+constexpr int kStageBytes = kKTileBytes + kVTileBytes;
+constexpr int kAttnLdsBytes = kAttnStages * kStageBytes;
 
 struct AttnArgs {
     int32_t kv_offset[DDTREE_MAX_BATCH + 1];
@@ -93,21 +99,32 @@ __device__ __forceinline__ uint32_t f2bf_pair(float lo, float hi)
            ((uint32_t)__builtin_bit_cast(unsigned short, b) << 16);
 }
 
+// Compile-time loop: f(IC<B>{}), ..., f(IC<E-1>{}); the index is a constant expression inside f,
+// as the immediate operands of the asm helpers below require.
+template <int N>
+struct IC {
+    static constexpr int value = N;
+};
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (B < E) {
+        f(IC<B>{});
+        static_for<B + 1, E>(f);
+    }
+}
+
 // Reads of the K/V tiles are written as asm.  The tiles are filled by LDS-DMA
 // (global_load_lds); the compiler cannot tell which stage a given LDS read touches and would
 // wait for every outstanding tile load before each read, serialising prefetch and compute.  With
 // asm reads the waits are placed by hand: s_waitcnt vmcnt(0) + barrier once per tile for the
-// DMA, lds_wait() below for the reads.
+// DMA, lds_wait_*() below for the reads (LDS reads return in order, so "at most N outstanding"
+// identifies exactly which of them have landed).
+template <int OFF>
 __device__ __forceinline__ u32x4 lds_rd128(uint32_t addr)
 {
     u32x4 v;
-    asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
-    return v;
-}
-__device__ __forceinline__ u32x4 lds_rd128_8k(uint32_t addr)
-{
-    u32x4 v;
-    asm volatile("ds_read_b128 %0, %1 offset:8192" : "=v"(v) : "v"(addr) : "memory");
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
     return v;
 }
 // LDS transpose read (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane 4*j + r points
@@ -115,62 +132,37 @@ __device__ __forceinline__ u32x4 lds_rd128_8k(uint32_t addr)
 // i % 4 of what lane 4*j + i / 4 pointed at.  With lane 4*j + r pointing at V[key_j][d0 + 4*r ..],
 // lane i receives V[key_0..3][d0 + i]: a column of the row-major V tile, which is what the A
 // operand (V^T) of the second product needs.
+template <int OFF>
 __device__ __forceinline__ u32x2 lds_rdtr(uint32_t addr)
 {
     u32x2 v;
-    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
     return v;
 }
-__device__ __forceinline__ u32x2 lds_rdtr_2k(uint32_t addr)
+// Wait until at most N LDS reads are outstanding; the operands tie the wait to the registers it
+// protects so that their uses cannot be scheduled above it.
+template <int N>
+__device__ __forceinline__ void lds_wait_k(u32x4 (&k)[8])
 {
-    u32x2 v;
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:2048" : "=v"(v) : "v"(addr) : "memory");
-    return v;
+    asm volatile("s_waitcnt lgkmcnt(%8)"
+                 : "+v"(k[0]), "+v"(k[1]), "+v"(k[2]), "+v"(k[3]), "+v"(k[4]), "+v"(k[5]), "+v"(k[6]),
+                   "+v"(k[7])
+                 : "n"(N)
+                 : "memory");
 }
-// Wait until every LDS read issued so far has returned; the operands tie the wait to the
-// registers it protects so that their uses cannot be scheduled above it.
-__device__ __forceinline__ void lds_wait(u32x4 &a, u32x4 &b)
+template <int N>
+__device__ __forceinline__ void lds_wait_v(u32x2 (&v)[2][4][2])
 {
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b) : : "memory");
-}
-__device__ __forceinline__ void lds_wait8(u32x2 (&v)[4][2])
-{
-    asm volatile("s_waitcnt lgkmcnt(0)"
-                 : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[1][0]), "+v"(v[1][1]), "+v"(v[2][0]),
-                   "+v"(v[2][1]), "+v"(v[3][0]), "+v"(v[3][1])
-                 :
+    asm volatile("s_waitcnt lgkmcnt(%16)"
+                 : "+v"(v[0][0][0]), "+v"(v[0][0][1]), "+v"(v[0][1][0]), "+v"(v[0][1][1]),
+                   "+v"(v[0][2][0]), "+v"(v[0][2][1]), "+v"(v[0][3][0]), "+v"(v[0][3][1]),
+                   "+v"(v[1][0][0]), "+v"(v[1][0][1]), "+v"(v[1][1][0]), "+v"(v[1][1][1]),
+                   "+v"(v[1][2][0]), "+v"(v[1][2][1]), "+v"(v[1][3][0]), "+v"(v[1][3][1])
+                 : "n"(N)
                  : "memory");
 }
 
-// acc *= alpha when flag != 0 (flag is wave-uniform), in place in the accumulator registers.
-// The branch lives inside the asm so that, for the compiler, the accumulators flow straight
-// through: a C++ "if" around a VALU update makes it keep a second copy of all of them.
-__device__ __forceinline__ void scale_acc_if(floatx16 &acc, float alpha, int flag)
-{
-    float e0 = acc[0], e1 = acc[1], e2 = acc[2], e3 = acc[3], e4 = acc[4], e5 = acc[5], e6 = acc[6],
-          e7 = acc[7], e8 = acc[8], e9 = acc[9], e10 = acc[10], e11 = acc[11], e12 = acc[12],
-          e13 = acc[13], e14 = acc[14], e15 = acc[15];
-    float tmp;
-#define DDT_SC(n) "v_accvgpr_read_b32 %16, %" #n "\n\ts_nop 0\n\tv_mul_f32 %16, %16, %17\n\ts_nop 0\n\tv_accvgpr_write_b32 %" #n ", %16\n\t"
-    asm volatile("s_cmp_eq_u32 %18, 0\n\t"
-                 "s_cbranch_scc1 ddt_skip_%=\n\t"
-                 "s_nop 15\n\ts_nop 7\n\t"  // let matrix results land before reading them
-                 DDT_SC(0) DDT_SC(1) DDT_SC(2) DDT_SC(3) DDT_SC(4) DDT_SC(5) DDT_SC(6) DDT_SC(7)
-                 DDT_SC(8) DDT_SC(9) DDT_SC(10) DDT_SC(11) DDT_SC(12) DDT_SC(13) DDT_SC(14) DDT_SC(15)
-                 "s_nop 7\n"
-                 "ddt_skip_%=:"
-                 : "+a"(e0), "+a"(e1), "+a"(e2), "+a"(e3), "+a"(e4), "+a"(e5), "+a"(e6), "+a"(e7),
-                   "+a"(e8), "+a"(e9), "+a"(e10), "+a"(e11), "+a"(e12), "+a"(e13), "+a"(e14),
-                   "+a"(e15), "=&v"(tmp)
-                 : "v"(alpha), "s"(__builtin_amdgcn_readfirstlane(flag))
-                 : "scc");
-#undef DDT_SC
-    acc[0] = e0; acc[1] = e1; acc[2] = e2; acc[3] = e3; acc[4] = e4; acc[5] = e5; acc[6] = e6;
-    acc[7] = e7; acc[8] = e8; acc[9] = e9; acc[10] = e10; acc[11] = e11; acc[12] = e12;
-    acc[13] = e13; acc[14] = e14; acc[15] = e15;
-}
-
-constexpr float kRescaleThreshold = 8.0f;  // log2 units: stale running max tolerated up to 2^8
+constexpr float kRefSlack = 64.0f;  // log2 units a row's scores may exceed its softmax reference
 
 __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_cache,
@@ -179,13 +171,13 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                       AttnArgs args, int T, int Hq, int Hkv, float scale_log2e, int splits,
                       uint16_t *__restrict__ out, float *__restrict__ part, float *__restrict__ part_lse)
 {
-    // LDS: kStages stages of {K tile, V tile}, each tile 64 keys x 256 B, filled by direct
-    // global->LDS loads (64 lanes x 16 B land contiguously, so a wave instruction fills 4 rows).
-    // Bank conflicts are avoided by swizzling the 16-byte column index per row: K stores column c
-    // of key r at position c ^ (r & 7), V at position c ^ (2 * (r & 3)).
+    // LDS: kAttnStages stages of {K tile, V tile}, filled by direct global->LDS loads.  One wave
+    // instruction writes 64 x 16 B contiguously, but every lane may fetch any 16-byte chunk, so
+    // the tiles keep a padded row-major layout: K rows of 17 chunks (272 B), V rows of 18 chunks
+    // (288 B); the lanes that land on padding fetch a dummy chunk.  With these strides the 16-byte
+    // K reads and the transposing V reads are free of bank conflicts and every read address is
+    // one per-lane base plus an immediate.
     extern __shared__ __align__(16) unsigned char smem[];
-    constexpr int kTileBytes = kKT * kHD * 2;      // 16 KB
-    constexpr int kStageBytes = 2 * kTileBytes;    // K then V
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
@@ -239,18 +231,15 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) o[db][cb][v] = 0.0f;
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb) asm volatile("" : "+a"(o[db][cb]));
-    float m_run[2] = {-INFINITY, -INFINITY};  // reference maximum (may lag the true one)
+    float m_run[2] = {-INFINITY, -INFINITY};   // softmax reference of the row (log2 units)
+    float m_seen[2] = {-INFINITY, -INFINITY};  // true running maximum of the row
     float l_run[2] = {0.0f, 0.0f};
+    bool overflow = false;
 
-    // ---- tile loads: wave w, instruction i fills rows 4*(4*i + w) .. +3 of the K and V tiles;
-    //      lane -> (row in block = lane / 16, position = lane % 16) ----
+    // ---- tile loads: DMA block b (1 KB of LDS) is issued by wave b % 4; lane l of the block fills
+    //      16-byte slot u = 64*b + l, i.e. row u / chunks_per_row, chunk u % chunks_per_row ----
     const size_t rs = (size_t)Hkv * kHD;  // elements between consecutive keys in global memory
-    const int ld_r4 = lane >> 4, ld_pos = lane & 15;
-    auto issue_tile = [&](int tt, int stage) {
+    auto issue_tile = [&](int tt, int stage) __attribute__((always_inline)) {
         const uint16_t *kp, *vp;
         int valid_;
         if (tt < n_cache_tiles) {
@@ -266,183 +255,221 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         }
         unsigned char *st = smem + stage * kStageBytes;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 5; ++i) {
             const int blk = 4 * i + wave;
-            const int r = 4 * blk + ld_r4;
-            const int rsrc = min(r, valid_ - 1);  // rows past the end re-read a valid row (finite data)
-            const int ck = ld_pos ^ (r & 7);
-            const int cv = ld_pos ^ (2 * (r & 3));
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void *)(kp + rsrc * rs + ck * 8),
-                (__attribute__((address_space(3))) void *)(st + blk * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void *)(vp + rsrc * rs + cv * 8),
-                (__attribute__((address_space(3))) void *)(st + kTileBytes + blk * 1024), 16, 0, 0);
+            const int u = blk * 64 + lane;
+            if (blk < 17) {  // K: 17 chunks per row
+                int r = (u * 241) >> 12;  // u / 17 for u < 2048
+                int c = u - r * 17;
+                r = min(r, valid_ - 1);   // rows past the end re-read a valid row (finite data)
+                c = c == 16 ? 0 : c;      // padding slot: any in-bounds chunk
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void *)(kp + r * rs + c * 8),
+                    (__attribute__((address_space(3))) void *)(st + blk * 1024), 16, 0, 0);
+            }
+            if (blk < 18) {  // V: 18 chunks per row
+                int r = (u * 3641) >> 16;  // u / 18 for u < 2048
+                int c = u - r * 18;
+                r = min(r, valid_ - 1);
+                c = c >= 16 ? 0 : c;
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void *)(vp + r * rs + c * 8),
+                    (__attribute__((address_space(3))) void *)(st + kKTileBytes + blk * 1024), 16, 0, 0);
+            }
         }
     };
 
-    // per-lane LDS read offsets (bytes, relative to the tile), one per compile-time column group
-    int k_off[8];  // K: row l32 (+32*kb), column 2*ks + half
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) k_off[ks] = l32 * 256 + (((2 * ks + half) ^ (l32 & 7)) << 4);
+    // per-lane LDS read bases (bytes, relative to the tile); everything else is an immediate
+    const int k_base = l32 * kKRowBytes + half * 16;  // K: row l32 (+32*kb), column 2*ks + half
     const int lm = lane & 15, dim16 = (lane >> 4) & 1;
-    const int vj = lm >> 2, vr = lm & 3;
-    int v_off[4];  // V: row 4*half + vj (+16*kstep, +8), column 4*db + 2*dim16 + vr/2, 8-byte half vr%2
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-        v_off[db] = (4 * half + vj) * 256 + (((4 * db + 2 * dim16 + (vr >> 1)) ^ (2 * vj)) << 4) + 8 * (vr & 1);
+    // V: row 4*half + lm/4 (+16*kstep, +8), dims 32*db + 16*dim16 + 4*(lm%4)
+    const int v_base = (4 * half + (lm >> 2)) * kVRowBytes + 32 * dim16 + 8 * (lm & 3);
 
     const uint32_t lds_base =
         (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    const int n_tiles = t_end - t_begin;
 
-    if (t_begin < t_end) issue_tile(t_begin, 0);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    for (int t = t_begin; t < t_end; ++t) {
-        const int stage = (t - t_begin) & 1;
-        if (t + 1 < t_end) issue_tile(t + 1, stage ^ 1);
-        if (wave_active) {
-        const uint32_t sK_addr = lds_base + stage * kStageBytes;
-        const uint32_t sV_addr = sK_addr + kTileBytes;
+    // Operand staging registers: K rows of one 32-key sub-tile (8 k-steps over the head dim) and
+    // V columns of one sub-tile (2 k-steps x 4 dim blocks x 2 transposing reads).
+    u32x4 kbuf[8];
+    u32x2 vbuf[2][4][2];
+    floatx16 sc[2];     // scores of the sub-tile in flight, per query block cb
+    bf16x8 pb[2][2][2];  // P^T operands, double buffered by sub-tile parity: [parity][cb][k-step]
 
+    // K operand reads of sub-tile kb of the tile at LDS address tile_addr
+    auto issue_k = [&](uint32_t tile_addr, auto KB) __attribute__((always_inline)) {
+        static_for<0, 8>([&](auto KS) {
+            kbuf[KS.value] = lds_rd128<decltype(KB)::value * 32 * kKRowBytes + KS.value * 32>(tile_addr);
+        });
+    };
+    // V operand reads of sub-tile kb: key rows 32*kb + 16*t2 + 4*half + vj (+8)
+    auto issue_v = [&](uint32_t tile_addr, auto KB) __attribute__((always_inline)) {
+        static_for<0, 2>([&](auto T2) {
+            static_for<0, 4>([&](auto DB) {
+                constexpr int off = (2 * decltype(KB)::value + T2.value) * 16 * kVRowBytes + DB.value * 64;
+                vbuf[T2.value][DB.value][0] = lds_rdtr<off>(tile_addr);
+                vbuf[T2.value][DB.value][1] = lds_rdtr<off + 8 * kVRowBytes>(tile_addr);
+            });
+        });
+    };
+    // S^T sub-tile = K Q^T from the staged K operands
+    auto qk = [&](floatx16 (&sd)[2]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sd[cb][v] = 0.0f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            const bf16x8 a = __builtin_bit_cast(bf16x8, kbuf[ks]);
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb)
+                sd[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[cb][ks], sd[cb], 0, 0, 0);
+        }
+    };
+    // Mask + online softmax of one sub-tile (32 keys): sd -> pb, updating m_run / l_run and,
+    // flagging rows that outgrow their reference.  kb selects the half of the tile's mask word.
+    auto softmax = [&](floatx16 (&sd)[2], int t, int kb, bf16x8 (&pout)[2][2]) __attribute__((always_inline)) {
         const bool is_tree = t >= n_cache_tiles;
         const int tb = t - n_cache_tiles;
         const int valid = is_tree ? min(kKT, T - tb * kKT) : min(kKT, L - t * kKT);
-
-        // ---- S^T = K Q^T ----
-        floatx16 s[2][2];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) s[kb][cb][v] = 0.0f;
-        {
-            u32x4 ka[2][2];  // [buffer][kb]: operands of k-step ks + 1 are in flight during step ks
-            ka[0][0] = lds_rd128(sK_addr + k_off[0]);
-            ka[0][1] = lds_rd128_8k(sK_addr + k_off[0]);
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                const int cur = ks & 1;
-                lds_wait(ka[cur][0], ka[cur][1]);
-                if (ks + 1 < 8) {
-                    ka[cur ^ 1][0] = lds_rd128(sK_addr + k_off[ks + 1]);
-                    ka[cur ^ 1][1] = lds_rd128_8k(sK_addr + k_off[ks + 1]);
-                }
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-                    const bf16x8 a = __builtin_bit_cast(bf16x8, ka[cur][kb]);
-#pragma unroll
-                    for (int cb = 0; cb < 2; ++cb)
-                        s[kb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[cb][ks], s[kb][cb], 0, 0, 0);
-                }
-            }
-        }
-
-        // ---- mask (tree tiles and a ragged last cache tile only) ----
-        if (is_tree || valid < kKT) {
+        if (is_tree || valid < kKT) {  // tree tiles and a ragged last cache tile only
 #pragma unroll
             for (int cb = 0; cb < 2; ++cb) {
                 uint64_t word = ~0ull;
-                if (is_tree)
-                    word = rvalid[cb] ? mask[((size_t)seq * T + node_[cb]) * W + tb] : 0ull;
+                if (is_tree) word = rvalid[cb] ? mask[((size_t)seq * T + node_[cb]) * W + tb] : 0ull;
                 if (valid < kKT) word &= (1ull << valid) - 1ull;
+                const uint32_t w32 = (uint32_t)(word >> (32 * kb));
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int key = kb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-                        if (!((word >> key) & 1ull)) s[kb][cb][v] = -INFINITY;
-                    }
+                for (int v = 0; v < 16; ++v) {
+                    const int key = (v >> 2) * 8 + half * 4 + (v & 3);
+                    if (!((w32 >> key) & 1u)) sd[cb][v] = -INFINITY;
+                }
             }
         }
-
-        // ---- online softmax, one query row per lane and cb, lazily rescaled ----
-        float m_new[2];
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
-            float tmax = s[0][cb][0];
+            float tmax = sd[cb][0];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, s[kb][cb][v]);
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-            m_new[cb] = fmaxf(m_run[cb], tmax * scale_log2e);
-        }
-        // The running reference is only moved when some row's maximum grew by more than the
-        // threshold (always the case on a row's first visible key); otherwise exp2 arguments
-        // stay below the threshold and nothing has to be rescaled.
-        const int resc = __any((m_new[0] > m_run[0] + kRescaleThreshold) |
-                               (m_new[1] > m_run[1] + kRescaleThreshold));
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-            const float m_tgt = resc ? m_new[cb] : m_run[cb];
-            const float m_use = m_tgt == -INFINITY ? 0.0f : m_tgt;
-            const float alpha = __builtin_amdgcn_exp2f(m_run[cb] - m_use);  // exactly 1 when kept
-            m_run[cb] = m_tgt;
-            l_run[cb] *= alpha;
-#pragma unroll
-            for (int db = 0; db < 4; ++db) scale_acc_if(o[db][cb], alpha, resc);
-        }
-        bf16x8 pb[2][4];
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
+            for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, sd[cb][v]);
+            // the other half-wave holds the other 16 keys of this row
+            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax),
+                                                             false, false);
+            tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+            // The softmax reference of a row is fixed by its first visible key and never moved, so
+            // the accumulators are never rescaled: exp2 arguments may become positive, which
+            // fp32 and bf16 carry exactly as well as negative ones.  Only a row whose scores
+            // outgrow the reference by more than kRefSlack makes the workgroup redo its key
+            // range once, with the true maxima as references (see the retry loop).
+            m_seen[cb] = fmaxf(m_seen[cb], tmax * scale_log2e);
+            m_run[cb] = m_run[cb] == -INFINITY ? m_seen[cb] : m_run[cb];
+            overflow |= m_seen[cb] > m_run[cb] + kRefSlack;
             const float m_use = m_run[cb] == -INFINITY ? 0.0f : m_run[cb];
             float psum = 0.0f;
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const float p = __builtin_amdgcn_exp2f(fmaf(s[kb][cb][v], scale_log2e, -m_use));
-                    s[kb][cb][v] = p;
-                    psum += p;
-                }
-#pragma unroll
-                for (int t2 = 0; t2 < 2; ++t2) {
-                    uint4 pk;
-                    pk.x = f2bf_pair(s[kb][cb][8 * t2 + 0], s[kb][cb][8 * t2 + 1]);
-                    pk.y = f2bf_pair(s[kb][cb][8 * t2 + 2], s[kb][cb][8 * t2 + 3]);
-                    pk.z = f2bf_pair(s[kb][cb][8 * t2 + 4], s[kb][cb][8 * t2 + 5]);
-                    pk.w = f2bf_pair(s[kb][cb][8 * t2 + 6], s[kb][cb][8 * t2 + 7]);
-                    pb[cb][kb * 2 + t2] = __builtin_bit_cast(bf16x8, pk);
-                }
+            for (int v = 0; v < 16; ++v) {
+                const float p = __builtin_amdgcn_exp2f(fmaf(sd[cb][v], scale_log2e, -m_use));
+                sd[cb][v] = p;
+                psum += p;
             }
             l_run[cb] += psum;
+#pragma unroll
+            for (int t2 = 0; t2 < 2; ++t2) {
+                u32x4 pk;
+                pk.x = f2bf_pair(sd[cb][8 * t2 + 0], sd[cb][8 * t2 + 1]);
+                pk.y = f2bf_pair(sd[cb][8 * t2 + 2], sd[cb][8 * t2 + 3]);
+                pk.z = f2bf_pair(sd[cb][8 * t2 + 4], sd[cb][8 * t2 + 5]);
+                pk.w = f2bf_pair(sd[cb][8 * t2 + 6], sd[cb][8 * t2 + 7]);
+                pout[cb][t2] = __builtin_bit_cast(bf16x8, pk);
+            }
         }
-
-        // ---- O^T += V^T P^T.  Element j of the P^T operand of k-step kst is key
-        //      16*kst + 8*(j/4) + 4*half + j%4; the two transpose reads fetch exactly those keys ----
-        {
-            u32x2 va[2][4][2];  // [buffer][db][low / high four keys]
+    };
+    // O^T += V^T P^T for one sub-tile.  Element j of the P^T operand of k-step t2 is key
+    // 16*t2 + 8*(j/4) + 4*half + j%4 of the sub-tile; the two transposing reads fetched those keys.
+    auto pv = [&](bf16x8 (&pin)[2][2]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
-                va[0][db][0] = lds_rdtr(sV_addr + v_off[db]);
-                va[0][db][1] = lds_rdtr_2k(sV_addr + v_off[db]);
+                const bf16x8 a = __builtin_bit_cast(
+                    bf16x8, (u32x4){vbuf[t2][db][0].x, vbuf[t2][db][0].y, vbuf[t2][db][1].x, vbuf[t2][db][1].y});
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb)
+                    o[db][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pin[cb][t2], o[db][cb], 0, 0, 0);
             }
-#pragma unroll
-            for (int kst4 = 0; kst4 < 4; ++kst4) {
-                const int cur = kst4 & 1;
-                lds_wait8(va[cur]);
-                if (kst4 + 1 < 4) {
-#pragma unroll
-                    for (int db = 0; db < 4; ++db) {
-                        va[cur ^ 1][db][0] = lds_rdtr(sV_addr + v_off[db] + (kst4 + 1) * 4096);
-                        va[cur ^ 1][db][1] = lds_rdtr_2k(sV_addr + v_off[db] + (kst4 + 1) * 4096);
-                    }
-                }
-#pragma unroll
-                for (int db = 0; db < 4; ++db) {
-                    const bf16x8 a = __builtin_bit_cast(
-                        bf16x8, (u32x4){va[cur][db][0].x, va[cur][db][0].y, va[cur][db][1].x, va[cur][db][1].y});
-#pragma unroll
-                    for (int cb = 0; cb < 2; ++cb)
-                        o[db][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[cb][kst4], o[db][cb], 0, 0, 0);
-                }
-            }
-        }
-        }
+    };
+
+    // ---- software pipeline over 32-key sub-tiles j = (tile, half), three LDS stages ----
+    // The matrix cores alternate between the scores of sub-tile j and the P V product of sub-tile
+    // j-1; the vector ALUs do the softmax of sub-tile j while that P V product runs:
+    //   A: S = K Q^T of (t, 0)
+    //   B: O += P V of (t-1, 1)   ||  softmax of (t, 0)
+    //   -- tile t+1 has landed (vmcnt + barrier); tile t+2 is requested into the stage that
+    //      (t-1) occupied, whose last reader was phase B
+    //   C: S = K Q^T of (t, 1)
+    //   D: O += P V of (t, 0)     ||  softmax of (t, 1)
+    // LDS operands are requested one phase before the product that consumes them.
+    for (;;) {
+        if (n_tiles > 0) issue_tile(t_begin, 0);
+        if (n_tiles > 1) issue_tile(t_begin + 1, 1);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
+        if (wave_active && n_tiles > 0) issue_k(lds_base + k_base, IC<0>{});
+        for (int it = 0; it < n_tiles; ++it) {
+            const int t = t_begin + it;
+            const int st = it % kAttnStages;
+            const uint32_t stage_addr = lds_base + st * kStageBytes;
+            const uint32_t prev_addr = lds_base + ((it + kAttnStages - 1) % kAttnStages) * kStageBytes;
+            // when there is no next tile the K operands are re-read from this one and never used:
+            // the control flow stays the same for the last tile
+            const uint32_t next_addr =
+                it + 1 < n_tiles ? lds_base + ((it + 1) % kAttnStages) * kStageBytes : stage_addr;
+            if (wave_active) {
+                // ---- A ----
+                lds_wait_k<0>(kbuf);
+                if (it > 0) issue_v(prev_addr + kKTileBytes + v_base, IC<1>{});
+                qk(sc);
+                // ---- B ----
+                if (it > 0) lds_wait_v<0>(vbuf);
+                issue_k(stage_addr + k_base, IC<1>{});
+                if (it > 0) pv(pb[1]);
+                softmax(sc, t, 0, pb[0]);
+            }
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile t+1 is in LDS
+            __syncthreads();
+            if (it + 2 < n_tiles) issue_tile(t + 2, (it + 2) % kAttnStages);
+            if (wave_active) {
+                // ---- C ----
+                lds_wait_k<0>(kbuf);
+                issue_v(stage_addr + kKTileBytes + v_base, IC<0>{});
+                qk(sc);
+                // ---- D ----
+                lds_wait_v<0>(vbuf);
+                issue_k(next_addr + k_base, IC<0>{});
+                pv(pb[0]);
+                softmax(sc, t, 1, pb[1]);
+            }
+        }
+        if (wave_active && n_tiles > 0) {
+            // drain: P V of the last sub-tile
+            lds_wait_k<0>(kbuf);
+            const uint32_t last_addr = lds_base + ((n_tiles - 1) % kAttnStages) * kStageBytes;
+            issue_v(last_addr + kKTileBytes + v_base, IC<1>{});
+            lds_wait_v<0>(vbuf);
+            pv(pb[1]);
+        }
+        // Retry (rare): some row outgrew its reference.  All tiles have been seen, so m_seen holds
+        // the true row maxima; with those as references the second pass cannot outgrow anything.
+        if (!__syncthreads_or(overflow ? 1 : 0)) break;
+        overflow = false;
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            m_run[cb] = m_seen[cb];
+            l_run[cb] = 0.0f;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[db][cb][v] = 0.0f;
+        }
     }
 
     if (!wave_active) return;
