@@ -15,7 +15,7 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed fp32 instructions are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-ffp-contract=off", "-Wall", "-Wno-unused-variable",
+    "-ffp-contract=off", "-fno-honor-nans", "-Wall", "-Wno-unused-variable",
 ]
 
 

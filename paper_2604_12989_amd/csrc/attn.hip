@@ -92,11 +92,13 @@ size_t attn_ws_upper(int batch, int T, int Hq, int Hkv, int D)
 
 __device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xFFFFu) | (b << 16); }
 __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xFFFF0000u); }
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+// two floats -> packed bf16 pair (round to nearest even), one v_cvt_pk_bf16_f32
 __device__ __forceinline__ uint32_t f2bf_pair(float lo, float hi)
 {
-    const __bf16 a = (__bf16)lo, b = (__bf16)hi;
-    return (uint32_t)__builtin_bit_cast(unsigned short, a) |
-           ((uint32_t)__builtin_bit_cast(unsigned short, b) << 16);
+    const floatx2 f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
 }
 
 // Compile-time loop: f(IC<B>{}), ..., f(IC<E-1>{}); the index is a constant expression inside f,
@@ -237,43 +239,50 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     bool overflow = false;
 
     // ---- tile loads: DMA block b (1 KB of LDS) is issued by wave b % 4; lane l of the block fills
-    //      16-byte slot u = 64*b + l, i.e. row u / chunks_per_row, chunk u % chunks_per_row ----
-    const size_t rs = (size_t)Hkv * kHD;  // elements between consecutive keys in global memory
+    //      16-byte slot u = 64*b + l, i.e. row u / chunks_per_row, chunk u % chunks_per_row.
+    //      The per-lane source offsets (bytes from the tile's first key) are computed once. ----
+    const uint32_t row_bytes = (uint32_t)Hkv * kHD * 2;  // bytes between consecutive keys in global memory
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    uint32_t k_src[5], v_src[5];   // block 4*i + wave
+    int k_row[5], v_row[5];
+#pragma unroll
+    for (int i = 0; i < 5; ++i) {
+        const int u = (4 * i + wave) * 64 + lane;
+        const int rk = (u * 241) >> 12;   // u / 17 for u < 2048
+        const int ck = u - rk * 17;
+        k_row[i] = rk;
+        k_src[i] = (uint32_t)rk * row_bytes + (ck == 16 ? 0 : ck) * 16;  // padding slot: any chunk
+        const int rv = (u * 3641) >> 16;  // u / 18 for u < 2048
+        const int cv = u - rv * 18;
+        v_row[i] = rv;
+        v_src[i] = (uint32_t)rv * row_bytes + (cv >= 16 ? 0 : cv) * 16;
+    }
     auto issue_tile = [&](int tt, int stage) __attribute__((always_inline)) {
-        const uint16_t *kp, *vp;
-        int valid_;
-        if (tt < n_cache_tiles) {
-            const size_t row0 = (size_t)L0 + (size_t)tt * kKT;
-            kp = k_cache + (row0 * Hkv + hk) * kHD;
-            vp = v_cache + (row0 * Hkv + hk) * kHD;
-            valid_ = min(kKT, L - tt * kKT);
-        } else {
-            const size_t row0 = (size_t)seq * T + (size_t)(tt - n_cache_tiles) * kKT;
-            kp = k_tree + (row0 * Hkv + hk) * kHD;
-            vp = v_tree + (row0 * Hkv + hk) * kHD;
-            valid_ = min(kKT, T - (tt - n_cache_tiles) * kKT);
-        }
+        const bool cache = tt < n_cache_tiles;
+        const int tl = cache ? tt : tt - n_cache_tiles;
+        const size_t row0 = (cache ? (size_t)L0 : (size_t)seq * T) + (size_t)tl * kKT;
+        const unsigned char *kp =
+            reinterpret_cast<const unsigned char *>((cache ? k_cache : k_tree) + (row0 * Hkv + hk) * kHD);
+        const unsigned char *vp =
+            reinterpret_cast<const unsigned char *>((cache ? v_cache : v_tree) + (row0 * Hkv + hk) * kHD);
+        const int valid_ = min(kKT, (cache ? L : T) - tl * kKT);
         unsigned char *st = smem + stage * kStageBytes;
+        const bool ragged = valid_ < kKT;  // rows past the end re-read the last valid row (finite data)
 #pragma unroll
         for (int i = 0; i < 5; ++i) {
-            const int blk = 4 * i + wave;
-            const int u = blk * 64 + lane;
-            if (blk < 17) {  // K: 17 chunks per row
-                int r = (u * 241) >> 12;  // u / 17 for u < 2048
-                int c = u - r * 17;
-                r = min(r, valid_ - 1);   // rows past the end re-read a valid row (finite data)
-                c = c == 16 ? 0 : c;      // padding slot: any in-bounds chunk
+            const int blk = 4 * i + wave_u;
+            if (i < 4 || wave_u < 1) {  // K: 17 blocks
+                uint32_t off = k_src[i];
+                if (ragged && k_row[i] >= valid_) off -= (uint32_t)(k_row[i] - (valid_ - 1)) * row_bytes;
                 __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)(kp + r * rs + c * 8),
+                    (const __attribute__((address_space(1))) void *)(kp + off),
                     (__attribute__((address_space(3))) void *)(st + blk * 1024), 16, 0, 0);
             }
-            if (blk < 18) {  // V: 18 chunks per row
-                int r = (u * 3641) >> 16;  // u / 18 for u < 2048
-                int c = u - r * 18;
-                r = min(r, valid_ - 1);
-                c = c >= 16 ? 0 : c;
+            if (i < 4 || wave_u < 2) {  // V: 18 blocks
+                uint32_t off = v_src[i];
+                if (ragged && v_row[i] >= valid_) off -= (uint32_t)(v_row[i] - (valid_ - 1)) * row_bytes;
                 __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)(vp + r * rs + c * 8),
+                    (const __attribute__((address_space(1))) void *)(vp + off),
                     (__attribute__((address_space(3))) void *)(st + kKTileBytes + blk * 1024), 16, 0, 0);
             }
         }
@@ -325,6 +334,8 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             for (int cb = 0; cb < 2; ++cb)
                 sd[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[cb][ks], sd[cb], 0, 0, 0);
         }
+        // the scores are consumed by the vector ALUs: keep them out of the accumulation registers
+        asm volatile("" : "+v"(sd[0]), "+v"(sd[1]));
     };
     // Mask + online softmax of one sub-tile (32 keys): sd -> pb, updating m_run / l_run and,
     // flagging rows that outgrow their reference.  kb selects the half of the tile's mask word.
@@ -414,15 +425,16 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
         if (wave_active && n_tiles > 0) issue_k(lds_base + k_base, IC<0>{});
+        int st = 0;  // LDS stage of tile `it` (it % kAttnStages, kept without a division)
         for (int it = 0; it < n_tiles; ++it) {
             const int t = t_begin + it;
-            const int st = it % kAttnStages;
+            const int st_prev = st == 0 ? kAttnStages - 1 : st - 1;
+            const int st_next = st == kAttnStages - 1 ? 0 : st + 1;
             const uint32_t stage_addr = lds_base + st * kStageBytes;
-            const uint32_t prev_addr = lds_base + ((it + kAttnStages - 1) % kAttnStages) * kStageBytes;
+            const uint32_t prev_addr = lds_base + st_prev * kStageBytes;
             // when there is no next tile the K operands are re-read from this one and never used:
             // the control flow stays the same for the last tile
-            const uint32_t next_addr =
-                it + 1 < n_tiles ? lds_base + ((it + 1) % kAttnStages) * kStageBytes : stage_addr;
+            const uint32_t next_addr = it + 1 < n_tiles ? lds_base + st_next * kStageBytes : stage_addr;
             if (wave_active) {
                 // ---- A ----
                 lds_wait_k<0>(kbuf);
@@ -436,7 +448,7 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             }
             __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile t+1 is in LDS
             __syncthreads();
-            if (it + 2 < n_tiles) issue_tile(t + 2, (it + 2) % kAttnStages);
+            if (it + 2 < n_tiles) issue_tile(t + 2, st_prev);  // (it + 2) % 3 == (it - 1) % 3
             if (wave_active) {
                 // ---- C ----
                 lds_wait_k<0>(kbuf);
@@ -448,11 +460,12 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                 pv(pb[0]);
                 softmax(sc, t, 1, pb[1]);
             }
+            st = st_next;
         }
         if (wave_active && n_tiles > 0) {
             // drain: P V of the last sub-tile
             lds_wait_k<0>(kbuf);
-            const uint32_t last_addr = lds_base + ((n_tiles - 1) % kAttnStages) * kStageBytes;
+            const uint32_t last_addr = lds_base + (st == 0 ? kAttnStages - 1 : st - 1) * kStageBytes;
             issue_v(last_addr + kKTileBytes + v_base, IC<1>{});
             lds_wait_v<0>(vbuf);
             pv(pb[1]);
