@@ -56,30 +56,41 @@ struct AttnArgs {
 AttnPlan attn_plan(int batch, int T, int Hq, int Hkv, int D, long long sum_L, int dtype)
 {
     AttnPlan p{};
-    p.splits = 1;
-    p.mtiles = 0;
-    p.bytes = 0;
+    p.s_main = p.s_tail = 1;
     if (!(dtype == DDTREE_DTYPE_BF16 && D == kHD)) return p;  // generic path needs no scratch
     const int G = Hq / Hkv;
     const long long M = (long long)T * G;
-    p.mtiles = (int)((M + kMT - 1) / kMT);
-    const long long full = M / kMT > 0 ? M / kMT : 1;
-    const long long base = (long long)batch * Hkv * full;
-    int S;
-    if (base >= 512) S = 1;
-    else if (base >= 256) S = 2;
-    else S = (int)((256 + base - 1) / base);
-    // keep at least four tiles per split on average
-    const long long tiles = (sum_L / batch + T) / kKT;
-    if ((long long)S * 4 > tiles) S = (int)(tiles / 4 > 0 ? tiles / 4 : 1);
-    if (S > 32) S = 32;
-    p.splits = S;
-    if (S > 1) {
-        const size_t rows = (size_t)batch * T * Hq;
-        p.part_off = 0;
-        p.lse_off = align_up((size_t)S * rows * D * 4, 256);
-        p.bytes = align_up(p.lse_off + (size_t)S * rows * 4, 256);
+    p.n_full = (int)(M / kMT);
+    p.tail_rows = (int)(M % kMT);
+    const long long tiles = (sum_L / batch + T) / kKT;  // key tiles per sequence, roughly
+    const long long groups = (long long)batch * Hkv;
+    if (p.n_full > 0) {
+        const long long base = groups * p.n_full;  // full-tile workgroups per split
+        int S = base >= 384 ? 1 : (int)((256 + base - 1) / base);
+        if ((long long)S * 4 > tiles) S = (int)(tiles / 4 > 0 ? tiles / 4 : 1);  // >= 4 tiles per split
+        p.s_main = S > 32 ? 32 : S;
     }
+    if (p.tail_rows > 0) {
+        int S = (int)((256 + groups - 1) / groups);
+        if ((long long)S * 2 > tiles) S = (int)(tiles / 2 > 0 ? tiles / 2 : 1);  // >= 2 tiles per split
+        p.s_tail = S > 64 ? 64 : S;
+    }
+    size_t off = 0;
+    if (p.n_full > 0 && p.s_main > 1) {
+        const size_t rows = (size_t)batch * T * Hq;  // indexed by global row
+        p.part_main_off = off;
+        off = align_up(off + (size_t)p.s_main * rows * D * 4, 256);
+        p.lse_main_off = off;
+        off = align_up(off + (size_t)p.s_main * rows * 4, 256);
+    }
+    if (p.tail_rows > 0 && p.s_tail > 1) {
+        const size_t rows = (size_t)groups * p.tail_rows;  // compact tail-row index
+        p.part_tail_off = off;
+        off = align_up(off + (size_t)p.s_tail * rows * D * 4, 256);
+        p.lse_tail_off = off;
+        off = align_up(off + (size_t)p.s_tail * rows * 4, 256);
+    }
+    p.bytes = off;
     return p;
 }
 
@@ -170,8 +181,10 @@ __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(1,
 void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_cache,
                       const uint16_t *__restrict__ v_cache, const uint16_t *__restrict__ k_tree,
                       const uint16_t *__restrict__ v_tree, const uint64_t *__restrict__ mask,
-                      AttnArgs args, int T, int Hq, int Hkv, float scale_log2e, int splits,
-                      uint16_t *__restrict__ out, float *__restrict__ part, float *__restrict__ part_lse)
+                      AttnArgs args, int batch_n, int T, int Hq, int Hkv, float scale_log2e, int n_full,
+                      int s_main, int s_tail, uint16_t *__restrict__ out, float *__restrict__ part_main,
+                      float *__restrict__ lse_main, float *__restrict__ part_tail,
+                      float *__restrict__ lse_tail)
 {
     // LDS: kAttnStages stages of {K tile, V tile}, filled by direct global->LDS loads.  One wave
     // instruction writes 64 x 16 B contiguously, but every lane may fetch any 16-byte chunk, so
@@ -183,9 +196,21 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
-    const int split = blockIdx.x;
-    const int hk = blockIdx.y % Hkv, mt = blockIdx.y / Hkv;
-    const int seq = blockIdx.z;
+    // 1-D grid, dispatched in order: first every full-tile workgroup (split fastest, so that
+    // consecutive workgroups -- which land on different XCDs -- work on different key ranges and
+    // the workgroups of one XCD share theirs), then the short tail-tile workgroups, which fill
+    // the compute units as the long ones drain.
+    const int groups = Hkv * batch_n;                    // (sequence, kv head) pairs
+    const int n_main = groups * n_full * s_main;
+    const bool is_tail = (int)blockIdx.x >= n_main;
+    const int splits = is_tail ? s_tail : s_main;
+    const int wid = is_tail ? (int)blockIdx.x - n_main : (int)blockIdx.x;
+    const int split = wid % splits;
+    const int rest = wid / splits;                        // (row tile, group)
+    const int mt = is_tail ? n_full : rest % n_full;
+    const int grp = is_tail ? rest : rest / n_full;
+    const int hk = grp % Hkv;
+    const int seq = grp / Hkv;
     const int G = Hq / Hkv;
     const int W = (T + 63) >> 6;
     const int M = T * G;
@@ -244,17 +269,14 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     const uint32_t row_bytes = (uint32_t)Hkv * kHD * 2;  // bytes between consecutive keys in global memory
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     uint32_t k_src[5], v_src[5];   // block 4*i + wave
-    int k_row[5], v_row[5];
 #pragma unroll
     for (int i = 0; i < 5; ++i) {
         const int u = (4 * i + wave) * 64 + lane;
         const int rk = (u * 241) >> 12;   // u / 17 for u < 2048
         const int ck = u - rk * 17;
-        k_row[i] = rk;
         k_src[i] = (uint32_t)rk * row_bytes + (ck == 16 ? 0 : ck) * 16;  // padding slot: any chunk
         const int rv = (u * 3641) >> 16;  // u / 18 for u < 2048
         const int cv = u - rv * 18;
-        v_row[i] = rv;
         v_src[i] = (uint32_t)rv * row_bytes + (cv >= 16 ? 0 : cv) * 16;
     }
     auto issue_tile = [&](int tt, int stage) __attribute__((always_inline)) {
@@ -267,23 +289,43 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             reinterpret_cast<const unsigned char *>((cache ? v_cache : v_tree) + (row0 * Hkv + hk) * kHD);
         const int valid_ = min(kKT, (cache ? L : T) - tl * kKT);
         unsigned char *st = smem + stage * kStageBytes;
-        const bool ragged = valid_ < kKT;  // rows past the end re-read the last valid row (finite data)
+        if (valid_ == kKT) {
 #pragma unroll
-        for (int i = 0; i < 5; ++i) {
-            const int blk = 4 * i + wave_u;
-            if (i < 4 || wave_u < 1) {  // K: 17 blocks
-                uint32_t off = k_src[i];
-                if (ragged && k_row[i] >= valid_) off -= (uint32_t)(k_row[i] - (valid_ - 1)) * row_bytes;
+            for (int i = 0; i < 4; ++i) {
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kp + k_src[i]),
+                                                 (__attribute__((address_space(3))) void *)(st + (4 * i + wave_u) * 1024),
+                                                 16, 0, 0);
                 __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)(kp + off),
-                    (__attribute__((address_space(3))) void *)(st + blk * 1024), 16, 0, 0);
+                    (const __attribute__((address_space(1))) void *)(vp + v_src[i]),
+                    (__attribute__((address_space(3))) void *)(st + kKTileBytes + (4 * i + wave_u) * 1024), 16, 0, 0);
             }
-            if (i < 4 || wave_u < 2) {  // V: 18 blocks
-                uint32_t off = v_src[i];
-                if (ragged && v_row[i] >= valid_) off -= (uint32_t)(v_row[i] - (valid_ - 1)) * row_bytes;
+            if (wave_u < 1)  // K: 17 blocks
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kp + k_src[4]),
+                                                 (__attribute__((address_space(3))) void *)(st + 16 * 1024), 16, 0, 0);
+            if (wave_u < 2)  // V: 18 blocks
                 __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)(vp + off),
-                    (__attribute__((address_space(3))) void *)(st + kKTileBytes + blk * 1024), 16, 0, 0);
+                    (const __attribute__((address_space(1))) void *)(vp + v_src[4]),
+                    (__attribute__((address_space(3))) void *)(st + kKTileBytes + (16 + wave_u) * 1024), 16, 0, 0);
+        } else {
+            // ragged tile (at most two per key range): rows past the end re-read the last valid
+            // row, so that the LDS tile holds finite data everywhere
+#pragma unroll 1
+            for (int i = 0; i < 5; ++i) {
+                const int blk = 4 * i + wave_u;
+                const int u = blk * 64 + lane;
+                if (blk < 17) {
+                    const int r = (u * 241) >> 12, c = u - r * 17;
+                    const uint32_t off = (uint32_t)min(r, valid_ - 1) * row_bytes + (c == 16 ? 0 : c) * 16;
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kp + off),
+                                                     (__attribute__((address_space(3))) void *)(st + blk * 1024), 16, 0, 0);
+                }
+                if (blk < 18) {
+                    const int r = (u * 3641) >> 16, c = u - r * 18;
+                    const uint32_t off = (uint32_t)min(r, valid_ - 1) * row_bytes + (c >= 16 ? 0 : c) * 16;
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void *)(vp + off),
+                        (__attribute__((address_space(3))) void *)(st + kKTileBytes + blk * 1024), 16, 0, 0);
+                }
             }
         }
     };
@@ -334,12 +376,11 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             for (int cb = 0; cb < 2; ++cb)
                 sd[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[cb][ks], sd[cb], 0, 0, 0);
         }
-        // the scores are consumed by the vector ALUs: keep them out of the accumulation registers
-        asm volatile("" : "+v"(sd[0]), "+v"(sd[1]));
     };
-    // Mask + online softmax of one sub-tile (32 keys): sd -> pb, updating m_run / l_run and,
-    // flagging rows that outgrow their reference.  kb selects the half of the tile's mask word.
-    auto softmax = [&](floatx16 (&sd)[2], int t, int kb, bf16x8 (&pout)[2][2]) __attribute__((always_inline)) {
+    // Mask (apply_mask: tree tiles and ragged ends only; kb selects the half of the tile's 64-bit
+    // mask word) and softmax of one sub-tile (32 keys): sd -> P^T operands, updating m_run /
+    // l_run and flagging rows that outgrow their reference.
+    auto apply_mask = [&](floatx16 (&sd)[2], int t, int kb) __attribute__((always_inline)) {
         const bool is_tree = t >= n_cache_tiles;
         const int tb = t - n_cache_tiles;
         const int valid = is_tree ? min(kKT, T - tb * kKT) : min(kKT, L - t * kKT);
@@ -357,6 +398,8 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                 }
             }
         }
+    };
+    auto softmax = [&](floatx16 (&sd)[2], bf16x8 (&pout)[2][2]) __attribute__((always_inline)) {
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
             float tmax = sd[cb][0];
@@ -375,23 +418,23 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             m_run[cb] = m_run[cb] == -INFINITY ? m_seen[cb] : m_run[cb];
             overflow |= m_seen[cb] > m_run[cb] + kRefSlack;
             const float m_use = m_run[cb] == -INFINITY ? 0.0f : m_run[cb];
+            // p = 2^(s*scale - reference), rounded to bf16 in pairs; the row sum is taken over
+            // the rounded values (the same ones that multiply V) with one dot2 per pair
             float psum = 0.0f;
+            uint32_t pk[8];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(sd[cb][v], scale_log2e, -m_use));
-                sd[cb][v] = p;
-                psum += p;
+            for (int v2 = 0; v2 < 8; ++v2) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(sd[cb][2 * v2], scale_log2e, -m_use));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(sd[cb][2 * v2 + 1], scale_log2e, -m_use));
+                pk[v2] = f2bf_pair(p0, p1);
+                psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk[v2]),
+                                                       __builtin_bit_cast(bf16x2, 0x3f803f80u), psum, false);
             }
             l_run[cb] += psum;
 #pragma unroll
-            for (int t2 = 0; t2 < 2; ++t2) {
-                u32x4 pk;
-                pk.x = f2bf_pair(sd[cb][8 * t2 + 0], sd[cb][8 * t2 + 1]);
-                pk.y = f2bf_pair(sd[cb][8 * t2 + 2], sd[cb][8 * t2 + 3]);
-                pk.z = f2bf_pair(sd[cb][8 * t2 + 4], sd[cb][8 * t2 + 5]);
-                pk.w = f2bf_pair(sd[cb][8 * t2 + 6], sd[cb][8 * t2 + 7]);
-                pout[cb][t2] = __builtin_bit_cast(bf16x8, pk);
-            }
+            for (int t2 = 0; t2 < 2; ++t2)
+                pout[cb][t2] = __builtin_bit_cast(
+                    bf16x8, (u32x4){pk[4 * t2], pk[4 * t2 + 1], pk[4 * t2 + 2], pk[4 * t2 + 3]});
         }
     };
     // O^T += V^T P^T for one sub-tile.  Element j of the P^T operand of k-step t2 is key
@@ -409,6 +452,16 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             }
     };
 
+    // Scheduling request for the phases that pair a P V product with a softmax: one matrix
+    // instruction, then a dozen vector instructions, sixteen times, so that the vector work runs
+    // in the shadow of the matrix pipeline instead of after it.
+    auto interleave_mfma_valu = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x002, 13, 0);  // VALU
+        }
+    };
     // ---- software pipeline over 32-key sub-tiles j = (tile, half), three LDS stages ----
     // The matrix cores alternate between the scores of sub-tile j and the P V product of sub-tile
     // j-1; the vector ALUs do the softmax of sub-tile j while that P V product runs:
@@ -425,6 +478,10 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
         if (wave_active && n_tiles > 0) issue_k(lds_base + k_base, IC<0>{});
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int t2 = 0; t2 < 2; ++t2) pb[1][cb][t2] = __builtin_bit_cast(bf16x8, (u32x4){0u, 0u, 0u, 0u});
         int st = 0;  // LDS stage of tile `it` (it % kAttnStages, kept without a division)
         for (int it = 0; it < n_tiles; ++it) {
             const int t = t_begin + it;
@@ -438,13 +495,17 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             if (wave_active) {
                 // ---- A ----
                 lds_wait_k<0>(kbuf);
-                if (it > 0) issue_v(prev_addr + kKTileBytes + v_base, IC<1>{});
+                // the first tile has no predecessor: its P operands are zero and the V operands
+                // are read from the tile itself, so that 0 * V is a plain zero
+                issue_v((it > 0 ? prev_addr : stage_addr) + kKTileBytes + v_base, IC<1>{});
                 qk(sc);
+                apply_mask(sc, t, 0);
                 // ---- B ----
-                if (it > 0) lds_wait_v<0>(vbuf);
+                lds_wait_v<0>(vbuf);
                 issue_k(stage_addr + k_base, IC<1>{});
-                if (it > 0) pv(pb[1]);
-                softmax(sc, t, 0, pb[0]);
+                pv(pb[1]);
+                softmax(sc, pb[0]);
+                interleave_mfma_valu();
             }
             __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile t+1 is in LDS
             __syncthreads();
@@ -454,11 +515,13 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                 lds_wait_k<0>(kbuf);
                 issue_v(stage_addr + kKTileBytes + v_base, IC<0>{});
                 qk(sc);
+                apply_mask(sc, t, 1);
                 // ---- D ----
                 lds_wait_v<0>(vbuf);
                 issue_k(next_addr + k_base, IC<0>{});
                 pv(pb[0]);
-                softmax(sc, t, 1, pb[1]);
+                softmax(sc, pb[1]);
+                interleave_mfma_valu();
             }
             st = st_next;
         }
@@ -507,8 +570,12 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                     *reinterpret_cast<uint2 *>(dst + dim) = val;
                 }
         } else {
-            const size_t rows_total = (size_t)gridDim.z * T * Hq;
-            float *dst = part + ((size_t)split * rows_total + rowg_[cb]) * kHD;
+            // partial result of this split: normalised O and log2-sum-exp; main rows are indexed
+            // by global row, tail rows compactly by (sequence, kv head, row in tail)
+            const size_t n_rows = is_tail ? (size_t)batch_n * Hkv * (M - n_full * kMT) : (size_t)batch_n * T * Hq;
+            const size_t ridx = is_tail ? ((size_t)seq * Hkv + hk) * (M - n_full * kMT) + (wave * 64 + cb * 32 + l32)
+                                        : (size_t)rowg_[cb];
+            float *dst = (is_tail ? part_tail : part_main) + ((size_t)split * n_rows + ridx) * kHD;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -522,31 +589,47 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                     *reinterpret_cast<float4 *>(dst + dim) = val;
                 }
             if (half == 0)
-                part_lse[(size_t)split * rows_total + rowg_[cb]] =
+                (is_tail ? lse_tail : lse_main)[(size_t)split * n_rows + ridx] =
                     inv > 0.0f ? m_run[cb] + __builtin_amdgcn_logf(l_tot) : -INFINITY;
         }
     }
 }
 
-// Merge of the split-KV partials: out = sum_s 2^(lse_s - max) O_s / sum_s 2^(lse_s - max).
-__global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict__ part,
-                                                         const float *__restrict__ part_lse,
-                                                         int splits, size_t rows_total,
-                                                         uint16_t *__restrict__ out)
+// Merge of the split-KV partials: out = sum_s 2^(lse_s - max) O_s / sum_s 2^(lse_s - max), for
+// the rows whose tile was split (main rows when s_main > 1, tail rows when s_tail > 1).
+__global__ __launch_bounds__(256) void attn_merge_kernel(
+    const float *__restrict__ part_main, const float *__restrict__ lse_main,
+    const float *__restrict__ part_tail, const float *__restrict__ lse_tail, int batch, int T, int Hq,
+    int Hkv, int n_full, int s_main, int s_tail, uint16_t *__restrict__ out)
 {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;  // (row, 4-dim group)
+    const size_t rows_total = (size_t)batch * T * Hq;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;  // (global row, 4-dim group)
     const size_t row = idx / (kHD / 4);
     const int dg = (int)(idx % (kHD / 4));
     if (row >= rows_total) return;
+    const int G = Hq / Hkv;
+    const int h = (int)(row % Hq);
+    const size_t sn = row / Hq;  // seq * T + node
+    const int node = (int)(sn % T), seq = (int)(sn / T);
+    const int hk = h / G, g = h - hk * G;
+    const int r = node * G + g;  // row within the (sequence, kv head) group
+    const bool is_tail = r >= n_full * kMT;
+    const int splits = is_tail ? s_tail : s_main;
+    if (splits == 1) return;  // written directly by the attention kernel
+    const int tail_rows = T * G - n_full * kMT;
+    const size_t n_rows = is_tail ? (size_t)batch * Hkv * tail_rows : rows_total;
+    const size_t ridx = is_tail ? ((size_t)seq * Hkv + hk) * tail_rows + (r - n_full * kMT) : row;
+    const float *part = is_tail ? part_tail : part_main;
+    const float *lse = is_tail ? lse_tail : lse_main;
     float mx = -INFINITY;
-    for (int s = 0; s < splits; ++s) mx = fmaxf(mx, part_lse[(size_t)s * rows_total + row]);
+    for (int s = 0; s < splits; ++s) mx = fmaxf(mx, lse[(size_t)s * n_rows + ridx]);
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float wsum = 0.0f;
     if (mx > -INFINITY) {
         for (int s = 0; s < splits; ++s) {
-            const float w = __builtin_amdgcn_exp2f(part_lse[(size_t)s * rows_total + row] - mx);
+            const float w = __builtin_amdgcn_exp2f(lse[(size_t)s * n_rows + ridx] - mx);
             const float4 v =
-                *reinterpret_cast<const float4 *>(part + ((size_t)s * rows_total + row) * kHD + dg * 4);
+                *reinterpret_cast<const float4 *>(part + ((size_t)s * n_rows + ridx) * kHD + dg * 4);
             acc.x += w * v.x;
             acc.y += w * v.y;
             acc.z += w * v.z;
@@ -689,8 +772,11 @@ extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void
     if (dtype == DDTREE_DTYPE_BF16 && D == kHD) {
         AttnPlan p = attn_plan(batch, T, Hq, Hkv, D, sum_L, dtype);
         if (!ws_ok(workspace, workspace_bytes, p.bytes)) return DDTREE_ERR_WORKSPACE;
-        float *part = p.splits > 1 ? reinterpret_cast<float *>(static_cast<char *>(workspace) + p.part_off) : nullptr;
-        float *lse = p.splits > 1 ? reinterpret_cast<float *>(static_cast<char *>(workspace) + p.lse_off) : nullptr;
+        char *wsb = static_cast<char *>(workspace);
+        float *part_main = reinterpret_cast<float *>(wsb + p.part_main_off);
+        float *lse_main = reinterpret_cast<float *>(wsb + p.lse_main_off);
+        float *part_tail = reinterpret_cast<float *>(wsb + p.part_tail_off);
+        float *lse_tail = reinterpret_cast<float *>(wsb + p.lse_tail_off);
         static bool attr_set = false;
         if (!attr_set) {
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(attn_mfma_kernel),
@@ -698,16 +784,18 @@ extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void
                 return DDTREE_ERR_HIP;
             attr_set = true;
         }
-        DDT_LAUNCH(DDTREE_KERNEL_ATTN, st, attn_mfma_kernel, dim3(p.splits, p.mtiles * Hkv, batch), dim3(kAttnThreads),
-                           kAttnLdsBytes, st, static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(k_cache),
-                           static_cast<const uint16_t *>(v_cache), static_cast<const uint16_t *>(k_tree),
-                           static_cast<const uint16_t *>(v_tree), ancestor_mask, args, T, Hq, Hkv,
-                           softmax_scale * kLog2e, p.splits, static_cast<uint16_t *>(out), part, lse);
-        if (p.splits > 1) {
-            const size_t rows = (size_t)batch * T * Hq;
-            const size_t threads = rows * (kHD / 4);
-            DDT_LAUNCH(DDTREE_KERNEL_ATTN_MERGE, st, attn_merge_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
-                               part, lse, p.splits, rows, static_cast<uint16_t *>(out));
+        const long long gx = (long long)batch * Hkv * (p.n_full * p.s_main + (p.tail_rows > 0 ? p.s_tail : 0));
+        DDT_LAUNCH(DDTREE_KERNEL_ATTN, st, attn_mfma_kernel, dim3((unsigned)gx), dim3(kAttnThreads),
+                   kAttnLdsBytes, st, static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(k_cache),
+                   static_cast<const uint16_t *>(v_cache), static_cast<const uint16_t *>(k_tree),
+                   static_cast<const uint16_t *>(v_tree), ancestor_mask, args, batch, T, Hq, Hkv,
+                   softmax_scale * kLog2e, p.n_full, p.s_main, p.s_tail, static_cast<uint16_t *>(out),
+                   part_main, lse_main, part_tail, lse_tail);
+        if ((p.n_full > 0 && p.s_main > 1) || (p.tail_rows > 0 && p.s_tail > 1)) {
+            const size_t threads = (size_t)batch * T * Hq * (kHD / 4);
+            DDT_LAUNCH(DDTREE_KERNEL_ATTN_MERGE, st, attn_merge_kernel, dim3((unsigned)((threads + 255) / 256)),
+                       dim3(256), 0, st, part_main, lse_main, part_tail, lse_tail, batch, T, Hq, Hkv,
+                       p.n_full, p.s_main, p.s_tail, static_cast<uint16_t *>(out));
         }
         return launch_status();
     }
