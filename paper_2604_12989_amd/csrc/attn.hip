@@ -602,15 +602,16 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(
     const float *__restrict__ part_tail, const float *__restrict__ lse_tail, int batch, int T, int Hq,
     int Hkv, int n_full, int s_main, int s_tail, uint16_t *__restrict__ out)
 {
+    // blockIdx.y = seq * T + node; threads cover (query head, 4-dim group) of that node
     const size_t rows_total = (size_t)batch * T * Hq;
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;  // (global row, 4-dim group)
-    const size_t row = idx / (kHD / 4);
-    const int dg = (int)(idx % (kHD / 4));
-    if (row >= rows_total) return;
-    const int G = Hq / Hkv;
-    const int h = (int)(row % Hq);
-    const size_t sn = row / Hq;  // seq * T + node
+    const int hd = blockIdx.x * 256 + threadIdx.x;
+    const int h = hd / (kHD / 4);
+    const int dg = hd % (kHD / 4);
+    if (h >= Hq) return;
+    const size_t sn = blockIdx.y;
     const int node = (int)(sn % T), seq = (int)(sn / T);
+    const size_t row = sn * Hq + h;
+    const int G = Hq / Hkv;
     const int hk = h / G, g = h - hk * G;
     const int r = node * G + g;  // row within the (sequence, kv head) group
     const bool is_tail = r >= n_full * kMT;
@@ -792,9 +793,8 @@ extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void
                    softmax_scale * kLog2e, p.n_full, p.s_main, p.s_tail, static_cast<uint16_t *>(out),
                    part_main, lse_main, part_tail, lse_tail);
         if ((p.n_full > 0 && p.s_main > 1) || (p.tail_rows > 0 && p.s_tail > 1)) {
-            const size_t threads = (size_t)batch * T * Hq * (kHD / 4);
-            DDT_LAUNCH(DDTREE_KERNEL_ATTN_MERGE, st, attn_merge_kernel, dim3((unsigned)((threads + 255) / 256)),
-                       dim3(256), 0, st, part_main, lse_main, part_tail, lse_tail, batch, T, Hq, Hkv,
+            DDT_LAUNCH(DDTREE_KERNEL_ATTN_MERGE, st, attn_merge_kernel,
+                       dim3((unsigned)((Hq * (kHD / 4) + 255) / 256), (unsigned)(batch * T)), dim3(256), 0, st, part_main, lse_main, part_tail, lse_tail, batch, T, Hq, Hkv,
                        p.n_full, p.s_main, p.s_tail, static_cast<uint16_t *>(out));
         }
         return launch_status();
