@@ -14,6 +14,10 @@
 // The log-probability a popped entry needs next (rank c+1 of its row) is prefetched into the
 // entry one pop ahead, so no LDS access sits on the pop-to-pop dependency chain.
 //
+// Runs of consecutive siblings (flat distributions pop many ranks of one parent in a row) are
+// popped as one batch: 64 lanes evaluate the next 64 ranks at once against a bound that no other
+// entry and no child created by the batch can exceed.
+//
 // Ties (equal fp32 scores) are resolved as the boundary specifies: the lexicographically
 // smaller rank tuple first, a prefix before its extensions.  They are rare and take a slow
 // path that walks parent links in LDS.
@@ -115,93 +119,124 @@ __global__ __launch_bounds__(kBuildThreads) void build_kernel(
             nlp1[0] = lp1;
         }
         int n = 0;
-        bool done = false;
+        int prev_p = -1;  // entry popped by the previous iteration
+        while (n < N) {
+            uint32_t lb = cand[0];
 #pragma unroll
-        for (int sn = 0; sn < NSLOT; ++sn) {  // register slot that receives the new nodes
-            for (int j = sn == 0 ? 1 : 0; j < 64 && !done; ++j) {
-                if (n >= N) {
-                    done = true;
-                    break;
+            for (int s = 1; s < NSLOT; ++s) lb = min(lb, cand[s]);
+            const uint32_t wmb = wave_min_u32(lb);
+            if (wmb == kEmpty) break;  // frontier empty: fewer than N prefixes exist
+            // which entries hold the best score (one compare per slot, wave-uniform masks)
+            unsigned long long eq[NSLOT];
+            int matches = 0;
+#pragma unroll
+            for (int s = 0; s < NSLOT; ++s) {
+                eq[s] = __ballot(cand[s] == wmb);
+                matches += __popcll(eq[s]);
+            }
+            int ws = 0, wl = 0;
+#pragma unroll
+            for (int s = 0; s < NSLOT; ++s)
+                if (eq[s]) {
+                    ws = s;
+                    wl = __ffsll((long long)eq[s]) - 1;
                 }
-                uint32_t lb = cand[0];
-#pragma unroll
-                for (int s = 1; s < NSLOT; ++s) lb = min(lb, cand[s]);
-                const uint32_t wmb = wave_min_u32(lb);
-                if (wmb == kEmpty) {  // frontier empty: fewer than N prefixes exist
-                    done = true;
-                    break;
-                }
-                // which entries hold the best score (one compare per slot, wave-uniform masks)
-                unsigned long long eq[NSLOT];
-                int matches = 0;
-#pragma unroll
-                for (int s = 0; s < NSLOT; ++s) {
-                    eq[s] = __ballot(cand[s] == wmb);
-                    matches += __popcll(eq[s]);
-                }
-                int ws = 0, wl = 0;
-#pragma unroll
-                for (int s = 0; s < NSLOT; ++s)
-                    if (eq[s]) {
-                        ws = s;
-                        wl = __ffsll((long long)eq[s]) - 1;
-                    }
-                if (matches != 1) {
-                    // slow path: several candidates share the best score
-                    int bp = -1, bc = 0;
+            if (matches != 1) {
+                // slow path: several candidates share the best score
+                int bp = -1, bc = 0;
 #pragma unroll 1
-                    for (int s = 0; s < NSLOT; ++s) {
-                        unsigned long long mm = eq[s];
-                        while (mm) {
-                            const int l = __ffsll((long long)mm) - 1;
-                            mm &= mm - 1;
-                            const int p = s * 64 + l;
-                            int ms = 0;
+                for (int s = 0; s < NSLOT; ++s) {
+                    unsigned long long mm = eq[s];
+                    while (mm) {
+                        const int l = __ffsll((long long)mm) - 1;
+                        mm &= mm - 1;
+                        const int p = s * 64 + l;
+                        int ms = 0;
 #pragma unroll
-                            for (int s2 = 0; s2 < NSLOT; ++s2)
-                                if (s2 == s) ms = __builtin_amdgcn_readlane(meta[s2], l);
-                            const int c = ms >> 8;
-                            if (bp < 0 || tuple_before(s_node, p, c, bp, bc)) {
-                                bp = p;
-                                bc = c;
-                                ws = s;
-                                wl = l;
-                            }
+                        for (int s2 = 0; s2 < NSLOT; ++s2)
+                            if (s2 == s) ms = __builtin_amdgcn_readlane(meta[s2], l);
+                        const int c = ms >> 8;
+                        if (bp < 0 || tuple_before(s_node, p, c, bp, bc)) {
+                            bp = p;
+                            bc = c;
+                            ws = s;
+                            wl = l;
                         }
                     }
-                }
-                // pop: the winner lane updates its own entry in place (next sibling), the other
-                // lanes only need the entry's meta word
-                int M = 0;
-                const bool me = lane == wl;
-#pragma unroll
-                for (int s = 0; s < NSLOT; ++s)
-                    if (ws == s) {
-                        M = __builtin_amdgcn_readlane(meta[s], wl);
-                        if (me) {
-                            // next sibling: score(parent node) + lp[row][c+1]  (-inf once c+1 == K)
-                            cand[s] = __float_as_uint(nsc[s] + nlp1[s]);
-                            nlp1[s] = s_lp[(meta[s] & 0xFF) * Kp + (meta[s] >> 8) + 2];
-                            meta[s] += 256;
-                        }
-                    }
-                const int c = M >> 8, d = (M & 0xFF) + 1;  // rank and depth of the new node
-                const float wm = __uint_as_float(wmb);
-                ++n;
-                if (lane == 0) {
-                    s_node[n] = pack_node(ws * 64 + wl, c, d);
-                    s_score[n] = wm;
-                }
-                // first child of the new node: score + lp[d][0]   (-inf once d == B)
-                const float ch = wm + __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lp0), d));
-                const float c1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lp1), d));
-                if (lane == j) {  // node n = sn * 64 + j lives in this lane's slot sn
-                    cand[sn] = __float_as_uint(ch);
-                    nsc[sn] = wm;
-                    nlp1[sn] = c1;
-                    meta[sn] = d;  // rank 0, children read row d
                 }
             }
+            // the popped entry: its meta word and its node's score, read from the owner lane
+            int M = 0;
+            float NS = 0.0f;
+#pragma unroll
+            for (int s = 0; s < NSLOT; ++s)
+                if (ws == s) {
+                    M = __builtin_amdgcn_readlane(meta[s], wl);
+                    NS = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(nsc[s]), wl));
+                }
+            const int p = ws * 64 + wl;
+            const int c = M >> 8, row = M & 0xFF, d = row + 1;  // rank, children's row, depth of the new node
+            const float wm = __uint_as_float(wmb);
+            const float lp0d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lp0), d));
+            const float lp1d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lp1), d));
+            const bool me = lane == wl;
+
+            // Sibling run.  When the same entry is popped twice in a row (flat distributions pop
+            // long runs of consecutive ranks of one parent), pop a whole batch: ranks c .. c+J-1
+            // go out in this order as long as each score is strictly above every other frontier
+            // entry and above the best child the batch itself creates (the first one's).  Lane j
+            // evaluates rank c+j; equal scores end the batch and are left to the tie logic.
+            int J = 1;
+            float myscore = wm;  // score of rank c + lane (lane 0: the popped candidate itself)
+            if (p == prev_p && matches == 1) {
+#pragma unroll
+                for (int s = 0; s < NSLOT; ++s)
+                    if (ws == s && me) cand[s] = kEmpty;  // leave the popped entry out of the bound
+                uint32_t lb2 = cand[0];
+#pragma unroll
+                for (int s = 1; s < NSLOT; ++s) lb2 = min(lb2, cand[s]);
+                const float others = __uint_as_float(wave_min_u32(lb2));
+                const float bound = fmaxf(others, wm + lp0d);
+                myscore = NS + s_lp[row * Kp + min(c + lane, Kp - 1)];  // -inf past rank K-1
+                const unsigned long long okm = __ballot(lane == 0 || myscore > bound);
+                J = ~okm == 0ull ? 64 : __ffsll((long long)~okm) - 1;
+                J = min(J, N - n);
+            }
+            prev_p = p;
+            // records of nodes n+1 .. n+J
+            if (lane < J) {
+                s_node[n + 1 + lane] = pack_node(p, c + lane, d);
+                s_score[n + 1 + lane] = myscore;
+            }
+            // their frontier entries ("push first child"): entry e = n+1+j lives in lane e % 64,
+            // slot e / 64; lane j's score travels there
+            const int j_here = (lane - (n + 1)) & 63;
+            const float sc_e = J == 1 ? wm : __shfl(myscore, j_here, 64);
+            if (j_here < J) {
+                const int slot_e = (n + 1 + j_here) >> 6;
+#pragma unroll
+                for (int s = 0; s < NSLOT; ++s)
+                    if (slot_e == s) {
+                        cand[s] = __float_as_uint(sc_e + lp0d);  // -inf once d == B
+                        nsc[s] = sc_e;
+                        nlp1[s] = lp1d;
+                        meta[s] = d;  // rank 0, children read row d
+                    }
+            }
+            // the popped entry moves on to rank c + J ("push next sibling")
+#pragma unroll
+            for (int s = 0; s < NSLOT; ++s)
+                if (ws == s && me) {
+                    if (J == 1) {
+                        cand[s] = __float_as_uint(nsc[s] + nlp1[s]);  // -inf once c+1 == K
+                        nlp1[s] = s_lp[row * Kp + c + 2];
+                    } else {
+                        cand[s] = __float_as_uint(nsc[s] + s_lp[row * Kp + min(c + J, Kp - 1)]);
+                        nlp1[s] = s_lp[row * Kp + min(c + J + 1, Kp - 1)];
+                    }
+                    meta[s] += J << 8;
+                }
+            n += J;
         }
         if (lane == 0) s_built = n;
     }
