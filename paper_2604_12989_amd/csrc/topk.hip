@@ -204,14 +204,27 @@ __global__ __launch_bounds__(kChunkThreads) void topk_chunk_kernel(
     }
     const int nvec = (n - head) >> 2;
     const float4 *pv = reinterpret_cast<const float4 *>(p + head);
-    for (int j = tid; j < nvec; j += kChunkThreads) {
-        float4 x = pv[j];
-        tmax = fmaxf(fmaxf(tmax, x.x), fmaxf(x.y, fmaxf(x.z, x.w)));
-        int o = head + 4 * j;
-        s_key[o + 0] = float_key(x.x);
-        s_key[o + 1] = float_key(x.y);
-        s_key[o + 2] = float_key(x.z);
-        s_key[o + 3] = float_key(x.w);
+    // all of a thread's loads are issued before the first one is consumed (at most
+    // kTopkChunkMax / 4 / kChunkThreads = 12 per thread): one HBM round trip instead of twelve
+    constexpr int kMaxVec = kTopkChunkMax / 4 / kChunkThreads;
+    float4 xv[kMaxVec];
+#pragma unroll
+    for (int u = 0; u < kMaxVec; ++u) {
+        const int j = tid + u * kChunkThreads;
+        xv[u] = j < nvec ? pv[j] : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    }
+#pragma unroll
+    for (int u = 0; u < kMaxVec; ++u) {
+        const int j = tid + u * kChunkThreads;
+        if (j < nvec) {
+            const float4 x = xv[u];
+            tmax = fmaxf(fmaxf(tmax, x.x), fmaxf(x.y, fmaxf(x.z, x.w)));
+            const int o = head + 4 * j;
+            s_key[o + 0] = float_key(x.x);
+            s_key[o + 1] = float_key(x.y);
+            s_key[o + 2] = float_key(x.z);
+            s_key[o + 3] = float_key(x.w);
+        }
     }
     const int tail0 = head + 4 * nvec;
     if (tid < n - tail0) {
@@ -289,7 +302,21 @@ __global__ __launch_bounds__(kMergeThreads) void topk_merge_kernel(
     const int tid = threadIdx.x;
     const size_t row = (size_t)blockIdx.y * gridDim.x + blockIdx.x;
     const uint64_t *in = cand + row * (size_t)n;
-    for (int i = tid; i < n; i += kMergeThreads) s_cand[i] = in[i];
+    {
+        // candidates of the row (at most kTopkMergeMaxCand): loads issued back to back
+        constexpr int kMaxLd = (kTopkMergeMaxCand + kMergeThreads - 1) / kMergeThreads;
+        uint64_t cv[kMaxLd];
+#pragma unroll
+        for (int u = 0; u < kMaxLd; ++u) {
+            const int i = tid + u * kMergeThreads;
+            cv[u] = i < n ? in[i] : 0ull;
+        }
+#pragma unroll
+        for (int u = 0; u < kMaxLd; ++u) {
+            const int i = tid + u * kMergeThreads;
+            if (i < n) s_cand[i] = cv[u];
+        }
+    }
     for (int i = tid; i < K; i += kMergeThreads) s_rank[i] = 0;
     if (tid == 0) {
         const double *st = stat + row * (size_t)chunks * 2;
