@@ -167,198 +167,392 @@ __device__ uint64_t block_select_threshold(Get get, int n, int k, SelectScratch 
     return pval;  // all 64 bits fixed: a single element
 }
 
+// Ranks the m distinct composites in list[] (descending; m <= kCandCap) and calls
+// emit(rank, composite) once per element: all-pairs counting, used on the rare tie-heavy path.
+template <int NT, class Emit>
+__device__ void block_rank_emit(const uint64_t *list, int m, Emit emit)
+{
+    for (int e = threadIdx.x; e < m; e += NT) {
+        const uint64_t c = list[e];
+        int g = 0;
+        for (int j = 0; j < m; ++j) g += list[j] > c ? 1 : 0;
+        emit(g, c);
+    }
+}
+
+// Sum over the wave's lanes in a fixed butterfly order.
+__device__ __forceinline__ double wave_sum_f64(double v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+constexpr int kCandCap = 2048;  // elements placed in LDS for exact ranking
+constexpr int kBuckets = 1024;
+
+struct BucketScratch {
+    uint32_t *cnt;     // [kBuckets]
+    int *start;        // [kBuckets]
+    uint64_t *sorted;  // [kCandCap]
+    int *s_wave;       // [NT/64 + 1]
+    int *s_misc;       // [8]
+};
+
+// Exact descending ranks, for ranks < want, of the workgroup's composites with key in
+// [lo_key, hi_key]; each thread brings NS composites in registers (0 = empty slot, and slots
+// with key < lo_key are ignored).  The key range is cut into kBuckets equal buckets, bucket 0
+// the highest: an element's rank is the population of the buckets above its own plus the number
+// of larger elements inside its bucket, which is found by placing the buckets that can reach
+// rank < want side by side in LDS.  Returns false, having emitted nothing, if those buckets
+// hold more than kCandCap elements (heavy ties); *total_out = number of elements considered.
+template <int NT, int NS, class Emit>
+__device__ bool block_bucket_rank(const uint64_t (&c)[NS], uint32_t lo_key, uint32_t hi_key, int want,
+                                  BucketScratch s, int *total_out, Emit emit)
+{
+    static_assert(NT == kBuckets, "one bucket per thread");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    s.cnt[tid] = 0;
+    if (tid == 0) {
+        s.s_misc[0] = -1;
+        s.s_misc[1] = kBuckets - 1;
+    }
+    __syncthreads();
+    const float inv = (float)kBuckets / ((float)(hi_key - lo_key) + 1.0f);
+    auto bucket_of = [&](uint32_t key) {
+        const int b = (int)((float)(key - lo_key) * inv);
+        return kBuckets - 1 - min(b, kBuckets - 1);
+    };
+    // bucket of every slot first, then the counting atomics back to back: their returned
+    // positions are not needed before the scan below
+    int bkt[NS];
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+        const uint32_t key = (uint32_t)(c[i] >> 32);
+        bkt[i] = (c[i] != 0ull && key >= lo_key) ? bucket_of(key) : -1;
+    }
+    uint32_t pos[NS];
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+        pos[i] = 0;
+        if (bkt[i] >= 0) pos[i] = atomicAdd(&s.cnt[bkt[i]], 1u);
+    }
+    __syncthreads();
+    // exclusive scan of the bucket populations, bucket 0 (highest keys) first
+    const int mine = (int)s.cnt[tid];
+    int incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += o;
+    }
+    if (lane == 63) s.s_wave[wave] = incl;
+    __syncthreads();
+    int base = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < NT / 64; ++w) {
+        const int v = s.s_wave[w];
+        base += w < wave ? v : 0;
+        total += v;
+    }
+    const int start = base + incl - mine;
+    s.start[tid] = start;
+    if (start < want && start + mine >= want) {  // the last bucket that can hold a rank < want
+        s.s_misc[0] = start + mine;
+        s.s_misc[1] = tid;
+    }
+    __syncthreads();
+    const int placed = s.s_misc[0] < 0 ? total : s.s_misc[0];
+    const int b_last = s.s_misc[1];
+    *total_out = total;
+    if (placed > kCandCap) return false;
+    // place the elements of buckets 0..b_last side by side, bucket by bucket
+    int st[NS];
+#pragma unroll
+    for (int i = 0; i < NS; ++i) st[i] = s.start[bkt[i] >= 0 ? bkt[i] : 0];
+#pragma unroll
+    for (int i = 0; i < NS; ++i)
+        if (bkt[i] >= 0 && bkt[i] <= b_last) s.sorted[st[i] + (int)pos[i]] = c[i];
+    __syncthreads();
+    // one thread per placed element: count the larger members of its bucket
+    for (int e = tid; e < placed; e += NT) {
+        const uint64_t ce = s.sorted[e];
+        const int b = bucket_of((uint32_t)(ce >> 32));
+        const int bs = s.start[b], nb = (int)s.cnt[b];
+        int g = 0;
+        for (int j = 0; j < nb; ++j) g += s.sorted[bs + j] > ce ? 1 : 0;
+        if (bs + g < want) emit(bs + g, ce);
+    }
+    return true;
+}
+
 // ------------------------------------------------------------------------------------------
 // Chunk kernel
 // ------------------------------------------------------------------------------------------
-constexpr int kChunkThreads = 256;
+constexpr int kChunkThreads = 1024;
+constexpr int kChunkWaves = kChunkThreads / 64;
+constexpr int kVecPerThread = kTopkChunkMax / 4 / kChunkThreads;
+constexpr int kSlots = 4 * kVecPerThread + 2;  // float4 body + one head and one tail element
+static_assert(kVecPerThread * 4 * kChunkThreads == kTopkChunkMax, "chunk must tile the workgroup");
 
+// The chunk stays in registers (at most 14 elements per thread).  A lower bound t on the
+// chunk's kc-th largest key comes almost free: cut every wave into g >= kc / waves groups of
+// adjacent lanes, take each group's largest key, and let t be the smallest of all group
+// maxima; the waves * g >= kc maxima are distinct elements that reach t.  Elements with
+// key >= t (about one in seven for kc = 256) are ranked exactly by block_bucket_rank and the top
+// kc written in descending order.  Chunks it cannot handle (heavy ties, or kc so large that
+// the bound passes most of the chunk) take the radix select over keys staged in LDS.
 __global__ __launch_bounds__(kChunkThreads) void topk_chunk_kernel(
-    const float *__restrict__ logits, int V, int K, int chunk_len, int kc, int chunks,
+    const float *__restrict__ logits, int V, int chunk_len, int kc, int chunks,
     uint64_t *__restrict__ cand, double *__restrict__ stat)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    uint32_t *s_key = reinterpret_cast<uint32_t *>(smem);
-    uint32_t *hist = s_key + chunk_len;
-    uint64_t *list = reinterpret_cast<uint64_t *>(hist + kHistBins);
-    __shared__ int s_wave[kChunkThreads / 64 + 1];
+    uint32_t *s_key = reinterpret_cast<uint32_t *>(smem);  // [chunk_len], fallback only
+    uint32_t *hist = s_key + chunk_len;                    // [kHistBins], fallback only
+    __shared__ __align__(16) uint64_t s_list[kCandCap];
+    __shared__ uint32_t s_cnt[kBuckets];
+    __shared__ int s_start[kBuckets];
+    __shared__ int s_wave[kChunkWaves + 1];
     __shared__ int s_misc[8];
     __shared__ uint64_t s_thr;
-    __shared__ float s_fmax[kChunkThreads / 64];
-    __shared__ double s_dsum[kChunkThreads];
+    __shared__ float s_fmax[kChunkWaves];
+    __shared__ uint32_t s_bound[kChunkWaves];
+    __shared__ double s_dsum[kChunkWaves];
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = blockIdx.x;
     const size_t row = (size_t)blockIdx.z * gridDim.y + blockIdx.y;
     const int start = c * chunk_len;
     const int n = min(chunk_len, V - start);
     const float *p = logits + row * (size_t)V + start;
 
-    // ---- load the chunk: scalar head up to 16-byte alignment, float4 body, scalar tail ----
-    float tmax = -INFINITY;
+    // ---- load: scalar head up to 16-byte alignment, float4 body, scalar tail; all of a
+    //      thread's loads are in flight together ----
     int head = (int)((4 - ((reinterpret_cast<uintptr_t>(p) >> 2) & 3)) & 3);
     if (head > n) head = n;
-    if (tid < head) {
-        float x = p[tid];
-        tmax = fmaxf(tmax, x);
-        s_key[tid] = float_key(x);
-    }
     const int nvec = (n - head) >> 2;
-    const float4 *pv = reinterpret_cast<const float4 *>(p + head);
-    // all of a thread's loads are issued before the first one is consumed (at most
-    // kTopkChunkMax / 4 / kChunkThreads = 12 per thread): one HBM round trip instead of twelve
-    constexpr int kMaxVec = kTopkChunkMax / 4 / kChunkThreads;
-    float4 xv[kMaxVec];
-#pragma unroll
-    for (int u = 0; u < kMaxVec; ++u) {
-        const int j = tid + u * kChunkThreads;
-        xv[u] = j < nvec ? pv[j] : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-    }
-#pragma unroll
-    for (int u = 0; u < kMaxVec; ++u) {
-        const int j = tid + u * kChunkThreads;
-        if (j < nvec) {
-            const float4 x = xv[u];
-            tmax = fmaxf(fmaxf(tmax, x.x), fmaxf(x.y, fmaxf(x.z, x.w)));
-            const int o = head + 4 * j;
-            s_key[o + 0] = float_key(x.x);
-            s_key[o + 1] = float_key(x.y);
-            s_key[o + 2] = float_key(x.z);
-            s_key[o + 3] = float_key(x.w);
-        }
-    }
     const int tail0 = head + 4 * nvec;
-    if (tid < n - tail0) {
-        float x = p[tail0 + tid];
-        tmax = fmaxf(tmax, x);
-        s_key[tail0 + tid] = float_key(x);
-    }
-    // ---- chunk max ----
+    const float4 *pv = reinterpret_cast<const float4 *>(p + head);
+    float x[kSlots];
 #pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) tmax = fmaxf(tmax, __shfl_xor(tmax, d, 64));
-    if ((tid & 63) == 0) s_fmax[tid >> 6] = tmax;
+    for (int u = 0; u < kVecPerThread; ++u) {
+        const int j = tid + u * kChunkThreads;
+        const float4 v = j < nvec ? pv[j] : make_float4(0.f, 0.f, 0.f, 0.f);
+        x[4 * u + 0] = v.x;
+        x[4 * u + 1] = v.y;
+        x[4 * u + 2] = v.z;
+        x[4 * u + 3] = v.w;
+    }
+    x[kSlots - 2] = tid < head ? p[tid] : 0.f;
+    x[kSlots - 1] = tid < n - tail0 ? p[tail0 + tid] : 0.f;
+    // element index of slot s within the chunk, -1 if the slot is empty
+    auto slot_index = [&](int s) -> int {
+        if (s < 4 * kVecPerThread) {
+            const int j = tid + (s >> 2) * kChunkThreads;
+            return j < nvec ? head + 4 * j + (s & 3) : -1;
+        }
+        if (s == kSlots - 2) return tid < head ? tid : -1;
+        return tid < n - tail0 ? tail0 + tid : -1;
+    };
+
+    // ---- chunk max, and the bound t (for n <= kCandCap every element is ranked: t = the
+    //      smallest key) ----
+    const bool take_all = n <= kCandCap;
+    float tmax = -INFINITY, tmin = INFINITY;
+    bool any = false;
+#pragma unroll
+    for (int s = 0; s < kSlots; ++s)
+        if (slot_index(s) >= 0) {
+            tmax = fmaxf(tmax, x[s]);
+            tmin = fminf(tmin, x[s]);
+            any = true;
+        }
+    float wmax = tmax;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) wmax = fmaxf(wmax, __shfl_xor(wmax, d, 64));
+    int group = 64;  // lanes per group: the largest power of two with waves * (64 / group) >= kc
+    while (group > 1 && kChunkWaves * (64 / group) < kc) group >>= 1;
+    uint32_t bound = take_all ? (any ? float_key(tmin) : ~0u) : (any ? float_key(tmax) : 0u);
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)bound, d, 64);
+        bound = (d < group && !take_all) ? max(bound, o) : min(bound, o);
+    }
+    if (lane == 0) {
+        s_fmax[wave] = wmax;
+        s_bound[wave] = bound;
+    }
     __syncthreads();
     float cmax = s_fmax[0];
+    uint32_t t = s_bound[0];
 #pragma unroll
-    for (int w = 1; w < kChunkThreads / 64; ++w) cmax = fmaxf(cmax, s_fmax[w]);
+    for (int w = 1; w < kChunkWaves; ++w) {
+        cmax = fmaxf(cmax, s_fmax[w]);
+        t = min(t, s_bound[w]);
+    }
+
     // ---- sum of exp(x - cmax) in fp64, fixed reduction order ----
     double acc = 0.0;
-    for (int i = tid; i < n; i += kChunkThreads)
-        acc += exp((double)key_float(s_key[i]) - (double)cmax);
-    s_dsum[tid] = acc;
-    __syncthreads();
-    for (int d = kChunkThreads / 2; d >= 1; d >>= 1) {
-        if (tid < d) s_dsum[tid] += s_dsum[tid + d];
-        __syncthreads();
+#pragma unroll
+    for (int s = 0; s < kSlots; ++s)
+        if (slot_index(s) >= 0) acc += exp((double)x[s] - (double)cmax);
+    acc = wave_sum_f64(acc);
+    if (lane == 0) s_dsum[wave] = acc;
+
+    // ---- rank the elements that reach t ----
+    const uint32_t base_id = (uint32_t)start;
+    auto composite = [&](uint32_t key, int i) -> uint64_t {
+        return ((uint64_t)key << 32) | (uint64_t)(uint32_t)(~(base_id + (uint32_t)i));
+    };
+    uint64_t comp[kSlots];
+#pragma unroll
+    for (int s = 0; s < kSlots; ++s) {
+        const int i = slot_index(s);
+        comp[s] = i >= 0 ? composite(float_key(x[s]), i) : 0ull;
     }
-    if (tid == 0) {
+    uint64_t *out = cand + (row * chunks + c) * (size_t)kc;
+    auto emit = [&](int rank, uint64_t cc) { out[rank] = cc; };
+    BucketScratch bs{s_cnt, s_start, s_list, s_wave, s_misc};
+    int m;
+    const bool done = block_bucket_rank<kChunkThreads, kSlots>(comp, t, float_key(cmax), kc, bs, &m, emit);
+    if (tid == 0) {  // s_dsum is complete: block_bucket_rank synchronised the workgroup
+        double S = s_dsum[0];
+        for (int w = 1; w < kChunkWaves; ++w) S += s_dsum[w];
         double *st = stat + (row * chunks + c) * 2;
         st[0] = (double)cmax;
-        st[1] = s_dsum[0];
+        st[1] = S;
     }
-    // ---- exact top-kc of the chunk ----
-    uint64_t *out = cand + (row * chunks + c) * (size_t)kc;
-    const uint32_t base_id = (uint32_t)start;
-    auto get = [&](int i) -> uint64_t {
-        return ((uint64_t)s_key[i] << 32) | (uint64_t)(uint32_t)(~(base_id + (uint32_t)i));
-    };
-    if (n <= kc) {
-        for (int i = tid; i < kc; i += kChunkThreads) out[i] = i < n ? get(i) : 0ull;
-        return;
-    }
-    SelectScratch sc{hist, list, s_wave, s_misc, &s_thr};
-    const uint64_t thr = block_select_threshold<kChunkThreads>(get, n, kc, sc);
-    if (tid == 0) s_misc[5] = 0;
-    __syncthreads();
-    for (int i = tid; i < n; i += kChunkThreads) {
-        uint64_t cc = get(i);
-        if (cc >= thr) {
-            int pos = atomicAdd(&s_misc[5], 1);
-            if (pos < kc) out[pos] = cc;
+    if (!done) {
+        // exact radix select over the whole chunk, then all-pairs ranking of the kc selected
+#pragma unroll
+        for (int s = 0; s < kSlots; ++s) {
+            const int i = slot_index(s);
+            if (i >= 0) s_key[i] = float_key(x[s]);
         }
+        if (tid == 0) s_misc[7] = 0;
+        __syncthreads();
+        auto get = [&](int i) -> uint64_t { return composite(s_key[i], i); };
+        SelectScratch sc{hist, s_list, s_wave, s_misc, &s_thr};
+        const uint64_t thr = block_select_threshold<kChunkThreads>(get, n, kc, sc);  // n > kc here
+        for (int i = tid; i < n; i += kChunkThreads) {
+            const uint64_t cc = get(i);
+            if (cc >= thr) s_list[atomicAdd(&s_misc[7], 1)] = cc;  // exactly kc <= kCandCap
+        }
+        __syncthreads();
+        block_rank_emit<kChunkThreads>(s_list, kc, emit);
+        m = kc;
     }
+    for (int i = m + tid; i < kc; i += kChunkThreads) out[i] = 0ull;  // chunk shorter than kc
 }
 
 // ------------------------------------------------------------------------------------------
 // Merge kernel
 // ------------------------------------------------------------------------------------------
 constexpr int kMergeThreads = 1024;
+constexpr int kMergeWaves = kMergeThreads / 64;
+constexpr int kMergeLoads = (kTopkMergeMaxCand + kMergeThreads - 1) / kMergeThreads;
 
+// Every chunk's list arrives sorted, so the q-th entry of each (q = ceil(K / chunks)) bounds
+// the row's K-th largest from below: T = the smallest of them is reached by at least
+// chunks * q >= K candidates.  Only candidates >= T (a little more than K) are ranked.
 __global__ __launch_bounds__(kMergeThreads) void topk_merge_kernel(
     const uint64_t *__restrict__ cand, const double *__restrict__ stat, int K, int kc, int chunks,
     int32_t *__restrict__ topk_tok, float *__restrict__ topk_lp)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int n = chunks * kc;
-    uint64_t *s_cand = reinterpret_cast<uint64_t *>(smem);
-    uint64_t *s_sel = s_cand + n;                       // [K]
-    uint64_t *list = s_sel + K;                         // [kListCap]
-    uint32_t *hist = reinterpret_cast<uint32_t *>(list + kListCap);  // [kHistBins]
-    int *s_rank = reinterpret_cast<int *>(hist + kHistBins);         // [K]
-    __shared__ int s_wave[kMergeThreads / 64 + 1];
+    uint64_t *s_cand = reinterpret_cast<uint64_t *>(smem);        // [n], fallback only
+    uint32_t *hist = reinterpret_cast<uint32_t *>(s_cand + n);    // [kHistBins], fallback only
+    __shared__ __align__(16) uint64_t s_list[kCandCap];
+    __shared__ uint32_t s_cnt[kBuckets];
+    __shared__ int s_start[kBuckets];
+    __shared__ int s_wave[kMergeWaves + 1];
     __shared__ int s_misc[8];
     __shared__ uint64_t s_thr;
+    __shared__ unsigned long long s_T, s_top;
+    __shared__ uint32_t s_mkey;
+    __shared__ double s_part[kMergeWaves];
     __shared__ double s_lse;
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t row = (size_t)blockIdx.y * gridDim.x + blockIdx.x;
     const uint64_t *in = cand + row * (size_t)n;
-    {
-        // candidates of the row (at most kTopkMergeMaxCand): loads issued back to back
-        constexpr int kMaxLd = (kTopkMergeMaxCand + kMergeThreads - 1) / kMergeThreads;
-        uint64_t cv[kMaxLd];
-#pragma unroll
-        for (int u = 0; u < kMaxLd; ++u) {
-            const int i = tid + u * kMergeThreads;
-            cv[u] = i < n ? in[i] : 0ull;
-        }
-#pragma unroll
-        for (int u = 0; u < kMaxLd; ++u) {
-            const int i = tid + u * kMergeThreads;
-            if (i < n) s_cand[i] = cv[u];
-        }
-    }
-    for (int i = tid; i < K; i += kMergeThreads) s_rank[i] = 0;
+    const double *st = stat + row * (size_t)chunks * 2;
     if (tid == 0) {
-        const double *st = stat + row * (size_t)chunks * 2;
-        double m = st[0];
-        for (int c = 1; c < chunks; ++c) m = fmax(m, st[2 * c]);
-        double S = 0.0;
-        for (int c = 0; c < chunks; ++c) S += st[2 * c + 1] * exp(st[2 * c] - m);
-        s_lse = m + log(S);
-        s_misc[5] = 0;
+        s_T = ~0ull;
+        s_top = 0ull;
+        s_mkey = 0u;
+        s_misc[7] = 0;
+    }
+    // candidates of the row (at most kTopkMergeMaxCand): loads issued back to back
+    uint64_t cv[kMergeLoads];
+#pragma unroll
+    for (int u = 0; u < kMergeLoads; ++u) {
+        const int i = tid + u * kMergeThreads;
+        cv[u] = i < n ? in[i] : 0ull;
+    }
+    // per-chunk entries: statistics, first (largest) and q-th candidate
+    const int q = (K + chunks - 1) / chunks;
+    uint64_t c_q = ~0ull, c_top = 0ull;
+    double c_max = 0.0, c_sum = 0.0;
+    if (tid < chunks) {
+        c_q = in[(size_t)tid * kc + q - 1];
+        c_top = in[(size_t)tid * kc];
+        c_max = st[2 * tid];
+        c_sum = st[2 * tid + 1];
+    }
+    __syncthreads();
+    if (tid < chunks) {
+        atomicMax(&s_mkey, float_key((float)c_max));
+        atomicMin(&s_T, (unsigned long long)c_q);
+        atomicMax(&s_top, (unsigned long long)c_top);
+    }
+    for (int c = tid + kMergeThreads; c < chunks; c += kMergeThreads) {
+        atomicMax(&s_mkey, float_key((float)st[2 * c]));
+        atomicMin(&s_T, (unsigned long long)in[(size_t)c * kc + q - 1]);
+        atomicMax(&s_top, (unsigned long long)in[(size_t)c * kc]);
+    }
+    __syncthreads();
+    // ---- log-sum-exp of the row from the chunk statistics (fp64, fixed order) ----
+    const double mx = (double)key_float(s_mkey);
+    double part = tid < chunks ? c_sum * exp(c_max - mx) : 0.0;
+    for (int c = tid + kMergeThreads; c < chunks; c += kMergeThreads)
+        part += st[2 * c + 1] * exp(st[2 * c] - mx);
+    part = wave_sum_f64(part);
+    if (lane == 0) s_part[wave] = part;
+    const uint32_t lo_key = (uint32_t)(s_T >> 32), hi_key = (uint32_t)(s_top >> 32);
+    __syncthreads();
+    if (tid == kMergeThreads - 1) {  // read by emit() only after further barriers
+        double S = s_part[0];
+        for (int w = 1; w < kMergeWaves; ++w) S += s_part[w];
+        s_lse = mx + log(S);
+    }
+    // ---- rank the candidates that reach T ----
+    // T == 0 (a chunk shorter than q): every candidate counts, down to key 0
+    auto emit = [&](int rank, uint64_t cc) {
+        topk_tok[row * (size_t)K + rank] = (int32_t)(~(uint32_t)cc);
+        topk_lp[row * (size_t)K + rank] = (float)((double)key_float((uint32_t)(cc >> 32)) - s_lse);
+    };
+    BucketScratch bs{s_cnt, s_start, s_list, s_wave, s_misc};
+    int m;
+    if (block_bucket_rank<kMergeThreads, kMergeLoads>(cv, lo_key, hi_key, K, bs, &m, emit)) return;
+    // heavy ties: exact radix select over all candidates staged in LDS
+#pragma unroll
+    for (int u = 0; u < kMergeLoads; ++u) {
+        const int i = tid + u * kMergeThreads;
+        if (i < n) s_cand[i] = cv[u];
     }
     __syncthreads();
     auto get = [&](int i) -> uint64_t { return s_cand[i]; };
-    SelectScratch sc{hist, list, s_wave, s_misc, &s_thr};
-    uint64_t thr = 0;
-    if (n > K) thr = block_select_threshold<kMergeThreads>(get, n, K, sc);
-    // n == K can only happen with a single chunk holding exactly K elements: keep them all
+    SelectScratch sc{hist, s_list, s_wave, s_misc, &s_thr};
+    // zero padding entries are smaller than every candidate, and K <= the number of real ones
+    const uint64_t thr = n > K ? block_select_threshold<kMergeThreads>(get, n, K, sc) : 1ull;
     for (int i = tid; i < n; i += kMergeThreads) {
-        uint64_t c = s_cand[i];
-        if (c >= thr && c != 0ull) {
-            int pos = atomicAdd(&s_misc[5], 1);
-            if (pos < K) s_sel[pos] = c;
-        }
+        const uint64_t cc = s_cand[i];
+        if (cc >= thr && cc != 0ull) s_list[atomicAdd(&s_misc[7], 1)] = cc;  // exactly K
     }
     __syncthreads();
-    // rank by counting: K*K comparisons spread over the workgroup
-    const int parts = kMergeThreads / K > 0 ? kMergeThreads / K : 1;
-    for (int idx = tid; idx < K * parts; idx += kMergeThreads) {
-        const int e = idx % K, part = idx / K;
-        const int j0 = (int)((long long)K * part / parts), j1 = (int)((long long)K * (part + 1) / parts);
-        const uint64_t c = s_sel[e];
-        int greater = 0;
-        for (int j = j0; j < j1; ++j) greater += s_sel[j] > c ? 1 : 0;
-        atomicAdd(&s_rank[e], greater);
-    }
-    __syncthreads();
-    const double lse = s_lse;
-    for (int e = tid; e < K; e += kMergeThreads) {
-        const uint64_t c = s_sel[e];
-        const int r = s_rank[e];
-        topk_tok[row * (size_t)K + r] = (int32_t)(~(uint32_t)c);
-        topk_lp[row * (size_t)K + r] = (float)((double)key_float((uint32_t)(c >> 32)) - lse);
-    }
+    block_rank_emit<kMergeThreads>(s_list, K, emit);
 }
 
 }  // namespace ddt
@@ -378,20 +572,19 @@ extern "C" int ddtree_topk(const float *logits, int batch, int B, int V, int K, 
     double *stat = reinterpret_cast<double *>(static_cast<char *>(workspace) + p.stat_off);
 
     static bool attr_set = false;
-    const size_t lds_chunk = (size_t)p.chunk_len * 4 + kHistBins * 4 + kListCap * 8;
-    const size_t lds_merge =
-        (size_t)p.chunks * p.kc * 8 + (size_t)K * 8 + kListCap * 8 + kHistBins * 4 + (size_t)K * 4;
+    const size_t lds_chunk = (size_t)p.chunk_len * 4 + kHistBins * 4;
+    const size_t lds_merge = (size_t)p.chunks * p.kc * 8 + kHistBins * 4;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(topk_chunk_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024) != hipSuccess ||
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kTopkChunkMax * 4 + kHistBins * 4) != hipSuccess ||
             hipFuncSetAttribute(reinterpret_cast<const void *>(topk_merge_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024) != hipSuccess)
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kTopkMergeMaxCand * 8 + kHistBins * 4) != hipSuccess)
             return DDTREE_ERR_HIP;
         attr_set = true;
     }
     hipStream_t st = as_stream(stream);
     DDT_LAUNCH(DDTREE_KERNEL_TOPK_CHUNK, st, topk_chunk_kernel, dim3(p.chunks, B, batch), dim3(kChunkThreads), lds_chunk, st,
-                       logits, V, K, p.chunk_len, p.kc, p.chunks, cand, stat);
+                       logits, V, p.chunk_len, p.kc, p.chunks, cand, stat);
     DDT_LAUNCH(DDTREE_KERNEL_TOPK_MERGE, st, topk_merge_kernel, dim3(B, batch), dim3(kMergeThreads), lds_merge, st, cand,
                        stat, K, p.kc, p.chunks, topk_tok, topk_lp);
     return launch_status();
