@@ -137,6 +137,42 @@ __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v)
     return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
+// DPP move that leaves 0 in lanes with no source lane (or in rows outside ROW_MASK).
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ int dpp_or_zero(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xF, false);
+}
+// Inclusive prefix sum over the wave's 64 lanes (all lanes must be active).
+__device__ __forceinline__ int wave_scan_inclusive_i32(int v)
+{
+    v += dpp_or_zero<0x111>(v);  // row_shr:1
+    v += dpp_or_zero<0x112>(v);  // row_shr:2
+    v += dpp_or_zero<0x114>(v);  // row_shr:4
+    v += dpp_or_zero<0x118>(v);  // row_shr:8  -> inclusive inside each row of 16
+    v += dpp_or_zero<0x142, 0xA>(v);  // rows 1 and 3 add the total of the row before
+    v += dpp_or_zero<0x143, 0xC>(v);  // rows 2 and 3 add the total of rows 0-1
+    return v;
+}
+// Sum of a double over the wave in a fixed order; the result is valid in lane 63 only.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ double dpp_d_or_zero(double v)
+{
+    const int lo = dpp_or_zero<CTRL, ROW_MASK>(__double2loint(v));
+    const int hi = dpp_or_zero<CTRL, ROW_MASK>(__double2hiint(v));
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double wave_sum_f64_lane63(double v)
+{
+    v += dpp_d_or_zero<0xB1>(v);
+    v += dpp_d_or_zero<0x4E>(v);
+    v += dpp_d_or_zero<0x141>(v);
+    v += dpp_d_or_zero<0x140>(v);
+    v += dpp_d_or_zero<0x142, 0xA>(v);
+    v += dpp_d_or_zero<0x143, 0xC>(v);
+    return v;
+}
+
 __device__ __forceinline__ int lane_id() { return __lane_id(); }
 #endif
 

@@ -180,35 +180,30 @@ __device__ void block_rank_emit(const uint64_t *list, int m, Emit emit)
     }
 }
 
-// Sum over the wave's lanes in a fixed butterfly order.
-__device__ __forceinline__ double wave_sum_f64(double v)
-{
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
-    return v;
-}
-
 constexpr int kCandCap = 2048;  // elements placed in LDS for exact ranking
 constexpr int kBuckets = 1024;
 
 struct BucketScratch {
     uint32_t *cnt;     // [kBuckets]
-    int *start;        // [kBuckets]
+    int *start;        // [kBuckets + 1]
     uint64_t *sorted;  // [kCandCap]
-    int *s_wave;       // [NT/64 + 1]
+    int *s_wave;       // [NT/64]
     int *s_misc;       // [8]
 };
 
-// Exact descending ranks, for ranks < want, of the workgroup's composites with key in
-// [lo_key, hi_key]; each thread brings NS composites in registers (0 = empty slot, and slots
-// with key < lo_key are ignored).  The key range is cut into kBuckets equal buckets, bucket 0
-// the highest: an element's rank is the population of the buckets above its own plus the number
-// of larger elements inside its bucket, which is found by placing the buckets that can reach
-// rank < want side by side in LDS.  Returns false, having emitted nothing, if those buckets
-// hold more than kCandCap elements (heavy ties); *total_out = number of elements considered.
-template <int NT, int NS, class Emit>
-__device__ bool block_bucket_rank(const uint64_t (&c)[NS], uint32_t lo_key, uint32_t hi_key, int want,
-                                  BucketScratch s, int *total_out, Emit emit)
+// Exact descending ranks, for ranks < want, of the workgroup's elements whose value lies in
+// [lo, hi].  Each thread brings NS values in registers (NaN = empty slot; values below lo are
+// ignored) and comp(i), the composite of slot i, evaluated only for the few elements that are
+// placed.  Bit i of `active` (uniform over the wave) tells whether slot i can be non-empty
+// anywhere in the wave, so that a wave skips the code of slots it does not use.
+// The value range is cut into kBuckets equal buckets, bucket 0 the highest: an element's rank
+// is the population of the buckets above its own plus the number of larger elements inside its
+// bucket, which is found by placing the buckets that can reach rank < want side by side in LDS.
+// Returns false, having emitted nothing, if those buckets hold more than kCandCap elements
+// (heavy ties); *total_out = number of elements considered.
+template <int NT, int NS, class Comp, class Emit>
+__device__ bool block_bucket_rank(const float (&x)[NS], Comp comp, uint32_t active, float lo, float hi,
+                                  int want, BucketScratch s, int *total_out, Emit emit)
 {
     static_assert(NT == kBuckets, "one bucket per thread");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -216,36 +211,31 @@ __device__ bool block_bucket_rank(const uint64_t (&c)[NS], uint32_t lo_key, uint
     if (tid == 0) {
         s.s_misc[0] = -1;
         s.s_misc[1] = kBuckets - 1;
+        s.start[kBuckets] = 0;  // read (and ignored) by slots that hold no element
     }
     __syncthreads();
-    const float inv = (float)kBuckets / ((float)(hi_key - lo_key) + 1.0f);
-    auto bucket_of = [&](uint32_t key) {
-        const int b = (int)((float)(key - lo_key) * inv);
-        return kBuckets - 1 - min(b, kBuckets - 1);
-    };
-    // bucket of every slot first, then the counting atomics back to back: their returned
-    // positions are not needed before the scan below
+    const float inv = (float)kBuckets / fmaxf(hi - lo, 1e-30f);
+    // monotone in the value: float subtraction, scaling and truncation all preserve order
+    auto bucket_of = [&](float v) { return min((int)((hi - v) * inv), kBuckets - 1); };
+    // the counting atomics go out back to back: the positions they return are not needed
+    // before the scan below
     int bkt[NS];
-#pragma unroll
-    for (int i = 0; i < NS; ++i) {
-        const uint32_t key = (uint32_t)(c[i] >> 32);
-        bkt[i] = (c[i] != 0ull && key >= lo_key) ? bucket_of(key) : -1;
-    }
     uint32_t pos[NS];
 #pragma unroll
     for (int i = 0; i < NS; ++i) {
+        bkt[i] = kBuckets;
         pos[i] = 0;
-        if (bkt[i] >= 0) pos[i] = atomicAdd(&s.cnt[bkt[i]], 1u);
+        if ((active >> i) & 1u) {
+            if (x[i] >= lo) {
+                bkt[i] = bucket_of(x[i]);
+                pos[i] = atomicAdd(&s.cnt[bkt[i]], 1u);
+            }
+        }
     }
     __syncthreads();
-    // exclusive scan of the bucket populations, bucket 0 (highest keys) first
+    // exclusive scan of the bucket populations, bucket 0 (highest values) first
     const int mine = (int)s.cnt[tid];
-    int incl = mine;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int o = __shfl_up(incl, d, 64);
-        if (lane >= d) incl += o;
-    }
+    const int incl = wave_scan_inclusive_i32(mine);
     if (lane == 63) s.s_wave[wave] = incl;
     __syncthreads();
     int base = 0, total = 0;
@@ -267,23 +257,58 @@ __device__ bool block_bucket_rank(const uint64_t (&c)[NS], uint32_t lo_key, uint
     *total_out = total;
     if (placed > kCandCap) return false;
     // place the elements of buckets 0..b_last side by side, bucket by bucket
-    int st[NS];
-#pragma unroll
-    for (int i = 0; i < NS; ++i) st[i] = s.start[bkt[i] >= 0 ? bkt[i] : 0];
 #pragma unroll
     for (int i = 0; i < NS; ++i)
-        if (bkt[i] >= 0 && bkt[i] <= b_last) s.sorted[st[i] + (int)pos[i]] = c[i];
+        if ((active >> i) & 1u) {
+            const int st = s.start[bkt[i]];
+            if (bkt[i] <= b_last) s.sorted[st + (int)pos[i]] = comp(i);
+        }
     __syncthreads();
     // one thread per placed element: count the larger members of its bucket
     for (int e = tid; e < placed; e += NT) {
         const uint64_t ce = s.sorted[e];
-        const int b = bucket_of((uint32_t)(ce >> 32));
+        const int b = bucket_of(key_float((uint32_t)(ce >> 32)));
         const int bs = s.start[b], nb = (int)s.cnt[b];
         int g = 0;
         for (int j = 0; j < nb; ++j) g += s.sorted[bs + j] > ce ? 1 : 0;
         if (bs + g < want) emit(bs + g, ce);
     }
     return true;
+}
+
+// exp(y) for y <= 0 in fp64, about 1 ulp: y = (64 n + j) ln2/64 + r with |r| <= ln2/128, so
+// exp(y) = 2^n * 2^(j/64) * exp(r); 2^(j/64) comes from a 64-entry table and exp(r) from its
+// Taylor polynomial of degree 5 (remainder below 4e-17).  Returns 0 below the fp64 range.
+__device__ const double kExp2Table[64] = {
+    0x1.0000000000000p+0, 0x1.02c9a3e778061p+0, 0x1.059b0d3158574p+0, 0x1.0874518759bc8p+0,
+    0x1.0b5586cf9890fp+0, 0x1.0e3ec32d3d1a2p+0, 0x1.11301d0125b51p+0, 0x1.1429aaea92de0p+0,
+    0x1.172b83c7d517bp+0, 0x1.1a35beb6fcb75p+0, 0x1.1d4873168b9aap+0, 0x1.2063b88628cd6p+0,
+    0x1.2387a6e756238p+0, 0x1.26b4565e27cddp+0, 0x1.29e9df51fdee1p+0, 0x1.2d285a6e4030bp+0,
+    0x1.306fe0a31b715p+0, 0x1.33c08b26416ffp+0, 0x1.371a7373aa9cbp+0, 0x1.3a7db34e59ff7p+0,
+    0x1.3dea64c123422p+0, 0x1.4160a21f72e2ap+0, 0x1.44e086061892dp+0, 0x1.486a2b5c13cd0p+0,
+    0x1.4bfdad5362a27p+0, 0x1.4f9b2769d2ca7p+0, 0x1.5342b569d4f82p+0, 0x1.56f4736b527dap+0,
+    0x1.5ab07dd485429p+0, 0x1.5e76f15ad2148p+0, 0x1.6247eb03a5585p+0, 0x1.6623882552225p+0,
+    0x1.6a09e667f3bcdp+0, 0x1.6dfb23c651a2fp+0, 0x1.71f75e8ec5f74p+0, 0x1.75feb564267c9p+0,
+    0x1.7a11473eb0187p+0, 0x1.7e2f336cf4e62p+0, 0x1.82589994cce13p+0, 0x1.868d99b4492edp+0,
+    0x1.8ace5422aa0dbp+0, 0x1.8f1ae99157736p+0, 0x1.93737b0cdc5e5p+0, 0x1.97d829fde4e50p+0,
+    0x1.9c49182a3f090p+0, 0x1.a0c667b5de565p+0, 0x1.a5503b23e255dp+0, 0x1.a9e6b5579fdbfp+0,
+    0x1.ae89f995ad3adp+0, 0x1.b33a2b84f15fbp+0, 0x1.b7f76f2fb5e47p+0, 0x1.bcc1e904bc1d2p+0,
+    0x1.c199bdd85529cp+0, 0x1.c67f12e57d14bp+0, 0x1.cb720dcef9069p+0, 0x1.d072d4a07897cp+0,
+    0x1.d5818dcfba487p+0, 0x1.da9e603db3285p+0, 0x1.dfc97337b9b5fp+0, 0x1.e502ee78b3ff6p+0,
+    0x1.ea4afa2a490dap+0, 0x1.efa1bee615a27p+0, 0x1.f50765b6e4540p+0, 0x1.fa7c1819e90d8p+0};
+__device__ __forceinline__ double exp_nonpositive(double y, const double *s_tab)
+{
+    const double k = rint(y * 92.33248261689366);              // 64 / ln 2
+    double r = fma(k, -0x1.62e42fefa0000p-7, y);               // ln2/64, leading 36 bits
+    r = fma(k, -0x1.cf79abc9e3b3ap-46, r);                     // ln2/64, remainder
+    const int ki = (int)k;
+    double p = fma(r, 1.0 / 120.0, 1.0 / 24.0);
+    p = fma(r, p, 1.0 / 6.0);
+    p = fma(r, p, 0.5);
+    p = fma(r, p, 1.0);
+    p = fma(r, p, 1.0);
+    const double v = ldexp(s_tab[ki & 63] * p, ki >> 6);
+    return y > -708.0 ? v : 0.0;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -295,13 +320,27 @@ constexpr int kVecPerThread = kTopkChunkMax / 4 / kChunkThreads;
 constexpr int kSlots = 4 * kVecPerThread + 2;  // float4 body + one head and one tail element
 static_assert(kVecPerThread * 4 * kChunkThreads == kTopkChunkMax, "chunk must tile the workgroup");
 
+// Largest value of each group of `group` adjacent lanes (a power of two), then the smallest of
+// the wave's group maxima.  Valid in lane 63.
+__device__ __forceinline__ uint32_t wave_min_of_group_max(uint32_t v, int group)
+{
+    auto step = [&](uint32_t o, int d) { v = d < group ? max(v, o) : min(v, o); };
+    step(dpp_u<0xB1>(v), 1);
+    step(dpp_u<0x4E>(v), 2);
+    step(dpp_u<0x141>(v), 4);
+    step(dpp_u<0x140>(v), 8);
+    step(dpp_u<0x142, 0xA>(v), 16);
+    step(dpp_u<0x143, 0xC>(v), 32);
+    return v;
+}
+
 // The chunk stays in registers (at most 14 elements per thread).  A lower bound t on the
-// chunk's kc-th largest key comes almost free: cut every wave into g >= kc / waves groups of
-// adjacent lanes, take each group's largest key, and let t be the smallest of all group
-// maxima; the waves * g >= kc maxima are distinct elements that reach t.  Elements with
-// key >= t (about one in seven for kc = 256) are ranked exactly by block_bucket_rank and the top
-// kc written in descending order.  Chunks it cannot handle (heavy ties, or kc so large that
-// the bound passes most of the chunk) take the radix select over keys staged in LDS.
+// chunk's kc-th largest value comes almost free: cut every wave into g >= kc / waves groups of
+// adjacent lanes, take each group's largest value, and let t be the smallest of all group
+// maxima; the waves * g >= kc maxima are distinct elements that reach t.  Elements >= t (about
+// one in seven for kc = 256) are ranked exactly by block_bucket_rank and the top kc written in
+// descending order.  Chunks it cannot handle (heavy ties, or kc so large that the bound passes
+// most of the chunk) take the radix select over keys staged in LDS.
 __global__ __launch_bounds__(kChunkThreads) void topk_chunk_kernel(
     const float *__restrict__ logits, int V, int chunk_len, int kc, int chunks,
     uint64_t *__restrict__ cand, double *__restrict__ stat)
@@ -311,13 +350,15 @@ __global__ __launch_bounds__(kChunkThreads) void topk_chunk_kernel(
     uint32_t *hist = s_key + chunk_len;                    // [kHistBins], fallback only
     __shared__ __align__(16) uint64_t s_list[kCandCap];
     __shared__ uint32_t s_cnt[kBuckets];
-    __shared__ int s_start[kBuckets];
+    __shared__ int s_start[kBuckets + 1];
     __shared__ int s_wave[kChunkWaves + 1];
     __shared__ int s_misc[8];
     __shared__ uint64_t s_thr;
     __shared__ float s_fmax[kChunkWaves];
     __shared__ uint32_t s_bound[kChunkWaves];
+    __shared__ float s_fmin[kChunkWaves];
     __shared__ double s_dsum[kChunkWaves];
+    __shared__ double s_exp2[64];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = blockIdx.x;
@@ -333,18 +374,22 @@ __global__ __launch_bounds__(kChunkThreads) void topk_chunk_kernel(
     const int nvec = (n - head) >> 2;
     const int tail0 = head + 4 * nvec;
     const float4 *pv = reinterpret_cast<const float4 *>(p + head);
+    // empty slots hold -inf: no effect on the max, an exp term of 0, and below every bound lo
+    // that block_bucket_rank is given (chunks with real -inf elements take the radix select)
+    const float kEmpty = -INFINITY;
     float x[kSlots];
 #pragma unroll
     for (int u = 0; u < kVecPerThread; ++u) {
         const int j = tid + u * kChunkThreads;
-        const float4 v = j < nvec ? pv[j] : make_float4(0.f, 0.f, 0.f, 0.f);
+        const float4 v = j < nvec ? pv[j] : make_float4(kEmpty, kEmpty, kEmpty, kEmpty);
         x[4 * u + 0] = v.x;
         x[4 * u + 1] = v.y;
         x[4 * u + 2] = v.z;
         x[4 * u + 3] = v.w;
     }
-    x[kSlots - 2] = tid < head ? p[tid] : 0.f;
-    x[kSlots - 1] = tid < n - tail0 ? p[tail0 + tid] : 0.f;
+    x[kSlots - 2] = tid < head ? p[tid] : kEmpty;
+    x[kSlots - 1] = tid < n - tail0 ? p[tail0 + tid] : kEmpty;
+    if (tid < 64) s_exp2[tid] = kExp2Table[tid];
     // element index of slot s within the chunk, -1 if the slot is empty
     auto slot_index = [&](int s) -> int {
         if (s < 4 * kVecPerThread) {
@@ -354,68 +399,72 @@ __global__ __launch_bounds__(kChunkThreads) void topk_chunk_kernel(
         if (s == kSlots - 2) return tid < head ? tid : -1;
         return tid < n - tail0 ? tail0 + tid : -1;
     };
+    // slots that hold an element in at least one lane of this wave (uniform)
+    const int wave_base = __builtin_amdgcn_readfirstlane(tid & ~63);
+    uint32_t active = 0;
+#pragma unroll
+    for (int u = 0; u < kVecPerThread; ++u)
+        if (wave_base + u * kChunkThreads < nvec) active |= 0xFu << (4 * u);
+    if (wave_base < head) active |= 1u << (kSlots - 2);
+    if (wave_base < n - tail0) active |= 1u << (kSlots - 1);
 
-    // ---- chunk max, and the bound t (for n <= kCandCap every element is ranked: t = the
-    //      smallest key) ----
+    // ---- chunk max, chunk min and the bound t.  Every element is ranked (t = chunk min) when
+    //      the chunk is small, or when a group has no element at all and the bound is void ----
     const bool take_all = n <= kCandCap;
+    const bool void_bound = nvec < kChunkThreads;  // some thread holds no element
     float tmax = -INFINITY, tmin = INFINITY;
-    bool any = false;
 #pragma unroll
     for (int s = 0; s < kSlots; ++s)
-        if (slot_index(s) >= 0) {
-            tmax = fmaxf(tmax, x[s]);
-            tmin = fminf(tmin, x[s]);
-            any = true;
-        }
-    float wmax = tmax;
+        if ((active >> s) & 1u) tmax = fmaxf(tmax, x[s]);
+    if (take_all || void_bound) {
 #pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) wmax = fmaxf(wmax, __shfl_xor(wmax, d, 64));
+        for (int s = 0; s < kSlots; ++s)
+            if (((active >> s) & 1u) && slot_index(s) >= 0) tmin = fminf(tmin, x[s]);
+    }
+    const bool any = tid < nvec || tid < head || tid < n - tail0;
+    const float wmax = wave_max_f32(tmax);
     int group = 64;  // lanes per group: the largest power of two with waves * (64 / group) >= kc
     while (group > 1 && kChunkWaves * (64 / group) < kc) group >>= 1;
-    uint32_t bound = take_all ? (any ? float_key(tmin) : ~0u) : (any ? float_key(tmax) : 0u);
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t o = (uint32_t)__shfl_xor((int)bound, d, 64);
-        bound = (d < group && !take_all) ? max(bound, o) : min(bound, o);
-    }
-    if (lane == 0) {
+    const uint32_t bound = wave_min_of_group_max(any ? float_key(tmax) : 0u, group);
+    const float wmin = -wave_max_f32(-tmin);
+    if (lane == 63) {
         s_fmax[wave] = wmax;
+        s_fmin[wave] = wmin;
         s_bound[wave] = bound;
     }
     __syncthreads();
-    float cmax = s_fmax[0];
+    float cmax = s_fmax[0], cmin = s_fmin[0];
     uint32_t t = s_bound[0];
 #pragma unroll
     for (int w = 1; w < kChunkWaves; ++w) {
         cmax = fmaxf(cmax, s_fmax[w]);
+        cmin = fminf(cmin, s_fmin[w]);
         t = min(t, s_bound[w]);
     }
+    const float lo = (take_all || void_bound) ? cmin : key_float(t);
 
     // ---- sum of exp(x - cmax) in fp64, fixed reduction order ----
     double acc = 0.0;
 #pragma unroll
     for (int s = 0; s < kSlots; ++s)
-        if (slot_index(s) >= 0) acc += exp((double)x[s] - (double)cmax);
-    acc = wave_sum_f64(acc);
-    if (lane == 0) s_dsum[wave] = acc;
+        if ((active >> s) & 1u) acc += exp_nonpositive((double)x[s] - (double)cmax, s_exp2);
+    acc = wave_sum_f64_lane63(acc);
+    if (lane == 63) s_dsum[wave] = acc;
 
     // ---- rank the elements that reach t ----
     const uint32_t base_id = (uint32_t)start;
     auto composite = [&](uint32_t key, int i) -> uint64_t {
         return ((uint64_t)key << 32) | (uint64_t)(uint32_t)(~(base_id + (uint32_t)i));
     };
-    uint64_t comp[kSlots];
-#pragma unroll
-    for (int s = 0; s < kSlots; ++s) {
-        const int i = slot_index(s);
-        comp[s] = i >= 0 ? composite(float_key(x[s]), i) : 0ull;
-    }
+    auto comp = [&](int s) { return composite(float_key(x[s]), slot_index(s)); };
     uint64_t *out = cand + (row * chunks + c) * (size_t)kc;
     auto emit = [&](int rank, uint64_t cc) { out[rank] = cc; };
     BucketScratch bs{s_cnt, s_start, s_list, s_wave, s_misc};
-    int m;
-    const bool done = block_bucket_rank<kChunkThreads, kSlots>(comp, t, float_key(cmax), kc, bs, &m, emit);
-    if (tid == 0) {  // s_dsum is complete: block_bucket_rank synchronised the workgroup
+    int m = 0;
+    const bool done = lo > -INFINITY &&
+                      block_bucket_rank<kChunkThreads, kSlots>(x, comp, active, lo, cmax, kc, bs, &m, emit);
+    __syncthreads();
+    if (tid == 0) {
         double S = s_dsum[0];
         for (int w = 1; w < kChunkWaves; ++w) S += s_dsum[w];
         double *st = stat + (row * chunks + c) * 2;
@@ -465,7 +514,7 @@ __global__ __launch_bounds__(kMergeThreads) void topk_merge_kernel(
     uint32_t *hist = reinterpret_cast<uint32_t *>(s_cand + n);    // [kHistBins], fallback only
     __shared__ __align__(16) uint64_t s_list[kCandCap];
     __shared__ uint32_t s_cnt[kBuckets];
-    __shared__ int s_start[kBuckets];
+    __shared__ int s_start[kBuckets + 1];
     __shared__ int s_wave[kMergeWaves + 1];
     __shared__ int s_misc[8];
     __shared__ uint64_t s_thr;
@@ -485,12 +534,19 @@ __global__ __launch_bounds__(kMergeThreads) void topk_merge_kernel(
         s_misc[7] = 0;
     }
     // candidates of the row (at most kTopkMergeMaxCand): loads issued back to back
+    const int wave_base = __builtin_amdgcn_readfirstlane(tid & ~63);
+    uint32_t active = 0;
     uint64_t cv[kMergeLoads];
 #pragma unroll
     for (int u = 0; u < kMergeLoads; ++u) {
         const int i = tid + u * kMergeThreads;
         cv[u] = i < n ? in[i] : 0ull;
+        if (wave_base + u * kMergeThreads < n) active |= 1u << u;
     }
+    float xv[kMergeLoads];  // candidate values, -inf where there is none
+#pragma unroll
+    for (int u = 0; u < kMergeLoads; ++u)
+        xv[u] = cv[u] != 0ull ? key_float((uint32_t)(cv[u] >> 32)) : -INFINITY;
     // per-chunk entries: statistics, first (largest) and q-th candidate
     const int q = (K + chunks - 1) / chunks;
     uint64_t c_q = ~0ull, c_top = 0ull;
@@ -518,24 +574,33 @@ __global__ __launch_bounds__(kMergeThreads) void topk_merge_kernel(
     double part = tid < chunks ? c_sum * exp(c_max - mx) : 0.0;
     for (int c = tid + kMergeThreads; c < chunks; c += kMergeThreads)
         part += st[2 * c + 1] * exp(st[2 * c] - mx);
-    part = wave_sum_f64(part);
-    if (lane == 0) s_part[wave] = part;
-    const uint32_t lo_key = (uint32_t)(s_T >> 32), hi_key = (uint32_t)(s_top >> 32);
-    __syncthreads();
-    if (tid == kMergeThreads - 1) {  // read by emit() only after further barriers
-        double S = s_part[0];
-        for (int w = 1; w < kMergeWaves; ++w) S += s_part[w];
-        s_lse = mx + log(S);
+    part = wave_sum_f64_lane63(part);
+    // T == 0 (a chunk shorter than q): every candidate counts, which the radix select handles
+    const float lo = s_T >> 32 ? key_float((uint32_t)(s_T >> 32)) : -INFINITY;
+    const float hi = key_float((uint32_t)(s_top >> 32));
+    // s_lse is read by emit() only after the barriers of the ranking
+    if (chunks <= 64) {
+        if (tid == 63) s_lse = mx + log(part);
+    } else {
+        if (lane == 63) s_part[wave] = part;
+        __syncthreads();
+        if (tid == kMergeThreads - 1) {
+            double S = s_part[0];
+            for (int w = 1; w < kMergeWaves; ++w) S += s_part[w];
+            s_lse = mx + log(S);
+        }
     }
     // ---- rank the candidates that reach T ----
-    // T == 0 (a chunk shorter than q): every candidate counts, down to key 0
     auto emit = [&](int rank, uint64_t cc) {
         topk_tok[row * (size_t)K + rank] = (int32_t)(~(uint32_t)cc);
         topk_lp[row * (size_t)K + rank] = (float)((double)key_float((uint32_t)(cc >> 32)) - s_lse);
     };
     BucketScratch bs{s_cnt, s_start, s_list, s_wave, s_misc};
     int m;
-    if (block_bucket_rank<kMergeThreads, kMergeLoads>(cv, lo_key, hi_key, K, bs, &m, emit)) return;
+    if (lo > -INFINITY && block_bucket_rank<kMergeThreads, kMergeLoads>(
+                              xv, [&](int u) { return cv[u]; }, active, lo, hi, K, bs, &m, emit))
+        return;
+    __syncthreads();  // s_lse is complete
     // heavy ties: exact radix select over all candidates staged in LDS
 #pragma unroll
     for (int u = 0; u < kMergeLoads; ++u) {

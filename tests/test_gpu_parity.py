@@ -73,6 +73,24 @@ def test_topk_duplicates_and_flat_rows():
         assert ulp_diff(lp_g[0], lp_o).max() <= 2
 
 
+def test_topk_masked_vocabulary():
+    """Rows where most of the vocabulary is masked with -inf, some with fewer finite entries
+    than K: the -inf entries then fill the tail in token order, with log-probability -inf."""
+    V, K = 30000, 64
+    x = di.draft_logits(21, 4, V)
+    x[0, 100:] = -np.inf                     # 100 finite entries >= K
+    x[1, 40:] = -np.inf                      # 40 finite entries < K
+    x[2, ::2] = -np.inf                      # every other entry masked
+    x[3, :29000] = -np.inf                   # whole chunks masked
+    tok_o, lp_o = oracle.topk(x, K)
+    tok_g, lp_g = gu.gpu_topk(x, K)
+    assert np.array_equal(tok_g[0], tok_o)
+    fin = np.isfinite(lp_o)
+    assert np.array_equal(np.isfinite(lp_g[0]), fin)
+    assert np.all(lp_g[0][~fin] == -np.inf)
+    assert ulp_diff(lp_g[0][fin], lp_o[fin]).max() <= 2
+
+
 def test_topk_batched():
     xs = np.stack([di.draft_logits(11, 4, 20000, batch_index=b) for b in range(3)])
     tok_g, lp_g = gu.gpu_topk(xs, 32)
