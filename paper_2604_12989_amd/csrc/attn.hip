@@ -56,39 +56,27 @@ struct AttnArgs {
 AttnPlan attn_plan(int batch, int T, int Hq, int Hkv, int D, long long sum_L, int dtype)
 {
     AttnPlan p{};
-    p.s_main = p.s_tail = 1;
+    p.splits = 1;
     if (!(dtype == DDTREE_DTYPE_BF16 && D == kHD)) return p;  // generic path needs no scratch
     const int G = Hq / Hkv;
     const long long M = (long long)T * G;
-    p.n_full = (int)(M / kMT);
-    p.tail_rows = (int)(M % kMT);
+    const int nblk = (int)((M + 31) / 32);
+    p.n_tiles = (nblk + 7) / 8;
+    p.blk_base = nblk / p.n_tiles;
+    p.blk_extra = nblk % p.n_tiles;
     const long long tiles = (sum_L / batch + T) / kKT;  // key tiles per sequence, roughly
-    const long long groups = (long long)batch * Hkv;
-    if (p.n_full > 0) {
-        const long long base = groups * p.n_full;  // full-tile workgroups per split
-        int S = base >= 384 ? 1 : (int)((256 + base - 1) / base);
-        if ((long long)S * 4 > tiles) S = (int)(tiles / 4 > 0 ? tiles / 4 : 1);  // >= 4 tiles per split
-        p.s_main = S > 32 ? 32 : S;
-    }
-    if (p.tail_rows > 0) {
-        int S = (int)((256 + groups - 1) / groups);
-        if ((long long)S * 2 > tiles) S = (int)(tiles / 2 > 0 ? tiles / 2 : 1);  // >= 2 tiles per split
-        p.s_tail = S > 64 ? 64 : S;
-    }
+    const long long base = (long long)batch * Hkv * p.n_tiles;  // workgroups per split
+    // one workgroup per compute unit and launch round: as many splits as still fit 256 units
+    int S = base >= 256 ? 1 : (int)(256 / base);
+    if ((long long)S * 4 > tiles) S = (int)(tiles / 4 > 0 ? tiles / 4 : 1);  // >= 4 tiles per split
+    p.splits = S > 32 ? 32 : S;
     size_t off = 0;
-    if (p.n_full > 0 && p.s_main > 1) {
+    if (p.splits > 1) {
         const size_t rows = (size_t)batch * T * Hq;  // indexed by global row
-        p.part_main_off = off;
-        off = align_up(off + (size_t)p.s_main * rows * D * 4, 256);
-        p.lse_main_off = off;
-        off = align_up(off + (size_t)p.s_main * rows * 4, 256);
-    }
-    if (p.tail_rows > 0 && p.s_tail > 1) {
-        const size_t rows = (size_t)groups * p.tail_rows;  // compact tail-row index
-        p.part_tail_off = off;
-        off = align_up(off + (size_t)p.s_tail * rows * D * 4, 256);
-        p.lse_tail_off = off;
-        off = align_up(off + (size_t)p.s_tail * rows * 4, 256);
+        p.part_off = off;
+        off = align_up(off + (size_t)p.splits * rows * D * 2, 256);  // fp16 partials
+        p.lse_off = off;
+        off = align_up(off + (size_t)p.splits * rows * 4, 256);
     }
     p.bytes = off;
     return p;
@@ -110,6 +98,14 @@ __device__ __forceinline__ uint32_t f2bf_pair(float lo, float hi)
 {
     const floatx2 f = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+}
+
+// two floats -> packed fp16 pair (round to nearest even)
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t f2h_pair(float lo, float hi)
+{
+    const f16x2 h = {(_Float16)lo, (_Float16)hi};
+    return __builtin_bit_cast(uint32_t, h);
 }
 
 // Compile-time loop: f(IC<B>{}), ..., f(IC<E-1>{}); the index is a constant expression inside f,
@@ -181,10 +177,9 @@ __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(1,
 void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_cache,
                       const uint16_t *__restrict__ v_cache, const uint16_t *__restrict__ k_tree,
                       const uint16_t *__restrict__ v_tree, const uint64_t *__restrict__ mask,
-                      AttnArgs args, int batch_n, int T, int Hq, int Hkv, float scale_log2e, int n_full,
-                      int s_main, int s_tail, uint16_t *__restrict__ out, float *__restrict__ part_main,
-                      float *__restrict__ lse_main, float *__restrict__ part_tail,
-                      float *__restrict__ lse_tail)
+                      AttnArgs args, int batch_n, int T, int Hq, int Hkv, float scale_log2e, int n_tiles_m,
+                      int blk_base, int blk_extra, int splits, uint16_t *__restrict__ out,
+                      uint16_t *__restrict__ part, float *__restrict__ lse)
 {
     // LDS: kAttnStages stages of {K tile, V tile}, filled by direct global->LDS loads.  One wave
     // instruction writes 64 x 16 B contiguously, but every lane may fetch any 16-byte chunk, so
@@ -196,19 +191,13 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
-    // 1-D grid, dispatched in order: first every full-tile workgroup (split fastest, so that
-    // consecutive workgroups -- which land on different XCDs -- work on different key ranges and
-    // the workgroups of one XCD share theirs), then the short tail-tile workgroups, which fill
-    // the compute units as the long ones drain.
-    const int groups = Hkv * batch_n;                    // (sequence, kv head) pairs
-    const int n_main = groups * n_full * s_main;
-    const bool is_tail = (int)blockIdx.x >= n_main;
-    const int splits = is_tail ? s_tail : s_main;
-    const int wid = is_tail ? (int)blockIdx.x - n_main : (int)blockIdx.x;
+    // 1-D grid with the split index fastest, so that consecutive workgroups -- which land on
+    // different XCDs -- work on different key ranges and the workgroups of one XCD share theirs.
+    const int wid = (int)blockIdx.x;
     const int split = wid % splits;
     const int rest = wid / splits;                        // (row tile, group)
-    const int mt = is_tail ? n_full : rest % n_full;
-    const int grp = is_tail ? rest : rest / n_full;
+    const int mt = rest % n_tiles_m;
+    const int grp = rest / n_tiles_m;                     // (sequence, kv head) pair
     const int hk = grp % Hkv;
     const int seq = grp / Hkv;
     const int G = Hq / Hkv;
@@ -216,14 +205,18 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     const int M = T * G;
     const int L0 = args.kv_offset[seq];
     const int L = args.kv_offset[seq + 1] - L0;
-    const int m0 = mt * kMT;
-    const int last_node = min(T - 1, (m0 + kMT - 1) / G);
+    // this tile's blocks of 32 rows: wave w owns blocks 2w and 2w+1 of the tile
+    const int first_blk = mt * blk_base + min(mt, blk_extra);
+    const int n_blk = blk_base + (mt < blk_extra ? 1 : 0);
+    const int m0 = first_blk * 32;
+    const int m_end = min(M, (first_blk + n_blk) * 32);
+    const int last_node = min(T - 1, (m_end - 1) / G);
     const int n_cache_tiles = (L + kKT - 1) / kKT;
     const int n_tree_tiles = last_node / kKT + 1;
     const int nt = n_cache_tiles + n_tree_tiles;
     const int t_begin = (int)((long long)nt * split / splits);
     const int t_end = (int)((long long)nt * (split + 1) / splits);
-    const bool wave_active = m0 + wave * 64 < M;
+    const bool wave_active = m0 + wave * 64 < m_end;
 
     // this lane's two query rows (cb = 0, 1)
     int node_[2], rowg_[2];
@@ -231,7 +224,7 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
         const int r = m0 + wave * 64 + cb * 32 + l32;
-        rvalid[cb] = r < M;
+        rvalid[cb] = r < m_end;
         const int node = rvalid[cb] ? r / G : 0;
         const int g = rvalid[cb] ? r - node * G : 0;
         node_[cb] = node;
@@ -570,79 +563,83 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                     *reinterpret_cast<uint2 *>(dst + dim) = val;
                 }
         } else {
-            // partial result of this split: normalised O and log2-sum-exp; main rows are indexed
-            // by global row, tail rows compactly by (sequence, kv head, row in tail)
-            const size_t n_rows = is_tail ? (size_t)batch_n * Hkv * (M - n_full * kMT) : (size_t)batch_n * T * Hq;
-            const size_t ridx = is_tail ? ((size_t)seq * Hkv + hk) * (M - n_full * kMT) + (wave * 64 + cb * 32 + l32)
-                                        : (size_t)rowg_[cb];
-            float *dst = (is_tail ? part_tail : part_main) + ((size_t)split * n_rows + ridx) * kHD;
+            // partial result of this split, indexed by global row: normalised O and log2-sum-exp
+            const size_t n_rows = (size_t)batch_n * T * Hq;
+            const size_t ridx = (size_t)rowg_[cb];
+            uint16_t *dst = part + ((size_t)split * n_rows + ridx) * kHD;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
                 for (int g4 = 0; g4 < 4; ++g4) {
                     const int dim = db * 32 + g4 * 8 + half * 4;
-                    float4 val;
-                    val.x = o[db][cb][4 * g4 + 0] * inv;
-                    val.y = o[db][cb][4 * g4 + 1] * inv;
-                    val.z = o[db][cb][4 * g4 + 2] * inv;
-                    val.w = o[db][cb][4 * g4 + 3] * inv;
-                    *reinterpret_cast<float4 *>(dst + dim) = val;
+                    uint2 val;
+                    val.x = f2h_pair(o[db][cb][4 * g4 + 0] * inv, o[db][cb][4 * g4 + 1] * inv);
+                    val.y = f2h_pair(o[db][cb][4 * g4 + 2] * inv, o[db][cb][4 * g4 + 3] * inv);
+                    *reinterpret_cast<uint2 *>(dst + dim) = val;
                 }
             if (half == 0)
-                (is_tail ? lse_tail : lse_main)[(size_t)split * n_rows + ridx] =
+                lse[(size_t)split * n_rows + ridx] =
                     inv > 0.0f ? m_run[cb] + __builtin_amdgcn_logf(l_tot) : -INFINITY;
         }
     }
 }
 
-// Merge of the split-KV partials: out = sum_s 2^(lse_s - max) O_s / sum_s 2^(lse_s - max), for
-// the rows whose tile was split (main rows when s_main > 1, tail rows when s_tail > 1).
-__global__ __launch_bounds__(256) void attn_merge_kernel(
-    const float *__restrict__ part_main, const float *__restrict__ lse_main,
-    const float *__restrict__ part_tail, const float *__restrict__ lse_tail, int batch, int T, int Hq,
-    int Hkv, int n_full, int s_main, int s_tail, uint16_t *__restrict__ out)
+// Merge of the split-KV partials: out = sum_s 2^(lse_s - max) O_s / sum_s 2^(lse_s - max).
+// Partials are normalised per split and stored as fp16 (outputs are averages of V entries, far
+// inside the fp16 range for any KV cache a bf16 model produces; eps 2^-11 is below the bf16
+// rounding of the result).  One thread per (row, 8 dims); the loads of 8 splits are in flight
+// together.
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+constexpr int kMergeBatch = 8;
+
+__global__ __launch_bounds__(256) void attn_merge_kernel(const uint16_t *__restrict__ part_all,
+                                                         const float *__restrict__ lse_all, size_t n_rows,
+                                                         int splits, uint16_t *__restrict__ out)
 {
-    // blockIdx.y = seq * T + node; threads cover (query head, 4-dim group) of that node
-    const size_t rows_total = (size_t)batch * T * Hq;
-    const int hd = blockIdx.x * 256 + threadIdx.x;
-    const int h = hd / (kHD / 4);
-    const int dg = hd % (kHD / 4);
-    if (h >= Hq) return;
-    const size_t sn = blockIdx.y;
-    const int node = (int)(sn % T), seq = (int)(sn / T);
-    const size_t row = sn * Hq + h;
-    const int G = Hq / Hkv;
-    const int hk = h / G, g = h - hk * G;
-    const int r = node * G + g;  // row within the (sequence, kv head) group
-    const bool is_tail = r >= n_full * kMT;
-    const int splits = is_tail ? s_tail : s_main;
-    if (splits == 1) return;  // written directly by the attention kernel
-    const int tail_rows = T * G - n_full * kMT;
-    const size_t n_rows = is_tail ? (size_t)batch * Hkv * tail_rows : rows_total;
-    const size_t ridx = is_tail ? ((size_t)seq * Hkv + hk) * tail_rows + (r - n_full * kMT) : row;
-    const float *part = is_tail ? part_tail : part_main;
-    const float *lse = is_tail ? lse_tail : lse_main;
+    const size_t gid = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t row = gid >> 4;
+    const int dg = (int)(gid & 15);
+    if (row >= n_rows) return;
+    const uint16_t *part = part_all + row * kHD + dg * 8;
+    const float *lse = lse_all + row;
+    const size_t pstride = n_rows * kHD;
+
     float mx = -INFINITY;
-    for (int s = 0; s < splits; ++s) mx = fmaxf(mx, lse[(size_t)s * n_rows + ridx]);
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s0 = 0; s0 < splits; s0 += kMergeBatch) {
+        float l[kMergeBatch];
+#pragma unroll
+        for (int j = 0; j < kMergeBatch; ++j) l[j] = s0 + j < splits ? lse[(size_t)(s0 + j) * n_rows] : -INFINITY;
+#pragma unroll
+        for (int j = 0; j < kMergeBatch; ++j) mx = fmaxf(mx, l[j]);
+    }
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     float wsum = 0.0f;
     if (mx > -INFINITY) {
-        for (int s = 0; s < splits; ++s) {
-            const float w = __builtin_amdgcn_exp2f(lse[(size_t)s * n_rows + ridx] - mx);
-            const float4 v =
-                *reinterpret_cast<const float4 *>(part + ((size_t)s * n_rows + ridx) * kHD + dg * 4);
-            acc.x += w * v.x;
-            acc.y += w * v.y;
-            acc.z += w * v.z;
-            acc.w += w * v.w;
-            wsum += w;
+        for (int s0 = 0; s0 < splits; s0 += kMergeBatch) {
+            f16x8 v[kMergeBatch];
+            float l[kMergeBatch];
+#pragma unroll
+            for (int j = 0; j < kMergeBatch; ++j) {
+                const bool on = s0 + j < splits;
+                l[j] = on ? lse[(size_t)(s0 + j) * n_rows] : -INFINITY;
+                v[j] = on ? *reinterpret_cast<const f16x8 *>(part + (size_t)(s0 + j) * pstride) : f16x8(0);
+            }
+#pragma unroll
+            for (int j = 0; j < kMergeBatch; ++j) {
+                const float w = __builtin_amdgcn_exp2f(l[j] - mx);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e] += w * (float)v[j][e];
+                wsum += w;
+            }
         }
     }
     const float inv = wsum > 0.0f ? 1.0f / wsum : 0.0f;
-    uint2 val;
-    val.x = f2bf_pair(acc.x * inv, acc.y * inv);
-    val.y = f2bf_pair(acc.z * inv, acc.w * inv);
-    *reinterpret_cast<uint2 *>(out + row * kHD + dg * 4) = val;
+    uint4 val;
+    val.x = f2bf_pair(acc[0] * inv, acc[1] * inv);
+    val.y = f2bf_pair(acc[2] * inv, acc[3] * inv);
+    val.z = f2bf_pair(acc[4] * inv, acc[5] * inv);
+    val.w = f2bf_pair(acc[6] * inv, acc[7] * inv);
+    *reinterpret_cast<uint4 *>(out + row * kHD + dg * 8) = val;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -774,10 +771,8 @@ extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void
         AttnPlan p = attn_plan(batch, T, Hq, Hkv, D, sum_L, dtype);
         if (!ws_ok(workspace, workspace_bytes, p.bytes)) return DDTREE_ERR_WORKSPACE;
         char *wsb = static_cast<char *>(workspace);
-        float *part_main = reinterpret_cast<float *>(wsb + p.part_main_off);
-        float *lse_main = reinterpret_cast<float *>(wsb + p.lse_main_off);
-        float *part_tail = reinterpret_cast<float *>(wsb + p.part_tail_off);
-        float *lse_tail = reinterpret_cast<float *>(wsb + p.lse_tail_off);
+        uint16_t *part = reinterpret_cast<uint16_t *>(wsb + p.part_off);
+        float *lse = reinterpret_cast<float *>(wsb + p.lse_off);
         static bool attr_set = false;
         if (!attr_set) {
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(attn_mfma_kernel),
@@ -785,17 +780,18 @@ extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void
                 return DDTREE_ERR_HIP;
             attr_set = true;
         }
-        const long long gx = (long long)batch * Hkv * (p.n_full * p.s_main + (p.tail_rows > 0 ? p.s_tail : 0));
+        const long long gx = (long long)batch * Hkv * p.n_tiles * p.splits;
         DDT_LAUNCH(DDTREE_KERNEL_ATTN, st, attn_mfma_kernel, dim3((unsigned)gx), dim3(kAttnThreads),
                    kAttnLdsBytes, st, static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(k_cache),
                    static_cast<const uint16_t *>(v_cache), static_cast<const uint16_t *>(k_tree),
                    static_cast<const uint16_t *>(v_tree), ancestor_mask, args, batch, T, Hq, Hkv,
-                   softmax_scale * kLog2e, p.n_full, p.s_main, p.s_tail, static_cast<uint16_t *>(out),
-                   part_main, lse_main, part_tail, lse_tail);
-        if ((p.n_full > 0 && p.s_main > 1) || (p.tail_rows > 0 && p.s_tail > 1)) {
+                   softmax_scale * kLog2e, p.n_tiles, p.blk_base, p.blk_extra, p.splits,
+                   static_cast<uint16_t *>(out), part, lse);
+        if (p.splits > 1) {
+            const size_t n_rows = (size_t)batch * T * Hq;
             DDT_LAUNCH(DDTREE_KERNEL_ATTN_MERGE, st, attn_merge_kernel,
-                       dim3((unsigned)((Hq * (kHD / 4) + 255) / 256), (unsigned)(batch * T)), dim3(256), 0, st, part_main, lse_main, part_tail, lse_tail, batch, T, Hq, Hkv,
-                       p.n_full, p.s_main, p.s_tail, static_cast<uint16_t *>(out));
+                       dim3((unsigned)((n_rows * 16 + 255) / 256)), dim3(256), 0, st, part, lse, n_rows,
+                       p.splits, static_cast<uint16_t *>(out));
         }
         return launch_status();
     }

@@ -39,11 +39,12 @@ TopkPlan topk_plan(int batch, int B, int V, int K);
 
 // ---- layout of the attention scratch ----
 struct AttnPlan {
-    // Query rows of one (sequence, kv head) are split into n_full tiles of 256 rows plus a tail
-    // tile of tail_rows rows; the key range of a full tile is cut into s_main splits, that of the
-    // (much cheaper) tail tile into s_tail splits.  Partial results exist only where splits > 1.
-    int n_full, tail_rows, s_main, s_tail;
-    size_t part_main_off, lse_main_off, part_tail_off, lse_tail_off, bytes;
+    // The query rows of one (sequence, kv head) pair, in blocks of 32, are dealt as evenly as
+    // possible to n_tiles row tiles of at most 8 blocks: tile i holds blk_base + (i < blk_extra)
+    // blocks.  The key range of every tile is cut into `splits` parts; partial results exist
+    // only when splits > 1.
+    int n_tiles, blk_base, blk_extra, splits;
+    size_t part_off, lse_off, bytes;
 };
 AttnPlan attn_plan(int batch, int T, int Hq, int Hkv, int D, long long sum_L, int dtype);
 
