@@ -47,6 +47,10 @@ def parse():
     ap.add_argument("--sets", type=int, default=0, help="input copies to rotate over (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-reps", type=int, default=3)
+    ap.add_argument("--calib-copy-mb", type=int, default=0,
+                    help="also run a plain device copy of this many MiB (not timed): the kernel of "
+                         "known traffic that scales the FETCH_SIZE / WRITE_SIZE counters of a "
+                         "rocprofv3 --pmc run")
     return ap.parse_args()
 
 
@@ -133,6 +137,13 @@ def main():
             call()
 
     main_kernel = "attn" if (bf16 and D == 128) else "attn_generic"
+    if args.calib_copy_mb > 0:
+        src = torch.empty(args.calib_copy_mb << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     # ------------------------------------------------------------------ warm-up, then timed
     for i in range(args.warmup):
         run_step(i)
@@ -157,17 +168,21 @@ def main():
     flops = 4.0 * D * Hq * (float(T) * L + vis_tree)  # algorithmic: QK^T and PV over visible keys
     k_avg_ms = float(kernel_ms.mean())
     achieved = flops / (k_avg_ms * 1e-3) / 1e12
-    traffic = None
+    # HBM bytes per launch from committed rocprofv3 --pmc summaries (FETCH_SIZE + WRITE_SIZE, each
+    # scaled by a plain copy of known size); null for workloads that have not been profiled
+    traffic = traffic_detail = None
     tpath = os.path.join(ROOT, "profiles", "attn_traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(f"config{args.config}")
+            traffic_detail = json.load(open(tpath)).get(f"config{args.config}")
+            if traffic_detail:
+                traffic = traffic_detail["fetch_bytes"] + traffic_detail["write_bytes"]
         except Exception:  # noqa: BLE001
-            traffic = None
+            traffic = traffic_detail = None
     roofline = dict(bound="mfma", kernel="attn_mfma_kernel" if main_kernel == "attn" else main_kernel,
                     achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS if bf16 else 157.3,
                     unit="TFLOP/s", frac=round(achieved / (PEAK_BF16_TFLOPS if bf16 else 157.3), 4),
-                    traffic=traffic, flops_per_launch=flops, kernel_avg_us=round(1e3 * k_avg_ms, 2),
+                    traffic=traffic, traffic_detail=traffic_detail, flops_per_launch=flops, kernel_avg_us=round(1e3 * k_avg_ms, 2),
                     kernel_launches=int(kernel_ms.size))
 
     # ------------------------------------------------------------------ per-kernel breakdown (not timed)

@@ -191,13 +191,18 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
-    // 1-D grid with the split index fastest, so that consecutive workgroups -- which land on
-    // different XCDs -- work on different key ranges and the workgroups of one XCD share theirs.
-    const int wid = (int)blockIdx.x;
-    const int split = wid % splits;
-    const int rest = wid / splits;                        // (row tile, group)
-    const int mt = rest % n_tiles_m;
-    const int grp = rest / n_tiles_m;                     // (sequence, kv head) pair
+    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  The grid is read as
+    // 8 runs of per_xcd consecutive work items, run x being what XCD x executes, and consecutive
+    // work items are the row tiles of one (group, key range): the row tiles that read the same K
+    // and V rows share an L2, and those rows leave HBM once.
+    const int total = Hkv * batch_n * n_tiles_m * splits;
+    const int per_xcd = (total + 7) >> 3;
+    const int wid = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
+    if (wid >= total) return;
+    const int mt = wid % n_tiles_m;
+    const int unit = wid / n_tiles_m;                     // (group, key range)
+    const int split = unit % splits;
+    const int grp = unit / splits;                        // (sequence, kv head) pair
     const int hk = grp % Hkv;
     const int seq = grp / Hkv;
     const int G = Hq / Hkv;
@@ -780,7 +785,7 @@ extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void
                 return DDTREE_ERR_HIP;
             attr_set = true;
         }
-        const long long gx = (long long)batch * Hkv * p.n_tiles * p.splits;
+        const long long gx = ((long long)batch * Hkv * p.n_tiles * p.splits + 7) / 8 * 8;
         DDT_LAUNCH(DDTREE_KERNEL_ATTN, st, attn_mfma_kernel, dim3((unsigned)gx), dim3(kAttnThreads),
                    kAttnLdsBytes, st, static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(k_cache),
                    static_cast<const uint16_t *>(v_cache), static_cast<const uint16_t *>(k_tree),
