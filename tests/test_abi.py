@@ -51,7 +51,7 @@ def test_workspace_sizing_is_host_arithmetic(lib):
     import paper_2604_12989_amd as dd
     assert dd.workspace_bytes(1, 8, 1024, 16, 2, 1, 64, 128) >= 256
     big = dd.workspace_bytes(1, 16, 151936, 256, 32, 8, 128, 8192)
-    assert 30e6 < big < 80e6           # dominated by the split-KV partials of the attention
+    assert 8e6 < big < 40e6            # dominated by the fp16 split-KV partials of the attention
     assert dd.workspace_bytes(1, 16, 151936, 256, 32, 7, 128, 8192) == 0   # Hq % Hkv != 0
     assert dd.workspace_bytes(1, 16, 151936, 4096, 32, 8, 128, 8192) == 0  # N above the maximum
     assert dd.workspace_bytes(0, 16, 151936, 256, 32, 8, 128, 8192) == 0
