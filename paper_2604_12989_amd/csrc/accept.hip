@@ -71,28 +71,33 @@ __global__ __launch_bounds__(kArgmaxThreads) void accept_argmax_kernel(
     }
     const int nvec = (n - head) >> 2;
     const float4 *pv = reinterpret_cast<const float4 *>(p + head);
-    int j = tid;
-    // two independent 16-byte loads in flight per thread and iteration
-    for (; j + kArgmaxThreads < nvec; j += 2 * kArgmaxThreads) {
-        const float4 a = pv[j];
-        const float4 b = pv[j + kArgmaxThreads];
-        const int ia = start + head + 4 * j, ib = ia + 4 * kArgmaxThreads;
-        if (a.x > bv) { bv = a.x; bi = ia; }
-        if (a.y > bv) { bv = a.y; bi = ia + 1; }
-        if (a.z > bv) { bv = a.z; bi = ia + 2; }
-        if (a.w > bv) { bv = a.w; bi = ia + 3; }
-        if (b.x > bv) { bv = b.x; bi = ib; }
-        if (b.y > bv) { bv = b.y; bi = ib + 1; }
-        if (b.z > bv) { bv = b.z; bi = ib + 2; }
-        if (b.w > bv) { bv = b.w; bi = ib + 3; }
-    }
-    for (; j < nvec; j += kArgmaxThreads) {
-        const float4 a = pv[j];
-        const int ia = start + head + 4 * j;
-        if (a.x > bv) { bv = a.x; bi = ia; }
-        if (a.y > bv) { bv = a.y; bi = ia + 1; }
-        if (a.z > bv) { bv = a.z; bi = ia + 2; }
-        if (a.w > bv) { bv = a.w; bi = ia + 3; }
+    // eight independent 16-byte loads in flight per thread and iteration: about 128 KB per compute
+    // unit, what it takes to cover the HBM latency at full bandwidth; the logits are read once,
+    // so the loads are marked non-temporal
+    constexpr int kInFlight = 8;
+    for (int j0 = tid; j0 < nvec; j0 += kInFlight * kArgmaxThreads) {
+        float4 x[kInFlight];
+#pragma unroll
+        for (int u = 0; u < kInFlight; ++u) {
+            const int j = j0 + u * kArgmaxThreads;
+            if (j < nvec) {
+                const float *q = reinterpret_cast<const float *>(pv + j);
+                x[u].x = __builtin_nontemporal_load(q);
+                x[u].y = __builtin_nontemporal_load(q + 1);
+                x[u].z = __builtin_nontemporal_load(q + 2);
+                x[u].w = __builtin_nontemporal_load(q + 3);
+            } else {
+                x[u] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kInFlight; ++u) {
+            const int ia = start + head + 4 * (j0 + u * kArgmaxThreads);
+            if (x[u].x > bv) { bv = x[u].x; bi = ia; }
+            if (x[u].y > bv) { bv = x[u].y; bi = ia + 1; }
+            if (x[u].z > bv) { bv = x[u].z; bi = ia + 2; }
+            if (x[u].w > bv) { bv = x[u].w; bi = ia + 3; }
+        }
     }
     const int tail0 = head + 4 * nvec;
     if (tid < n - tail0) {
