@@ -83,10 +83,17 @@ __global__ __launch_bounds__(kBuildThreads) void build_kernel(
     const float *lp = topk_lp + (size_t)seq * B * K;
     const int32_t *tk = topk_tok + (size_t)seq * B * K;
 
-    for (int i = tid; i < B * Kp; i += kBuildThreads) {
-        int d = i / Kp, k = i - d * Kp;
-        s_lp[i] = k < K ? lp[d * K + k] : -INFINITY;
-    }
+    // log-probabilities into LDS, rows padded with -inf; four rows' loads in flight together
+    for (int d0 = 0; d0 < B; d0 += 4)
+        for (int k0 = 0; k0 < Kp; k0 += kBuildThreads) {
+            const int k = k0 + tid;
+            float v[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] = (d0 + r < B && k < K) ? lp[(d0 + r) * K + k] : -INFINITY;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (d0 + r < B && k < Kp) s_lp[(d0 + r) * Kp + k] = v[r];
+        }
     if (tid == 0) {
         s_node[0] = pack_node(0, 0, 0);
         s_score[0] = 0.0f;
