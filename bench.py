@@ -44,6 +44,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", type=int, default=3, help="workload (ddtree_inputs.CONFIGS), 1..4")
+    ap.add_argument("--budget", type=int, default=0,
+                    help="override the node budget N of the workload (budget sweep; 0 = the config's own)")
     ap.add_argument("--sets", type=int, default=0, help="input copies to rotate over (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-reps", type=int, default=3)
@@ -67,8 +69,11 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    c = di.CONFIGS[args.config]
+    c = dict(di.CONFIGS[args.config])
     assert c["batch"] == 1, "bench.py times the single-sequence configurations"
+    if args.budget > 0:
+        c["N"] = args.budget
+        c["name"] = f"{c['name']}, budget {args.budget}"
     seed = di.config_seed(args.config)
     B, V, N, Hq, Hkv, D, L = c["B"], c["V"], c["N"], c["Hq"], c["Hkv"], c["D"], c["L"]
     K, T = min(N, V), N + 1

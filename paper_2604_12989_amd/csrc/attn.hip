@@ -66,10 +66,22 @@ AttnPlan attn_plan(int batch, int T, int Hq, int Hkv, int D, long long sum_L, in
     p.blk_extra = nblk % p.n_tiles;
     const long long tiles = (sum_L / batch + T) / kKT;  // key tiles per sequence, roughly
     const long long base = (long long)batch * Hkv * p.n_tiles;  // workgroups per split
-    // one workgroup per compute unit and launch round: as many splits as still fit 256 units
-    int S = base >= 256 ? 1 : (int)(256 / base);
-    if ((long long)S * 4 > tiles) S = (int)(tiles / 4 > 0 ? tiles / 4 : 1);  // >= 4 tiles per split
-    p.splits = S > 32 ? 32 : S;
+    // One workgroup per compute unit and launch round: base * S workgroups take
+    // ceil(base * S / 256) rounds of 1/S of the key range each.  Take the S that minimises that
+    // time, charged 2 % per split for the partials it writes and the merge reads, with at least
+    // 4 key tiles per split.
+    int best_s = 1;
+    double best_cost = 1e30;
+    for (int S = 1; S <= 32; ++S) {
+        if (S > 1 && (long long)S * 4 > tiles) break;
+        const long long rounds = (base * S + 255) / 256;
+        const double cost = (double)rounds / S * (1.0 + 0.02 * (S - 1));
+        if (cost < best_cost - 1e-12) {
+            best_cost = cost;
+            best_s = S;
+        }
+    }
+    p.splits = best_s;
     size_t off = 0;
     if (p.splits > 1) {
         const size_t rows = (size_t)batch * T * Hq;  // indexed by global row
