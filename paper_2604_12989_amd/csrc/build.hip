@@ -128,59 +128,73 @@ __global__ __launch_bounds__(kBuildThreads) void build_kernel(
         int n = 0;
         int prev_p = -1;  // entry popped by the previous iteration
         while (n < N) {
+            // this lane's best entry and that entry's fields (selects, no branches)
             uint32_t lb = cand[0];
+            int l_meta = meta[0], l_slot = 0;
+            float l_nsc = nsc[0], l_nlp1 = nlp1[0];
 #pragma unroll
-            for (int s = 1; s < NSLOT; ++s) lb = min(lb, cand[s]);
+            for (int s = 1; s < NSLOT; ++s) {
+                const bool better = cand[s] < lb;
+                lb = better ? cand[s] : lb;
+                l_meta = better ? meta[s] : l_meta;
+                l_nsc = better ? nsc[s] : l_nsc;
+                l_nlp1 = better ? nlp1[s] : l_nlp1;
+                l_slot = better ? s : l_slot;
+            }
             const uint32_t wmb = wave_min_u32(lb);
             if (wmb == kEmpty) break;  // frontier empty: fewer than N prefixes exist
-            // which entries hold the best score (one compare per slot, wave-uniform masks)
-            unsigned long long eq[NSLOT];
-            int matches = 0;
+            // how many entries hold the best score: more than one takes the tie path
+            int eqcnt = 0;
 #pragma unroll
-            for (int s = 0; s < NSLOT; ++s) {
-                eq[s] = __ballot(cand[s] == wmb);
-                matches += __popcll(eq[s]);
-            }
-            int ws = 0, wl = 0;
-#pragma unroll
-            for (int s = 0; s < NSLOT; ++s)
-                if (eq[s]) {
-                    ws = s;
-                    wl = __ffsll((long long)eq[s]) - 1;
-                }
-            if (matches != 1) {
-                // slow path: several candidates share the best score
+            for (int s = 0; s < NSLOT; ++s) eqcnt += cand[s] == wmb ? 1 : 0;
+            const unsigned long long bal = __ballot(eqcnt > 0);
+            const bool tie = __popcll(bal) > 1 || __ballot(eqcnt > 1) != 0ull;
+            int wl = __ffsll((long long)bal) - 1;
+            int ws, M;
+            float NS, NL;
+            if (!tie) {
+                ws = __builtin_amdgcn_readlane(l_slot, wl);
+                M = __builtin_amdgcn_readlane(l_meta, wl);
+                NS = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(l_nsc), wl));
+                NL = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(l_nlp1), wl));
+            } else {
+                // slow path: several candidates share the best score; the rank-tuple order decides
                 int bp = -1, bc = 0;
+                ws = 0;
 #pragma unroll 1
                 for (int s = 0; s < NSLOT; ++s) {
-                    unsigned long long mm = eq[s];
+                    unsigned long long mm = 0ull;
+#pragma unroll
+                    for (int s2 = 0; s2 < NSLOT; ++s2)
+                        if (s2 == s) mm = __ballot(cand[s2] == wmb);
                     while (mm) {
                         const int l = __ffsll((long long)mm) - 1;
                         mm &= mm - 1;
-                        const int p = s * 64 + l;
+                        const int p2 = s * 64 + l;
                         int ms = 0;
 #pragma unroll
                         for (int s2 = 0; s2 < NSLOT; ++s2)
                             if (s2 == s) ms = __builtin_amdgcn_readlane(meta[s2], l);
-                        const int c = ms >> 8;
-                        if (bp < 0 || tuple_before(s_node, p, c, bp, bc)) {
-                            bp = p;
-                            bc = c;
+                        const int c2 = ms >> 8;
+                        if (bp < 0 || tuple_before(s_node, p2, c2, bp, bc)) {
+                            bp = p2;
+                            bc = c2;
                             ws = s;
                             wl = l;
                         }
                     }
                 }
-            }
-            // the popped entry: its meta word and its node's score, read from the owner lane
-            int M = 0;
-            float NS = 0.0f;
+                M = 0;
+                NS = 0.0f;
+                NL = 0.0f;
 #pragma unroll
-            for (int s = 0; s < NSLOT; ++s)
-                if (ws == s) {
-                    M = __builtin_amdgcn_readlane(meta[s], wl);
-                    NS = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(nsc[s]), wl));
-                }
+                for (int s = 0; s < NSLOT; ++s)
+                    if (ws == s) {
+                        M = __builtin_amdgcn_readlane(meta[s], wl);
+                        NS = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(nsc[s]), wl));
+                        NL = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(nlp1[s]), wl));
+                    }
+            }
             const int p = ws * 64 + wl;
             const int c = M >> 8, row = M & 0xFF, d = row + 1;  // rank, children's row, depth of the new node
             const float wm = __uint_as_float(wmb);
@@ -195,13 +209,10 @@ __global__ __launch_bounds__(kBuildThreads) void build_kernel(
             // evaluates rank c+j; equal scores end the batch and are left to the tie logic.
             int J = 1;
             float myscore = wm;  // score of rank c + lane (lane 0: the popped candidate itself)
-            if (p == prev_p && matches == 1) {
+            if (p == prev_p && !tie) {
+                uint32_t lb2 = kEmpty;  // best of this lane's entries, the popped one left out
 #pragma unroll
-                for (int s = 0; s < NSLOT; ++s)
-                    if (ws == s && me) cand[s] = kEmpty;  // leave the popped entry out of the bound
-                uint32_t lb2 = cand[0];
-#pragma unroll
-                for (int s = 1; s < NSLOT; ++s) lb2 = min(lb2, cand[s]);
+                for (int s = 0; s < NSLOT; ++s) lb2 = min(lb2, (me && ws == s) ? kEmpty : cand[s]);
                 const float others = __uint_as_float(wave_min_u32(lb2));
                 const float bound = fmaxf(others, wm + lp0d);
                 myscore = NS + s_lp[row * Kp + min(c + lane, Kp - 1)];  // -inf past rank K-1
@@ -210,6 +221,10 @@ __global__ __launch_bounds__(kBuildThreads) void build_kernel(
                 J = min(J, N - n);
             }
             prev_p = p;
+            // the popped entry moves on to rank c + J ("push next sibling"): its new candidate and
+            // the log-probability after it
+            const float p_inc = J == 1 ? NL : s_lp[row * Kp + min(c + J, Kp - 1)];  // -inf once c+J >= K
+            const float p_nlp1 = s_lp[row * Kp + min(c + J + 1, Kp - 1)];
             // records of nodes n+1 .. n+J
             if (lane < J) {
                 s_node[n + 1 + lane] = pack_node(p, c + lane, d);
@@ -219,30 +234,19 @@ __global__ __launch_bounds__(kBuildThreads) void build_kernel(
             // slot e / 64; lane j's score travels there
             const int j_here = (lane - (n + 1)) & 63;
             const float sc_e = J == 1 ? wm : __shfl(myscore, j_here, 64);
-            if (j_here < J) {
-                const int slot_e = (n + 1 + j_here) >> 6;
+            const int slot_e = j_here < J ? (n + 1 + j_here) >> 6 : -1;
+            const uint32_t e_cand = __float_as_uint(sc_e + lp0d);  // -inf once d == B
+            const uint32_t p_cand = __float_as_uint(NS + p_inc);
+            const int p_meta = M + (J << 8);
 #pragma unroll
-                for (int s = 0; s < NSLOT; ++s)
-                    if (slot_e == s) {
-                        cand[s] = __float_as_uint(sc_e + lp0d);  // -inf once d == B
-                        nsc[s] = sc_e;
-                        nlp1[s] = lp1d;
-                        meta[s] = d;  // rank 0, children read row d
-                    }
+            for (int s = 0; s < NSLOT; ++s) {
+                const bool fresh = slot_e == s;
+                const bool popped = me && ws == s;
+                cand[s] = fresh ? e_cand : popped ? p_cand : cand[s];
+                nsc[s] = fresh ? sc_e : nsc[s];
+                nlp1[s] = fresh ? lp1d : popped ? p_nlp1 : nlp1[s];
+                meta[s] = fresh ? d : popped ? p_meta : meta[s];  // fresh: rank 0, children read row d
             }
-            // the popped entry moves on to rank c + J ("push next sibling")
-#pragma unroll
-            for (int s = 0; s < NSLOT; ++s)
-                if (ws == s && me) {
-                    if (J == 1) {
-                        cand[s] = __float_as_uint(nsc[s] + nlp1[s]);  // -inf once c+1 == K
-                        nlp1[s] = s_lp[row * Kp + c + 2];
-                    } else {
-                        cand[s] = __float_as_uint(nsc[s] + s_lp[row * Kp + min(c + J, Kp - 1)]);
-                        nlp1[s] = s_lp[row * Kp + min(c + J + 1, Kp - 1)];
-                    }
-                    meta[s] += J << 8;
-                }
             n += J;
         }
         if (lane == 0) s_built = n;
