@@ -170,6 +170,50 @@ def accept(target_logits, tokens, parent, n_nodes, B):
     return dict(path=path, n_accepted=int(n_acc.value), bonus=int(bonus.value), posterior=post)
 
 
+def sample_uniform(seed, row, v):
+    """The uniform in (0,1) that the sampled walk draws for (seed, row, v)."""
+    f = _load().oracle_sample_uniform
+    f.restype = ctypes.c_double
+    f.argtypes = [ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32]
+    return float(f(int(seed), int(row), int(v)))
+
+
+def sample_tokens(target_logits, n_nodes, temperature, seed, first_row=0):
+    """Token the target selects at every node when sampling at `temperature` (Gumbel-max, fp64).
+    Returns (token int32 [T], runner_up int32 [T], gap float64 [T]); rows past n_nodes get -1."""
+    target_logits = _c(target_logits, np.float32)
+    T, V = target_logits.shape
+    tok = np.empty(T, np.int32)
+    run = np.empty(T, np.int32)
+    gap = np.empty(T, np.float64)
+    f = _load().oracle_sample_tokens
+    f.restype = ctypes.c_int
+    f.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                  ctypes.c_double, ctypes.c_uint64, ctypes.c_int, ctypes.POINTER(ctypes.c_int32),
+                  ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_double)]
+    rc = f(_p(target_logits, ctypes.c_float), T, V, int(n_nodes), float(temperature), int(seed),
+           int(first_row), _p(tok, ctypes.c_int32), _p(run, ctypes.c_int32), _p(gap, ctypes.c_double))
+    if rc != 0:
+        raise ValueError(f"oracle_sample_tokens failed: {rc}")
+    return tok, run, gap
+
+
+def walk(selected, tokens, parent, n_nodes, B):
+    """The verifier walk given the token selected at every node.  Returns dict(path, n_accepted, bonus)."""
+    selected = _c(selected, np.int32)
+    tokens = _c(tokens, np.int32)
+    parent = _c(parent, np.int32)
+    path = np.empty(B + 1, np.int32)
+    n_acc = ctypes.c_int32(0)
+    bonus = ctypes.c_int32(0)
+    rc = _load().oracle_walk(_p(selected, ctypes.c_int32), _p(tokens, ctypes.c_int32),
+                             _p(parent, ctypes.c_int32), int(n_nodes), int(B), _p(path, ctypes.c_int32),
+                             ctypes.byref(n_acc), ctypes.byref(bonus))
+    if rc != 0:
+        raise ValueError(f"oracle_walk failed: {rc}")
+    return dict(path=path, n_accepted=int(n_acc.value), bonus=int(bonus.value))
+
+
 def compact(tree_rows, path, n_accepted, cache, L):
     """Append tree rows path[0..n_accepted] to cache (fp32 [>=L+n_accepted+1, ...]) in place."""
     tree_rows = _c(tree_rows, np.float32)

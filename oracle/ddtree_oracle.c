@@ -420,6 +420,98 @@ int oracle_accept(const float *target_logits, int T, int V, const int32_t *token
 }
 
 /*
+ * Section 4.4, second paragraph: verification "follows the target model's own decoding rule,
+ * whether greedy or temperature-based sampling".  At temperature tau > 0 the token the target
+ * selects at node i is a sample from softmax(target_logits[i] / tau).  The sample is drawn by
+ * the Gumbel-max rule, argmax_v (logit[v] / tau + g[v]) with g = -log(-log(u)) and u uniform on
+ * (0,1), which is distributed exactly as that softmax; u comes from a counter-based generator
+ * keyed by (seed, row, v) so that the draw does not depend on any order of evaluation:
+ *     mix(x):  x ^= x >> 16; x *= 0x7feb352d; x ^= x >> 15; x *= 0x846ca68b; x ^= x >> 16
+ *     h = mix(mix(v ^ seed_lo) + 0x9E3779B9 * row + seed_hi)          (32-bit arithmetic)
+ *     u = ((h >> 8) + 0.5) / 2^24
+ * with row = first_row + i.  Everything here is fp64.  Besides the selected token the function
+ * reports the runner-up and the gap between their keys, so that a caller comparing against an
+ * fp32 implementation knows which decisions are closer than fp32 can resolve.
+ */
+static uint32_t sample_mix(uint32_t x)
+{
+    x ^= x >> 16;
+    x *= 0x7feb352du;
+    x ^= x >> 15;
+    x *= 0x846ca68bu;
+    x ^= x >> 16;
+    return x;
+}
+
+double oracle_sample_uniform(uint64_t seed, uint32_t row, uint32_t v)
+{
+    const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
+    const uint32_t h = sample_mix(sample_mix(v ^ lo) + 0x9E3779B9u * row + hi);
+    return ((double)(h >> 8) + 0.5) / 16777216.0;
+}
+
+int oracle_sample_tokens(const float *target_logits, int T, int V, int n_nodes, double temperature,
+                         uint64_t seed, int first_row, int32_t *token, int32_t *runner_up,
+                         double *gap)
+{
+    if (T < 1 || V < 1 || n_nodes + 1 > T || !(temperature > 0.0)) return -1;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < T; ++i) {
+        if (i > n_nodes) {
+            token[i] = -1;
+            if (runner_up) runner_up[i] = -1;
+            if (gap) gap[i] = 0.0;
+            continue;
+        }
+        const float *row = target_logits + (size_t)i * V;
+        int best = -1, second = -1;
+        double kbest = 0.0, ksecond = 0.0;
+        for (int v = 0; v < V; ++v) {
+            const double u = oracle_sample_uniform(seed, (uint32_t)(first_row + i), (uint32_t)v);
+            const double key = (double)row[v] / temperature - log(-log(u));
+            if (best < 0 || key > kbest) {
+                second = best;
+                ksecond = kbest;
+                best = v;
+                kbest = key;
+            } else if (second < 0 || key > ksecond) {
+                second = v;
+                ksecond = key;
+            }
+        }
+        token[i] = best;
+        if (runner_up) runner_up[i] = second;
+        if (gap) gap[i] = second >= 0 ? kbest - ksecond : INFINITY;
+    }
+    return 0;
+}
+
+/* The walk of Section 4.4 with `selected[i]` as the token the target chose at node i. */
+int oracle_walk(const int32_t *selected, const int32_t *tokens, const int32_t *parent, int n_nodes,
+                int B, int32_t *path, int32_t *n_accepted, int32_t *bonus)
+{
+    if (B < 1) return -1;
+    for (int s = 0; s <= B; ++s) path[s] = -1;
+    int cur = 0, len = 0;
+    path[0] = 0;
+    for (;;) {
+        int next = -1;
+        for (int c = 1; c <= n_nodes; ++c) {
+            if (parent[c] == cur && tokens[c] == selected[cur]) {
+                next = c;
+                break;
+            }
+        }
+        if (next < 0 || len >= B) break;
+        cur = next;
+        path[++len] = cur;
+    }
+    *n_accepted = len;
+    *bonus = selected[cur];
+    return 0;
+}
+
+/*
  * Section 4.4, last sentence: after the walk the cache keeps only the accepted
  * path.  Rows path[0..n_accepted] of the tree K (or V) are appended to the
  * cache at rows L, L+1, ...; row_elems = Hkv * D.
