@@ -147,6 +147,25 @@ int ddtree_accept(const float *target_logits, int batch, int T, int V, const int
                   int B, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The same walk at temperature > 0 (Section 4.4, second paragraph: verification follows the
+ * target model's own decoding rule, greedy or temperature-based sampling).  The token the target
+ * selects at node i is a sample from softmax(target_logits[i] / temperature), drawn by the
+ * Gumbel-max rule argmax_v (logit[v] / temperature - log(-log u)) with u in (0,1) from a
+ * counter-based generator keyed by (seed, row s*T+i, v):
+ *     mix(x):  x ^= x >> 16; x *= 0x7feb352d; x ^= x >> 15; x *= 0x846ca68b; x ^= x >> 16
+ *     h = mix(mix(v ^ seed_lo) + 0x9E3779B9 * row + seed_hi),   u = ((h >> 8) + 0.5) / 2^24
+ * so a (seed, row) pair always selects the same token, whatever the launch shape.  Keys are
+ * formed in fp32; two tokens whose keys differ by less than about 1e-4 may be selected either way.
+ * posterior receives the selected tokens.  Arguments otherwise as in ddtree_accept;
+ * temperature must be positive and finite (DDTREE_ERR_ARG otherwise).
+ */
+int ddtree_accept_sampled(const float *target_logits, int batch, int T, int V,
+                          const int32_t *tokens, const int32_t *parent, const int32_t *depth,
+                          const int32_t *n_nodes, float temperature, uint64_t seed, int32_t *path,
+                          int32_t *n_accepted, int32_t *bonus_token, int32_t *posterior, int B,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Cache compaction (Section 4.4, last sentence): the cache keeps only the accepted path.  For
  * every sequence s and j = 0..n_accepted[s]: cache[dst_row[s] + j] = tree[s*T + path[s][j]]
  * (j = 0 is the root, whose key/value rows were not in the cache before this round).

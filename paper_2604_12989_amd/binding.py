@@ -27,6 +27,8 @@ _SIGNATURES = {
                                 ctypes.c_float, _i, _vp, _vp, _sz, _vp]),
     "ddtree_accept": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _sz,
                            _vp]),
+    "ddtree_accept_sampled": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, ctypes.c_float,
+                                   ctypes.c_uint64, _vp, _vp, _vp, _vp, _i, _vp, _sz, _vp]),
     "ddtree_compact": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp]),
     "ddtree_profile_enable": (_i, [ctypes.c_uint, _i]),
     "ddtree_profile_reset": (_i, []),
@@ -201,8 +203,10 @@ def verify_attn(q, k_cache, v_cache, k_tree, v_tree, ancestor_mask, kv_offset, b
 
 
 def accept(target_logits, tokens, parent, depth, n_nodes, B, ws, out=None, want_posterior=True,
-           defer=False):
-    """target_logits fp32 [batch,T,V] -> dict(path [batch,B+1], n_accepted, bonus_token, posterior)."""
+           defer=False, temperature=None, seed=0):
+    """target_logits fp32 [batch,T,V] -> dict(path [batch,B+1], n_accepted, bonus_token, posterior).
+    temperature=None: greedy rule (ddtree_accept); a positive temperature: sampled selection
+    (ddtree_accept_sampled) with the given 64-bit seed."""
     _dev(target_logits, torch.float32, "target_logits")
     batch, T, V = target_logits.shape
     dev = target_logits.device
@@ -213,6 +217,12 @@ def accept(target_logits, tokens, parent, depth, n_nodes, B, ws, out=None, want_
                    posterior=(torch.empty((batch, T), dtype=torch.int32, device=dev)
                               if want_posterior else None))
     p, n = _ws(ws)
+    if temperature is not None:
+        args = (_ptr(target_logits), batch, T, V, _ptr(tokens), _ptr(parent), _ptr(depth),
+                _ptr(n_nodes), ctypes.c_float(float(temperature)), ctypes.c_uint64(int(seed)),
+                _ptr(out["path"]), _ptr(out["n_accepted"]), _ptr(out["bonus_token"]),
+                _ptr(out.get("posterior")), B, p, n, _stream())
+        return _call("ddtree_accept_sampled", args, out, defer)
     args = (_ptr(target_logits), batch, T, V, _ptr(tokens), _ptr(parent), _ptr(depth),
             _ptr(n_nodes), _ptr(out["path"]), _ptr(out["n_accepted"]), _ptr(out["bonus_token"]),
             _ptr(out.get("posterior")), B, p, n, _stream())

@@ -47,9 +47,48 @@ __device__ __forceinline__ void arg_update(float &bv, int &bi, float v, int i)
     }
 }
 
+// Temperature sampling (Section 4.4: verification follows the target's decoding rule, greedy or
+// temperature-based sampling).  The token selected at a node is argmax_v (logit[v] / tau + g[v])
+// with Gumbel noise g = -log(-log(u)), which is a sample from softmax(logit / tau); u in (0,1)
+// comes from a counter-based generator keyed by (seed, row, v), so the draw does not depend on
+// how the scan is split over threads:
+//     mix(x):  x ^= x >> 16; x *= 0x7feb352d; x ^= x >> 15; x *= 0x846ca68b; x ^= x >> 16
+//     h = mix(mix(v ^ seed_lo) + 0x9E3779B9 * row + seed_hi),   u = ((h >> 8) + 0.5) / 2^24
+struct SampleArgs {
+    float inv_tau;       // 0 selects the greedy rule
+    uint32_t seed_lo, seed_hi;
+};
+__device__ __forceinline__ uint32_t sample_mix(uint32_t x)
+{
+    x ^= x >> 16;
+    x *= 0x7feb352du;
+    x ^= x >> 15;
+    x *= 0x846ca68bu;
+    x ^= x >> 16;
+    return x;
+}
+template <bool SAMPLE>
+__device__ __forceinline__ float select_key(float logit, uint32_t id, uint32_t row_term, const SampleArgs &sa)
+{
+    if (!SAMPLE) return logit;
+    const uint32_t h = sample_mix(sample_mix(id ^ sa.seed_lo) + row_term);
+    // -ln u in fp32 without losing the draws that matter most (u close to 1 gives the largest
+    // noise): for k < 2^23, u = (k + 0.5) / 2^24 is exact in fp32; otherwise w = 1 - u =
+    // (2^24 - 1 - k + 0.5) / 2^24 is, and -ln(1 - w) is taken from its series when w is small
+    const uint32_t k = h >> 8;
+    const bool low = k < (1u << 23);
+    const float frac = ((float)(low ? k : 16777215u - k) + 0.5f) * (1.0f / 16777216.0f);  // u or w
+    const float la = -0.69314718056f * __builtin_amdgcn_logf(low ? frac : 1.0f - frac);
+    const float series = frac * (1.0f + frac * (0.5f + frac * (0.333333343f + frac * 0.25f)));
+    const float nl = (!low && frac < 0.015625f) ? series : la;
+    const float g = -0.69314718056f * __builtin_amdgcn_logf(nl);  // g = -ln(-ln u)
+    return fmaf(logit, sa.inv_tau, g);
+}
+
+template <bool SAMPLE>
 __global__ __launch_bounds__(kArgmaxThreads) void accept_argmax_kernel(
     const float *__restrict__ logits, int T, int V, int seg_len, int splits,
-    const int32_t *__restrict__ n_nodes, ArgPart *__restrict__ part)
+    const int32_t *__restrict__ n_nodes, ArgPart *__restrict__ part, SampleArgs sa)
 {
     __shared__ float s_v[kArgmaxThreads / 64];
     __shared__ int s_i[kArgmaxThreads / 64];
@@ -57,6 +96,7 @@ __global__ __launch_bounds__(kArgmaxThreads) void accept_argmax_kernel(
     const int seg = blockIdx.x, i = blockIdx.y, seq = blockIdx.z;
     if (i > n_nodes[seq]) return;  // padding row: never read, the walk ignores its partial
     const size_t rowi = (size_t)seq * T + i;
+    const uint32_t row_term = 0x9E3779B9u * (uint32_t)rowi + sa.seed_hi;
     const int start = seg * seg_len;
     const int n = min(seg_len, V - start);
     const float *p = logits + rowi * (size_t)V + start;
@@ -66,7 +106,7 @@ __global__ __launch_bounds__(kArgmaxThreads) void accept_argmax_kernel(
     int head = (int)((4 - ((reinterpret_cast<uintptr_t>(p) >> 2) & 3)) & 3);
     if (head > n) head = n;
     if (tid < head) {
-        bv = p[tid];
+        bv = select_key<SAMPLE>(p[tid], (uint32_t)(start + tid), row_term, sa);
         bi = start + tid;
     }
     const int nvec = (n - head) >> 2;
@@ -93,15 +133,20 @@ __global__ __launch_bounds__(kArgmaxThreads) void accept_argmax_kernel(
 #pragma unroll
         for (int u = 0; u < kInFlight; ++u) {
             const int ia = start + head + 4 * (j0 + u * kArgmaxThreads);
-            if (x[u].x > bv) { bv = x[u].x; bi = ia; }
-            if (x[u].y > bv) { bv = x[u].y; bi = ia + 1; }
-            if (x[u].z > bv) { bv = x[u].z; bi = ia + 2; }
-            if (x[u].w > bv) { bv = x[u].w; bi = ia + 3; }
+            if (SAMPLE && j0 + u * kArgmaxThreads >= nvec) continue;  // padding lanes draw no noise
+            const float k0 = select_key<SAMPLE>(x[u].x, (uint32_t)ia, row_term, sa);
+            const float k1 = select_key<SAMPLE>(x[u].y, (uint32_t)ia + 1u, row_term, sa);
+            const float k2 = select_key<SAMPLE>(x[u].z, (uint32_t)ia + 2u, row_term, sa);
+            const float k3 = select_key<SAMPLE>(x[u].w, (uint32_t)ia + 3u, row_term, sa);
+            if (k0 > bv) { bv = k0; bi = ia; }
+            if (k1 > bv) { bv = k1; bi = ia + 1; }
+            if (k2 > bv) { bv = k2; bi = ia + 2; }
+            if (k3 > bv) { bv = k3; bi = ia + 3; }
         }
     }
     const int tail0 = head + 4 * nvec;
     if (tid < n - tail0) {
-        const float x = p[tail0 + tid];
+        const float x = select_key<SAMPLE>(p[tail0 + tid], (uint32_t)(start + tail0 + tid), row_term, sa);
         if (x > bv) { bv = x; bi = start + tail0 + tid; }
     }
 #pragma unroll
@@ -209,11 +254,11 @@ __global__ __launch_bounds__(256) void compact_kernel(
 
 }  // namespace ddt
 
-extern "C" int ddtree_accept(const float *target_logits, int batch, int T, int V,
-                             const int32_t *tokens, const int32_t *parent, const int32_t *depth,
-                             const int32_t *n_nodes, int32_t *path, int32_t *n_accepted,
-                             int32_t *bonus_token, int32_t *posterior, int B, void *workspace,
-                             size_t workspace_bytes, void *stream)
+static int accept_impl(const float *target_logits, int batch, int T, int V, const int32_t *tokens,
+                       const int32_t *parent, const int32_t *depth, const int32_t *n_nodes,
+                       int32_t *path, int32_t *n_accepted, int32_t *bonus_token, int32_t *posterior,
+                       int B, void *workspace, size_t workspace_bytes, void *stream, bool sample,
+                       ddt::SampleArgs sa)
 {
     using namespace ddt;
     if (!target_logits || !tokens || !parent || !depth || !n_nodes || !path || !n_accepted ||
@@ -226,11 +271,39 @@ extern "C" int ddtree_accept(const float *target_logits, int batch, int T, int V
     if (!ws_ok(workspace, workspace_bytes, p.bytes)) return DDTREE_ERR_WORKSPACE;
     ArgPart *part = reinterpret_cast<ArgPart *>(static_cast<char *>(workspace) + p.part_off);
     hipStream_t st = as_stream(stream);
-    DDT_LAUNCH(DDTREE_KERNEL_ACCEPT_ARGMAX, st, accept_argmax_kernel, dim3(p.splits, T, batch), dim3(kArgmaxThreads), 0, st,
-                       target_logits, T, V, p.seg_len, p.splits, n_nodes, part);
+    if (sample)
+        DDT_LAUNCH(DDTREE_KERNEL_ACCEPT_ARGMAX, st, accept_argmax_kernel<true>, dim3(p.splits, T, batch),
+                   dim3(kArgmaxThreads), 0, st, target_logits, T, V, p.seg_len, p.splits, n_nodes, part, sa);
+    else
+        DDT_LAUNCH(DDTREE_KERNEL_ACCEPT_ARGMAX, st, accept_argmax_kernel<false>, dim3(p.splits, T, batch),
+                   dim3(kArgmaxThreads), 0, st, target_logits, T, V, p.seg_len, p.splits, n_nodes, part, sa);
     DDT_LAUNCH(DDTREE_KERNEL_ACCEPT_WALK, st, accept_walk_kernel, dim3(batch), dim3(kWalkThreads), 0, st, part, T, p.splits,
                        B, tokens, parent, depth, n_nodes, path, n_accepted, bonus_token, posterior);
     return launch_status();
+}
+
+extern "C" int ddtree_accept(const float *target_logits, int batch, int T, int V,
+                             const int32_t *tokens, const int32_t *parent, const int32_t *depth,
+                             const int32_t *n_nodes, int32_t *path, int32_t *n_accepted,
+                             int32_t *bonus_token, int32_t *posterior, int B, void *workspace,
+                             size_t workspace_bytes, void *stream)
+{
+    return accept_impl(target_logits, batch, T, V, tokens, parent, depth, n_nodes, path, n_accepted,
+                       bonus_token, posterior, B, workspace, workspace_bytes, stream, false,
+                       ddt::SampleArgs{0.0f, 0u, 0u});
+}
+
+extern "C" int ddtree_accept_sampled(const float *target_logits, int batch, int T, int V,
+                                     const int32_t *tokens, const int32_t *parent,
+                                     const int32_t *depth, const int32_t *n_nodes, float temperature,
+                                     uint64_t seed, int32_t *path, int32_t *n_accepted,
+                                     int32_t *bonus_token, int32_t *posterior, int B,
+                                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!(temperature > 0.0f) || !(temperature < 1e30f)) return DDTREE_ERR_ARG;
+    return accept_impl(target_logits, batch, T, V, tokens, parent, depth, n_nodes, path, n_accepted,
+                       bonus_token, posterior, B, workspace, workspace_bytes, stream, true,
+                       ddt::SampleArgs{1.0f / temperature, (uint32_t)seed, (uint32_t)(seed >> 32)});
 }
 
 extern "C" int ddtree_compact(const void *k_tree, const void *v_tree, const int32_t *path,

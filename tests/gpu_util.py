@@ -66,12 +66,13 @@ def gpu_attn(q, kc, vc, kt, vt, mask, kv_offset, batch, T, dtype, scale=None):
     return out.float().cpu().numpy().reshape(batch, T, Hq, D)
 
 
-def gpu_accept(target_logits, tokens, parent, depth, n_nodes, B):
+def gpu_accept(target_logits, tokens, parent, depth, n_nodes, B, temperature=None, seed=0):
     x = target_logits if target_logits.ndim == 3 else target_logits[None]
     batch, T, V = x.shape
     f = lambda a: to_dev(np.asarray(a, np.int32).reshape(batch, -1))
     ws = ws_for(batch, B, V, T - 1)
     out = dd.accept(to_dev(x), f(tokens), f(parent), f(depth),
-                    to_dev(np.asarray(n_nodes, np.int32).reshape(batch)), B, ws)
+                    to_dev(np.asarray(n_nodes, np.int32).reshape(batch)), B, ws,
+                    temperature=temperature, seed=seed)
     torch.cuda.synchronize()
     return {k: v.cpu().numpy() for k, v in out.items()}

@@ -195,3 +195,31 @@ def test_attention_retry_when_scores_outgrow_the_reference():
     err = float((np.abs(got - ref) / np.maximum(1.0, np.abs(ref))).max())
     print(f"retry case: max err {err:.2e}")
     assert err < 1e-2
+
+
+def test_sampled_walk_full_size_config3():
+    """Temperature sampling at the headline shape (257 rows x 151936 tokens, the launch shape of
+    the greedy scan): every selection against the oracle's fp64 Gumbel-max, the walk exactly."""
+    c = di.CONFIGS[3]
+    seed = di.config_seed(3, 2)
+    B, V, N = c["B"], c["V"], c["N"]
+    T = N + 1
+    x = di.draft_logits(seed, B, V)
+    tok_o, lp_o = oracle.topk(x, N)
+    tr = oracle.build_tree(tok_o, lp_o, N, 11)
+    plant = di.planted_tokens(seed, tr["depth"], tok_o[:, 0], B)
+    tl = di.target_logits(seed, T, V, plant)
+    for tau, s in ((1.0, 2026), (0.25, 7)):
+        got = gu.gpu_accept(tl, tr["tokens"], tr["parent"], tr["depth"], tr["n_nodes"], B,
+                            temperature=tau, seed=s)
+        sel, run, gap = oracle.sample_tokens(tl, tr["n_nodes"], tau, s)
+        post = got["posterior"][0]
+        clear = gap > 2e-4
+        assert clear.sum() >= T - 3
+        assert np.array_equal(post[clear], sel[clear])
+        assert np.all((post[~clear] == sel[~clear]) | (post[~clear] == run[~clear]))
+        w = oracle.walk(post, tr["tokens"], tr["parent"], tr["n_nodes"], B)
+        assert int(got["n_accepted"][0]) == w["n_accepted"]
+        assert int(got["bonus_token"][0]) == w["bonus"]
+        assert np.array_equal(got["path"][0], w["path"])
+        print(f"tau={tau}: accepted {w['n_accepted']}, {int((~clear).sum())} close selections")

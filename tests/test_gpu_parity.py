@@ -427,3 +427,82 @@ def test_end_to_end_chain(config):
         assert np.array_equal(ga["path"][0], acc_o["path"])
         assert int(ga["n_accepted"][0]) == acc_o["n_accepted"]
         assert int(ga["bonus_token"][0]) == acc_o["bonus"]
+
+
+# ------------------------------------------------------------------------------- sampled walk
+# fp32 keys on the GPU against fp64 keys in the oracle: a selection is compared where the oracle's
+# gap between winner and runner-up exceeds what fp32 can blur (logit/tau up to ~50 in magnitude:
+# 2^-24 * 50 * a few operations, plus the hardware log2 at 1 ulp), and must be one of the two
+# candidates where it does not.
+SAMPLE_GAP_TOL = 2e-4
+
+
+def _check_sampled(tl, tokens, parent, depth, n_nodes, B, tau, seed, batch_rows=None):
+    got = gu.gpu_accept(tl, tokens, parent, depth, n_nodes, B, temperature=tau, seed=seed)
+    x = tl if tl.ndim == 3 else tl[None]
+    tok2 = np.asarray(tokens).reshape(x.shape[0], -1)
+    par2 = np.asarray(parent).reshape(x.shape[0], -1)
+    nn = np.asarray(n_nodes).reshape(-1)
+    close = 0
+    for b in range(x.shape[0]):
+        T = x.shape[1]
+        sel, run, gap = oracle.sample_tokens(x[b], int(nn[b]), tau, seed, first_row=b * T)
+        post = got["posterior"][b]
+        clear = gap > SAMPLE_GAP_TOL
+        assert np.array_equal(post[clear], sel[clear])
+        assert np.all((post[~clear] == sel[~clear]) | (post[~clear] == run[~clear]))
+        close += int((~clear).sum())
+        # the walk is exact given the GPU's own selection
+        w = oracle.walk(post, tok2[b], par2[b], int(nn[b]), B)
+        assert int(got["n_accepted"][b]) == w["n_accepted"]
+        assert int(got["bonus_token"][b]) == w["bonus"]
+        assert np.array_equal(got["path"][b], w["path"])
+    return got, close
+
+
+@pytest.mark.parametrize("tau", [0.3, 1.0, 2.0])
+def test_accept_sampled_matches_oracle(tau):
+    rng = np.random.default_rng(31)
+    T, V, B = 65, 50001, 8
+    n = T - 1
+    par = np.full(T, -1, np.int32)
+    depth = np.zeros(T, np.int32)
+    for i in range(1, T):                       # a random tree no deeper than B
+        ok = np.flatnonzero(depth[:i] < B)
+        par[i] = i - 1 if (depth[i - 1] < B and rng.random() < 0.5) else rng.choice(ok)
+        depth[i] = depth[par[i]] + 1
+    tokens = rng.integers(0, V, T).astype(np.int32)
+    tl = (rng.standard_normal((T, V)) * 2.0).astype(np.float32)
+    got, close = _check_sampled(tl, tokens, par, depth, n, B, tau, seed=0xC0FFEE12345)
+    print(f"tau={tau}: {close} of {n + 1} selections closer than the fp32 tolerance")
+    # a different seed draws different tokens; the same seed repeats them
+    again = gu.gpu_accept(tl, tokens, par, depth, n, B, temperature=tau, seed=0xC0FFEE12345)
+    other = gu.gpu_accept(tl, tokens, par, depth, n, B, temperature=tau, seed=7)
+    assert np.array_equal(again["posterior"], got["posterior"])
+    assert np.mean(other["posterior"][0][: n + 1] == got["posterior"][0][: n + 1]) < 0.5
+
+
+def test_accept_sampled_walks_down_a_planted_chain_and_batches():
+    # two sequences; in the first a chain of tokens dominates its rows (logit + 60: sampled with
+    # probability ~1 at tau = 1), so the walk must descend it; the second has nothing planted
+    rng = np.random.default_rng(32)
+    T, V, B = 7, 20000, 6
+    par = np.stack([np.arange(-1, T - 1), np.arange(-1, T - 1)]).astype(np.int32)   # chains
+    depth = np.stack([np.arange(T), np.arange(T)]).astype(np.int32)
+    tokens = rng.integers(0, V, (2, T)).astype(np.int32)
+    tl = rng.standard_normal((2, T, V)).astype(np.float32)
+    for i in range(4):
+        tl[0, i, tokens[0, i + 1]] += 60.0
+    got, _ = _check_sampled(tl, tokens, par, depth, np.array([T - 1, T - 1]), B, 1.0, seed=5)
+    assert int(got["n_accepted"][0]) >= 4
+    assert list(got["path"][0][:5]) == [0, 1, 2, 3, 4]
+
+
+def test_accept_sampled_rejects_bad_temperature():
+    import paper_2604_12989_amd as dd
+    x = np.zeros((1, 3, 8), np.float32)
+    z = np.zeros((1, 3), np.int32)
+    for bad in (0.0, -1.0, float("inf"), float("nan")):
+        with pytest.raises(dd.DDTreeError):
+            gu.gpu_accept(x, z, z, z, np.array([2]), 2, temperature=bad, seed=1)
+
