@@ -8,8 +8,8 @@
 //                        vector ALUs; used for the small fp32 configuration and odd shapes.
 //
 // MFMA kernel.  Query rows of one KV head are the (node, group-head) pairs, G = Hq/Hkv per node,
-// so one K/V tile serves G*T rows.  A workgroup (4 waves) owns 256 consecutive rows (64 per
-// wave) and a contiguous range of 64-key tiles (split-KV; partial results are merged by
+// so one K/V tile serves G*T rows.  A workgroup (8 waves, two per SIMD) owns 256 consecutive
+// rows (32 per wave) and a contiguous range of 64-key tiles (split-KV; partial results are merged by
 // attn_merge_kernel).  Per tile:
 //   S^T = K Q^T   v_mfma_f32_32x32x16_bf16, A = K tile from LDS (row = key), B = Q^T held in
 //                 registers for the whole kernel.  In the accumulator layout a lane then owns
@@ -34,7 +34,13 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kAttnThreads = 256;
+// Blocks of 32 query rows per wave.  1: eight waves of 32 rows, two waves per SIMD with 256
+// registers each, so that one wave's waits (LDS, matrix results, barrier) are filled by the other;
+// 2: four waves of 64 rows with 512 registers each (half the LDS reads per matrix instruction, but
+// nothing to fill a stall with; measured slower).
+constexpr int kCB = 1;
+constexpr int kWaves = 8 / kCB;
+constexpr int kAttnThreads = 64 * kWaves;
 constexpr int kMT = 256;       // query rows per workgroup
 constexpr int kKT = 64;        // keys per tile
 constexpr int kHD = 128;       // head dim of the MFMA path
@@ -185,7 +191,7 @@ __device__ __forceinline__ void lds_wait_v(u32x2 (&v)[2][4][2])
 
 constexpr float kRefSlack = 64.0f;  // log2 units a row's scores may exceed its softmax reference
 
-__global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+__global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_cache,
                       const uint16_t *__restrict__ v_cache, const uint16_t *__restrict__ k_tree,
                       const uint16_t *__restrict__ v_tree, const uint64_t *__restrict__ mask,
@@ -222,7 +228,7 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     const int M = T * G;
     const int L0 = args.kv_offset[seq];
     const int L = args.kv_offset[seq + 1] - L0;
-    // this tile's blocks of 32 rows: wave w owns blocks 2w and 2w+1 of the tile
+    // this tile's blocks of 32 rows: wave w owns blocks kCB*w .. kCB*w + kCB - 1 of the tile
     const int first_blk = mt * blk_base + min(mt, blk_extra);
     const int n_blk = blk_base + (mt < blk_extra ? 1 : 0);
     const int m0 = first_blk * 32;
@@ -233,14 +239,14 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     const int nt = n_cache_tiles + n_tree_tiles;
     const int t_begin = (int)((long long)nt * split / splits);
     const int t_end = (int)((long long)nt * (split + 1) / splits);
-    const bool wave_active = m0 + wave * 64 < m_end;
+    const bool wave_active = m0 + wave * 32 * kCB < m_end;
 
     // this lane's two query rows (cb = 0, 1)
-    int node_[2], rowg_[2];
-    bool rvalid[2];
+    int node_[kCB], rowg_[kCB];
+    bool rvalid[kCB];
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
-        const int r = m0 + wave * 64 + cb * 32 + l32;
+    for (int cb = 0; cb < kCB; ++cb) {
+        const int r = m0 + wave * 32 * kCB + cb * 32 + l32;
         rvalid[cb] = r < m_end;
         const int node = rvalid[cb] ? r / G : 0;
         const int g = rvalid[cb] ? r - node * G : 0;
@@ -248,40 +254,49 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         rowg_[cb] = (seq * T + node) * Hq + hk * G + g;
     }
     // Q^T operand: lane holds Q[row][16*ks + 8*half .. +8]
-    bf16x8 qreg[2][8];
+    bf16x8 qreg[kCB][8];
+    bool real_[kCB];  // the row's node is a real tree node (it sees itself)
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
+    for (int cb = 0; cb < kCB; ++cb) {
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             uint4 v = make_uint4(0, 0, 0, 0);
             if (rvalid[cb])
                 v = *reinterpret_cast<const uint4 *>(q + (size_t)rowg_[cb] * kHD + ks * 16 + half * 8);
             qreg[cb][ks] = __builtin_bit_cast(bf16x8, v);
-            // the query operand is only ever read by MFMA: park it in the accumulator file
-            asm volatile("" : "+a"(qreg[cb][ks]));
         }
+        const int node = node_[cb];
+        real_[cb] = rvalid[cb] && ((mask[((size_t)seq * T + node) * W + (node >> 6)] >> (node & 63)) & 1ull);
+    }
 
-    floatx16 o[4][2];
+    floatx16 o[4][kCB];
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
+        for (int cb = 0; cb < kCB; ++cb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) o[db][cb][v] = 0.0f;
-    float m_run[2] = {-INFINITY, -INFINITY};   // softmax reference of the row (log2 units)
-    float m_seen[2] = {-INFINITY, -INFINITY};  // true running maximum of the row
-    float l_run[2] = {0.0f, 0.0f};
+    float m_run[kCB];   // softmax reference of the row (log2 units)
+    float m_seen[kCB];  // true running maximum of the row
+    float l_run[kCB];
+#pragma unroll
+    for (int cb = 0; cb < kCB; ++cb) {
+        m_run[cb] = -INFINITY;
+        m_seen[cb] = -INFINITY;
+        l_run[cb] = 0.0f;
+    }
     bool overflow = false;
 
-    // ---- tile loads: DMA block b (1 KB of LDS) is issued by wave b % 4; lane l of the block fills
+    // ---- tile loads: DMA block b (1 KB of LDS) is issued by wave b % kWaves; lane l of the block fills
     //      16-byte slot u = 64*b + l, i.e. row u / chunks_per_row, chunk u % chunks_per_row.
     //      The per-lane source offsets (bytes from the tile's first key) are computed once. ----
     const uint32_t row_bytes = (uint32_t)Hkv * kHD * 2;  // bytes between consecutive keys in global memory
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    uint32_t k_src[5], v_src[5];   // block 4*i + wave
+    constexpr int kFull = 16 / kWaves;
+    uint32_t k_src[kFull + 1], v_src[kFull + 1];   // block kWaves*i + wave
 #pragma unroll
-    for (int i = 0; i < 5; ++i) {
-        const int u = (4 * i + wave) * 64 + lane;
+    for (int i = 0; i < kFull + 1; ++i) {
+        const int u = (kWaves * i + wave) * 64 + lane;
         const int rk = (u * 241) >> 12;   // u / 17 for u < 2048
         const int ck = u - rk * 17;
         k_src[i] = (uint32_t)rk * row_bytes + (ck == 16 ? 0 : ck) * 16;  // padding slot: any chunk
@@ -301,27 +316,27 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         unsigned char *st = smem + stage * kStageBytes;
         if (valid_ == kKT) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < kFull; ++i) {
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kp + k_src[i]),
-                                                 (__attribute__((address_space(3))) void *)(st + (4 * i + wave_u) * 1024),
+                                                 (__attribute__((address_space(3))) void *)(st + (kWaves * i + wave_u) * 1024),
                                                  16, 0, 0);
                 __builtin_amdgcn_global_load_lds(
                     (const __attribute__((address_space(1))) void *)(vp + v_src[i]),
-                    (__attribute__((address_space(3))) void *)(st + kKTileBytes + (4 * i + wave_u) * 1024), 16, 0, 0);
+                    (__attribute__((address_space(3))) void *)(st + kKTileBytes + (kWaves * i + wave_u) * 1024), 16, 0, 0);
             }
             if (wave_u < 1)  // K: 17 blocks
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kp + k_src[4]),
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kp + k_src[kFull]),
                                                  (__attribute__((address_space(3))) void *)(st + 16 * 1024), 16, 0, 0);
             if (wave_u < 2)  // V: 18 blocks
                 __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)(vp + v_src[4]),
+                    (const __attribute__((address_space(1))) void *)(vp + v_src[kFull]),
                     (__attribute__((address_space(3))) void *)(st + kKTileBytes + (16 + wave_u) * 1024), 16, 0, 0);
         } else {
             // ragged tile (at most two per key range): rows past the end re-read the last valid
             // row, so that the LDS tile holds finite data everywhere
 #pragma unroll 1
-            for (int i = 0; i < 5; ++i) {
-                const int blk = 4 * i + wave_u;
+            for (int i = 0; i < kFull + 1; ++i) {
+                const int blk = kWaves * i + wave_u;
                 const int u = blk * 64 + lane;
                 if (blk < 17) {
                     const int r = (u * 241) >> 12, c = u - r * 17;
@@ -354,8 +369,8 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     // V columns of one sub-tile (2 k-steps x 4 dim blocks x 2 transposing reads).
     u32x4 kbuf[8];
     u32x2 vbuf[2][4][2];
-    floatx16 sc[2];     // scores of the sub-tile in flight, per query block cb
-    bf16x8 pb[2][2][2];  // P^T operands, double buffered by sub-tile parity: [parity][cb][k-step]
+    floatx16 sc[kCB];     // scores of the sub-tile in flight, per query block cb
+    bf16x8 pb[2][kCB][2];  // P^T operands, double buffered by sub-tile parity: [parity][cb][k-step]
 
     // K operand reads of sub-tile kb of the tile at LDS address tile_addr
     auto issue_k = [&](uint32_t tile_addr, auto KB) __attribute__((always_inline)) {
@@ -374,29 +389,29 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         });
     };
     // S^T sub-tile = K Q^T from the staged K operands
-    auto qk = [&](floatx16 (&sd)[2]) __attribute__((always_inline)) {
+    auto qk = [&](floatx16 (&sd)[kCB]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
+        for (int cb = 0; cb < kCB; ++cb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) sd[cb][v] = 0.0f;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             const bf16x8 a = __builtin_bit_cast(bf16x8, kbuf[ks]);
 #pragma unroll
-            for (int cb = 0; cb < 2; ++cb)
+            for (int cb = 0; cb < kCB; ++cb)
                 sd[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[cb][ks], sd[cb], 0, 0, 0);
         }
     };
     // Mask (apply_mask: tree tiles and ragged ends only; kb selects the half of the tile's 64-bit
     // mask word) and softmax of one sub-tile (32 keys): sd -> P^T operands, updating m_run /
     // l_run and flagging rows that outgrow their reference.
-    auto apply_mask = [&](floatx16 (&sd)[2], int t, int kb) __attribute__((always_inline)) {
+    auto apply_mask = [&](floatx16 (&sd)[kCB], int t, int kb) __attribute__((always_inline)) {
         const bool is_tree = t >= n_cache_tiles;
         const int tb = t - n_cache_tiles;
         const int valid = is_tree ? min(kKT, T - tb * kKT) : min(kKT, L - t * kKT);
         if (is_tree || valid < kKT) {  // tree tiles and a ragged last cache tile only
 #pragma unroll
-            for (int cb = 0; cb < 2; ++cb) {
+            for (int cb = 0; cb < kCB; ++cb) {
                 uint64_t word = ~0ull;
                 if (is_tree) word = rvalid[cb] ? mask[((size_t)seq * T + node_[cb]) * W + tb] : 0ull;
                 if (valid < kKT) word &= (1ull << valid) - 1ull;
@@ -409,9 +424,9 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             }
         }
     };
-    auto softmax = [&](floatx16 (&sd)[2], bf16x8 (&pout)[2][2]) __attribute__((always_inline)) {
+    auto softmax = [&](floatx16 (&sd)[kCB], bf16x8 (&pout)[kCB][2]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
+        for (int cb = 0; cb < kCB; ++cb) {
             float tmax = sd[cb][0];
 #pragma unroll
             for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, sd[cb][v]);
@@ -449,7 +464,7 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     };
     // O^T += V^T P^T for one sub-tile.  Element j of the P^T operand of k-step t2 is key
     // 16*t2 + 8*(j/4) + 4*half + j%4 of the sub-tile; the two transposing reads fetched those keys.
-    auto pv = [&](bf16x8 (&pin)[2][2]) __attribute__((always_inline)) {
+    auto pv = [&](bf16x8 (&pin)[kCB][2]) __attribute__((always_inline)) {
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
@@ -457,19 +472,19 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                 const bf16x8 a = __builtin_bit_cast(
                     bf16x8, (u32x4){vbuf[t2][db][0].x, vbuf[t2][db][0].y, vbuf[t2][db][1].x, vbuf[t2][db][1].y});
 #pragma unroll
-                for (int cb = 0; cb < 2; ++cb)
+                for (int cb = 0; cb < kCB; ++cb)
                     o[db][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pin[cb][t2], o[db][cb], 0, 0, 0);
             }
     };
 
     // Scheduling request for the phases that pair a P V product with a softmax: one matrix
-    // instruction, then a dozen vector instructions, sixteen times, so that the vector work runs
+    // instruction, then half a dozen vector instructions, once per matrix instruction, so that the vector work runs
     // in the shadow of the matrix pipeline instead of after it.
     auto interleave_mfma_valu = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
+        for (int i = 0; i < 8 * kCB; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x002, 13, 0);  // VALU
+            __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);   // VALU  // VALU
         }
     };
     // ---- software pipeline over 32-key sub-tiles j = (tile, half), three LDS stages ----
@@ -485,11 +500,17 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     for (;;) {
         if (n_tiles > 0) issue_tile(t_begin, 0);
         if (n_tiles > 1) issue_tile(t_begin + 1, 1);
+        // the query operand is only ever read by MFMA: park it in the accumulator file (here, so
+        // that the query loads and the first tile requests are in flight together)
+#pragma unroll
+        for (int cb = 0; cb < kCB; ++cb)
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+a"(qreg[cb][ks]));
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
         if (wave_active && n_tiles > 0) issue_k(lds_base + k_base, IC<0>{});
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
+        for (int cb = 0; cb < kCB; ++cb)
 #pragma unroll
             for (int t2 = 0; t2 < 2; ++t2) pb[1][cb][t2] = __builtin_bit_cast(bf16x8, (u32x4){0u, 0u, 0u, 0u});
         int st = 0;  // LDS stage of tile `it` (it % kAttnStages, kept without a division)
@@ -548,7 +569,7 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         if (!__syncthreads_or(overflow ? 1 : 0)) break;
         overflow = false;
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
+        for (int cb = 0; cb < kCB; ++cb) {
             m_run[cb] = m_seen[cb];
             l_run[cb] = 0.0f;
 #pragma unroll
@@ -561,11 +582,10 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     if (!wave_active) return;
     // ---- epilogue ----
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
+    for (int cb = 0; cb < kCB; ++cb) {
         const float l_tot = l_run[cb] + __shfl_xor(l_run[cb], 32, 64);
         if (!rvalid[cb]) continue;
-        const int node = node_[cb];
-        const bool real = (mask[((size_t)seq * T + node) * W + (node >> 6)] >> (node & 63)) & 1ull;
+        const bool real = real_[cb];
         const float inv = (real && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
         if (splits == 1) {
             uint16_t *dst = out + (size_t)rowg_[cb] * kHD;
