@@ -237,8 +237,10 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     const int n_cache_tiles = (L + kKT - 1) / kKT;
     const int n_tree_tiles = last_node / kKT + 1;
     const int nt = n_cache_tiles + n_tree_tiles;
-    const int t_begin = (int)((long long)nt * split / splits);
-    const int t_end = (int)((long long)nt * (split + 1) / splits);
+    // key ranges rounded up, so that a surplus tile goes to the early ranges: the last range holds
+    // the tree tiles, which carry the mask work on top
+    const int t_begin = (int)(((long long)nt * split + splits - 1) / splits);
+    const int t_end = (int)(((long long)nt * (split + 1) + splits - 1) / splits);
     const bool wave_active = m0 + wave * 32 * kCB < m_end;
 
     // this lane's two query rows (cb = 0, 1)
