@@ -97,6 +97,8 @@ int ddtree_topk(const float *logits, int batch, int B, int V, int K, int32_t *to
  *                                             iff j is the root, an ancestor of i, or i
  *   n_nodes     [device] int32 [batch]        nodes built, = N unless fewer prefixes exist
  * Rows past n_nodes hold tokens = parent = depth = rank = -1, score 0 and a zero mask row.
+ * A prefix of score -inf (it contains a token of probability zero; the paper assumes
+ * probabilities in (0,1)) never becomes a node: n_nodes counts prefixes of finite score only.
  * Requires 1 <= N <= DDTREE_MAX_N, 1 <= K <= DDTREE_MAX_N, 1 <= B <= DDTREE_MAX_B.
  */
 int ddtree_build(const int32_t *topk_tok, const float *topk_lp, int batch, int B, int K, int N,
@@ -179,6 +181,26 @@ int ddtree_accept_sampled(const float *target_logits, int batch, int T, int V,
 int ddtree_compact(const void *k_tree, const void *v_tree, const int32_t *path,
                    const int32_t *n_accepted, const int32_t *dst_row, int batch, int T, int B,
                    int Hkv, int D, int elem_bytes, void *k_cache, void *v_cache, void *stream);
+
+/*
+ * Construction used by ddtree_build (Algorithm 1 defines the result; both constructions produce
+ * it bit for bit).  DDTREE_BUILD_POPS runs the best-first pops one after the other on one
+ * wavefront; DDTREE_BUILD_LEVELS finds the same N best prefixes (Proposition 2) depth by depth
+ * with the whole workgroup and falls back to the pops when heavy score ties defeat its bounds;
+ * DDTREE_BUILD_AUTO (the default) picks per sequence from the budget and the shape of the
+ * log-probabilities.  Process-wide, takes effect at the next ddtree_build call; meant for
+ * tests and tuning.  Returns DDTREE_ERR_ARG for any other value.
+ */
+#define DDTREE_BUILD_AUTO 0
+#define DDTREE_BUILD_POPS 1
+#define DDTREE_BUILD_LEVELS 2
+int ddtree_set_build_algorithm(int algo);
+/*
+ * Number of sequences, since the library was loaded, for which the level-synchronous
+ * construction gave up and the pops built the tree instead.  count is a host pointer; the call
+ * waits for the device.  Meant for tests.
+ */
+int ddtree_build_giveups(unsigned int *count);
 
 /*
  * Kernel timing hook for benchmarks (no passage of the paper: measurement only).  While a

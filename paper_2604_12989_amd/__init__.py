@@ -7,8 +7,10 @@ fallback path.
 """
 from .binding import (DDTreeError, accept, build, compact, error_string, library_path, load,
                       topk, verify_attn, version, workspace_bytes, Workspace, DTYPE_BF16,
-                      DTYPE_FP32, KERNELS, profile_enable, profile_read, profile_reset)
+                      DTYPE_FP32, KERNELS, profile_enable, profile_read, profile_reset,
+                      set_build_algorithm, build_giveups, BUILD_AUTO, BUILD_POPS, BUILD_LEVELS)
 
 __all__ = ["DDTreeError", "accept", "build", "compact", "error_string", "library_path", "load",
            "topk", "verify_attn", "version", "workspace_bytes", "Workspace", "DTYPE_BF16",
-           "DTYPE_FP32", "KERNELS", "profile_enable", "profile_read", "profile_reset"]
+           "DTYPE_FP32", "KERNELS", "profile_enable", "profile_read", "profile_reset",
+           "set_build_algorithm", "build_giveups", "BUILD_AUTO", "BUILD_POPS", "BUILD_LEVELS"]

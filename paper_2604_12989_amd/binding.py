@@ -30,6 +30,8 @@ _SIGNATURES = {
     "ddtree_accept_sampled": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, ctypes.c_float,
                                    ctypes.c_uint64, _vp, _vp, _vp, _vp, _i, _vp, _sz, _vp]),
     "ddtree_compact": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp]),
+    "ddtree_set_build_algorithm": (_i, [_i]),
+    "ddtree_build_giveups": (_i, [ctypes.POINTER(ctypes.c_uint)]),
     "ddtree_profile_enable": (_i, [ctypes.c_uint, _i]),
     "ddtree_profile_reset": (_i, []),
     "ddtree_profile_read": (_i, [_i, _vp, _i]),
@@ -238,6 +240,21 @@ def compact(k_tree, v_tree, path, n_accepted, dst_row, batch, T, B, Hkv, D, k_ca
                                  dst.ctypes.data_as(ctypes.c_void_p), batch, T, B, Hkv, D,
                                  k_tree.element_size(), _ptr(k_cache), _ptr(v_cache), _stream()),
            "ddtree_compact")
+
+
+BUILD_AUTO, BUILD_POPS, BUILD_LEVELS = 0, 1, 2
+
+
+def set_build_algorithm(algo):
+    """Force one construction in ddtree_build (BUILD_POPS / BUILD_LEVELS) or let it choose (BUILD_AUTO)."""
+    _check(load().ddtree_set_build_algorithm(int(algo)), "ddtree_set_build_algorithm")
+
+
+def build_giveups():
+    """Sequences (since load) that the level-synchronous construction handed back to the pops."""
+    n = ctypes.c_uint(0)
+    _check(load().ddtree_build_giveups(ctypes.byref(n)), "ddtree_build_giveups")
+    return int(n.value)
 
 
 def profile_enable(kernels, capacity):

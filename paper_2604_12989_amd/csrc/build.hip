@@ -22,6 +22,7 @@
 // smaller rank tuple first, a prefix before its extensions.  They are rare and take a slow
 // path that walks parent links in LDS.
 #include "common.hpp"
+#include <atomic>
 
 namespace ddt {
 
@@ -61,13 +62,422 @@ __device__ bool tuple_before(const uint32_t *s_node, int pa, int ra, int pb, int
     return da0 < db0;
 }
 
+// ------------------------------------------------------------------------------------------
+// Level-synchronous construction.
+//
+// The tree is the set of the N best prefixes (Proposition 2) under the total order "score
+// descending, then rank tuple", and the pop order of Algorithm 1 is that order.  Instead of N
+// dependent pops, all 256 threads work depth by depth:
+//   * "alive" is a score bucket cut: the score range [lp[0][N-1], lp[0][0]] is divided into 256
+//     equal buckets (bucket 0 the best; one more bucket takes everything below the range), a
+//     histogram of every prefix found so far is kept, and the cut b* is the first bucket at which
+//     the cumulative count reaches N.  At least N prefixes lie at or above the cut, so a prefix
+//     below it is not in the tree, nor is any descendant (scores only fall along a path).  b* only
+//     moves up.
+//   * level d: every alive depth-(d-1) member finds, by bisection over its (sorted) row, how
+//     many of its children lie at or above the cut; the children are written out, bucketed, the
+//     cut is updated, and the children above the new cut join the members.
+//   * a parent with j better members of the same depth cannot have its child of rank b in the
+//     tree once (j+1)(b+1) > N (every (better parent, lower rank) pair goes first), so its
+//     children are cut at N/(j+1); j is taken from the bucket counts (a lower bound, hence a
+//     looser cut).  Rounding can merge scores and void that counting argument, so the first child
+//     left out of each cut is checked against the final cut of its level; if it would have
+//     survived, the construction gives up.
+//   * the end: the members above the cut are ranked exactly (bucket position plus an all-pairs
+//     count inside the bucket, ties by rank tuple) and the first N become nodes 1..N.
+// Giving up (a cut that cannot be proven, or a capacity that heavy ties exceed) returns -1 and
+// the caller runs the sequential pops instead.
+// ------------------------------------------------------------------------------------------
+__device__ unsigned int g_level_giveups;  // sequences the level construction handed to the pops
+
+constexpr int kLvBuckets = 256;
+constexpr float kLvNeg = -3.0e38f;   // scores at or below count as -inf: never part of a tree
+constexpr int kLvSmall = 8;          // parents with at most this many children write them alone
+constexpr int kLvBigCap = 256;
+
+__device__ __forceinline__ uint32_t pack_member(int parent, int rank, int depth)
+{
+    return (uint32_t)parent | ((uint32_t)rank << 13) | ((uint32_t)depth << 23);
+}
+__device__ __forceinline__ int member_parent(uint32_t x) { return (int)(x & 0x1FFFu); }
+__device__ __forceinline__ int member_rank(uint32_t x) { return (int)((x >> 13) & 0x3FFu); }
+__device__ __forceinline__ int member_depth(uint32_t x) { return (int)(x >> 23); }
+
+struct LevelMem {
+    float *m_score;     // [capm] member scores; member 0 is the root
+    uint32_t *m_info;   // [capm] (parent member, rank, depth)
+    uint16_t *m_jlo;    // [capm] lower bound on the better members of the same depth
+    uint16_t *p_c;      // [capp] per parent of the level: child count | cut flag
+    uint16_t *p_off;    // [capp] per parent: its first candidate (p_off = p_c + capp; together
+                        // they hold the renumbering table when members are squeezed: capm <= 2 capp)
+    float *c_score;     // [capc] candidates of the level; at the end, as u16: node id per member
+    uint32_t *c_info;   // [capc]; at the end, as u16: the members sorted by bucket
+    int capm, capp, capc;  // capm <= 2 * capc
+};
+
+// a goes before b in the total order (score, then rank tuple, a prefix before its extensions)
+__device__ bool member_before(const float *m_score, const uint32_t *m_info, int a, int b)
+{
+    const float sa = m_score[a], sb = m_score[b];
+    if (sa != sb) return sa > sb;
+    uint32_t ia = m_info[a], ib = m_info[b];
+    int da = member_depth(ia), db = member_depth(ib);
+    const int da0 = da, db0 = db;
+    int ra = member_rank(ia), rb = member_rank(ib);
+    int pa = member_parent(ia), pb = member_parent(ib);
+    while (da > db) {
+        ia = m_info[pa];
+        ra = member_rank(ia);
+        pa = member_parent(ia);
+        --da;
+    }
+    while (db > da) {
+        ib = m_info[pb];
+        rb = member_rank(ib);
+        pb = member_parent(ib);
+        --db;
+    }
+    while (pa != pb) {
+        ia = m_info[pa];
+        ra = member_rank(ia);
+        pa = member_parent(ia);
+        ib = m_info[pb];
+        rb = member_rank(ib);
+        pb = member_parent(ib);
+    }
+    if (ra != rb) return ra < rb;
+    return da0 < db0;
+}
+
+// Exclusive prefix sum over the workgroup's kBuildThreads values; *total = their sum.
+__device__ __forceinline__ int build_block_scan(int v, int *s_w, int *total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int incl = wave_scan_inclusive_i32(v);
+    if (lane == 63) s_w[wave] = incl;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kBuildThreads / 64; ++w) {
+        const int x = s_w[w];
+        base += w < wave ? x : 0;
+        tot += x;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + incl - v;
+}
+
+// The same for two values at once; *a and *b are replaced by their exclusive prefixes.
+__device__ __forceinline__ void build_block_scan2(int *a, int *b, int (*s_w2)[kBuildThreads / 64],
+                                                  int *total_a, int *total_b)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int ia = wave_scan_inclusive_i32(*a), ib = wave_scan_inclusive_i32(*b);
+    if (lane == 63) {
+        s_w2[0][wave] = ia;
+        s_w2[1][wave] = ib;
+    }
+    __syncthreads();
+    int base_a = 0, base_b = 0, ta = 0, tb = 0;
+#pragma unroll
+    for (int w = 0; w < kBuildThreads / 64; ++w) {
+        const int xa = s_w2[0][w], xb = s_w2[1][w];
+        base_a += w < wave ? xa : 0;
+        base_b += w < wave ? xb : 0;
+        ta += xa;
+        tb += xb;
+    }
+    __syncthreads();
+    *total_a = ta;
+    *total_b = tb;
+    *a = base_a + ia - *a;
+    *b = base_b + ib - *b;
+}
+
+// Returns the number of nodes written to s_node / s_score (ids 1..n), or -1 after giving up.
+__device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, LevelMem L,
+                           uint32_t *s_node, float *s_score)
+{
+    static_assert(kBuildThreads == kLvBuckets, "one bucket per thread");
+    __shared__ int s_hist[kLvBuckets + 1];    // every prefix found so far, by bucket
+    __shared__ int s_histc[kLvBuckets + 1];   // the candidates of the level; at the end: cursors
+    __shared__ int s_pref[kLvBuckets + 1];    // exclusive prefix of s_histc, later of s_hist
+    __shared__ int s_w[kBuildThreads / 64];
+    __shared__ int s_w2[2][kBuildThreads / 64];
+    __shared__ int s_M, s_fail, s_nbig, s_bstar, s_cum;
+    __shared__ uint16_t s_big[kLvBigCap];
+    constexpr int NT = kBuildThreads;
+    const int tid = threadIdx.x;
+
+    if (tid == 0) {
+        L.m_score[0] = 0.0f;
+        L.m_info[0] = pack_member(0, 0, 0);
+        L.m_jlo[0] = 0;
+        s_M = 1;
+        s_fail = 0;
+    }
+    s_hist[tid] = 0;
+    if (tid == 0) s_hist[kLvBuckets] = 0;
+    const float hi = s_lp[0];
+    const float lo_raw = s_lp[min(K, N) - 1];
+    const float lo = lo_raw > kLvNeg ? lo_raw : hi - 64.0f;
+    // lo itself maps to the middle of the last regular bucket; scores further down go to bucket
+    // kLvBuckets.  Monotone in the score: subtraction, scaling, clamping and truncation all
+    // preserve order.
+    const float inv = ((float)kLvBuckets - 0.5f) / fmaxf(hi - lo, 1e-30f);
+    auto bucket_of = [&](float sc) { return (int)fminf((hi - sc) * inv, (float)kLvBuckets); };
+    __syncthreads();
+
+    int bstar = kLvBuckets;  // alive <=> bucket <= bstar
+    int M = 1, ls = 0, le = 1;   // members so far; the previous level's members are [ls, le)
+    for (int d = 1; d <= B; ++d) {
+        const float *row = s_lp + (d - 1) * Kp;
+        const int n_par = le - ls;
+        if (n_par > L.capp) return -1;
+        if (tid == 0) {
+            s_nbig = 0;
+            s_bstar = bstar;
+        }
+        s_histc[tid] = 0;
+        if (tid == 0) s_histc[kLvBuckets] = 0;
+        // 1. children at or above the cut, per parent (a prefix of the sorted row, found by a
+        //    5-ary search: four independent probes per round), and where they go; small families
+        //    are written on the spot by their parent's thread, large ones are queued
+        auto child_ok = [&](float S, int r) {
+            const float sc = S + row[r];
+            return sc > kLvNeg && bucket_of(sc) <= bstar;
+        };
+        int C = 0;
+        for (int i0 = 0; i0 < n_par; i0 += NT) {
+            const int i = i0 + tid;
+            const int m = ls + i;
+            int c = 0;
+            bool cut = false;
+            float S = 0.0f;
+            if (i < n_par) {
+                S = L.m_score[m];
+                if (m == 0 || bucket_of(S) <= bstar) {
+                    const int cap = min(K, max(1, N / ((int)L.m_jlo[m] + 1)));
+                    int a = 0, b = cap;  // the count lies in [a, b]
+                    while (a < b) {
+                        const int len = b - a;
+                        const int step = len <= 4 ? 1 : (len + 4) / 5;
+                        int q[4];
+                        bool ok[4];
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) q[k] = min(a + (k + 1) * step - 1, b - 1);
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) ok[k] = child_ok(S, q[k]);
+                        // first failing probe (the probes are increasing, the answers monotone)
+                        if (!ok[0]) {
+                            b = q[0];
+                        } else if (!ok[1]) {
+                            a = q[0] + 1;
+                            b = q[1];
+                        } else if (!ok[2]) {
+                            a = q[1] + 1;
+                            b = q[2];
+                        } else if (!ok[3]) {
+                            a = q[2] + 1;
+                            b = q[3];
+                        } else {
+                            a = q[3] + 1;
+                        }
+                    }
+                    c = a;
+                    cut = c == cap && cap < K;
+                }
+            }
+            int total;
+            const int off = C + build_block_scan(c, s_w, &total);
+            if (i < n_par) {
+                L.p_c[i] = (uint16_t)(c | (cut ? 0x8000 : 0));
+                L.p_off[i] = (uint16_t)min(off, 0xFFFF);
+                if (c > kLvSmall) {
+                    const int slot = atomicAdd(&s_nbig, 1);
+                    if (slot < kLvBigCap) s_big[slot] = (uint16_t)i; else s_fail = 1;
+                } else if (c > 0 && off + c <= L.capc) {  // (too many candidates: given up below)
+                    float v[kLvSmall];
+#pragma unroll
+                    for (int r = 0; r < kLvSmall; ++r) v[r] = row[min(r, K - 1)];
+#pragma unroll
+                    for (int r = 0; r < kLvSmall; ++r)
+                        if (r < c) {
+                            L.c_score[off + r] = S + v[r];
+                            L.c_info[off + r] = pack_member(m, r, d);
+                        }
+                }
+            }
+            C += total;
+        }
+        if (C == 0) break;
+        if (C > L.capc) return -1;
+        __syncthreads();
+        if (s_fail) return -1;
+        // 2. the large families, each written by all threads
+        const int nbig = s_nbig;
+        for (int q = 0; q < nbig; ++q) {
+            const int i = s_big[q];
+            const int m = ls + i, off = L.p_off[i], c = L.p_c[i] & 0x7FFF;
+            const float S = L.m_score[m];
+            for (int r = tid; r < c; r += NT) {
+                L.c_score[off + r] = S + row[r];
+                L.c_info[off + r] = pack_member(m, r, d);
+            }
+        }
+        __syncthreads();
+        // 3. bucket the candidates, move the cut
+        for (int t = tid; t < C; t += NT) atomicAdd(&s_histc[bucket_of(L.c_score[t])], 1);
+        __syncthreads();
+        const int hc = s_histc[tid];
+        const int ha = s_hist[tid] + hc;
+        int total_a, total_c;
+        int ex_a = ha, ex_c = hc;
+        build_block_scan2(&ex_a, &ex_c, s_w2, &total_a, &total_c);
+        s_pref[tid] = ex_c;
+        s_hist[tid] = ha;
+        if (tid == 0) {
+            s_pref[kLvBuckets] = total_c;
+            s_hist[kLvBuckets] += s_histc[kLvBuckets];
+        }
+        if (ex_a < N && ex_a + ha >= N) s_bstar = tid;  // the bucket that holds the N-th best
+        __syncthreads();
+        bstar = min(bstar, s_bstar);
+        // 4. every rank cut must have left out only children below the new cut
+        for (int i = tid; i < n_par; i += NT) {
+            const int pc = L.p_c[i];
+            if (pc & 0x8000) {
+                const float sc = L.m_score[ls + i] + row[pc & 0x7FFF];
+                if (sc > kLvNeg && bucket_of(sc) <= bstar) s_fail = 1;
+            }
+        }
+        __syncthreads();
+        if (s_fail) return -1;
+        // 5. room for the survivors: when the member arrays would overflow, the members that
+        //    have fallen below the cut are squeezed out (the order is kept, so the previous
+        //    level stays a contiguous range; parent references are renumbered)
+        const int n_surv = s_pref[bstar] + s_histc[bstar];
+        if (M + n_surv > L.capm) {
+            uint16_t *remap = L.p_c;  // p_c and p_off (contiguous, 2 * capp >= capm) are free now
+            int base = 1;
+            if (tid == 0) remap[0] = 0;
+            for (int m0 = 1; m0 < M; m0 += NT) {
+                const int m = m0 + tid;
+                float sc = 0.0f;
+                uint32_t info = 0;
+                uint16_t jl = 0;
+                bool keep = false;
+                if (m < M) {
+                    sc = L.m_score[m];
+                    keep = bucket_of(sc) <= bstar;
+                    info = L.m_info[m];
+                    jl = L.m_jlo[m];
+                }
+                int tot;
+                const int dst = base + build_block_scan(keep ? 1 : 0, s_w, &tot);
+                if (keep) {  // dst <= m, and every entry up to this chunk's end has been read
+                    remap[m] = (uint16_t)dst;
+                    L.m_score[dst] = sc;
+                    L.m_info[dst] = info;
+                    L.m_jlo[dst] = jl;
+                }
+                base += tot;
+            }
+            __syncthreads();
+            const int M2 = base;
+            for (int m = 1 + tid; m < M2; m += NT) {
+                const uint32_t info = L.m_info[m];
+                L.m_info[m] = pack_member(remap[member_parent(info)], member_rank(info), member_depth(info));
+            }
+            for (int t = tid; t < C; t += NT) {
+                if (bucket_of(L.c_score[t]) <= bstar) {  // (a survivor's parent is alive)
+                    const uint32_t info = L.c_info[t];
+                    L.c_info[t] = pack_member(remap[member_parent(info)], member_rank(info), member_depth(info));
+                }
+            }
+            M = M2;
+            if (tid == 0) s_M = M2;
+            __syncthreads();
+            if (M + n_surv > L.capm) return -1;
+        }
+        // 6. candidates at or above the cut become members
+        for (int t = tid; t < C; t += NT) {
+            const float sc = L.c_score[t];
+            const int bk = bucket_of(sc);
+            if (bk <= bstar) {
+                const int slot = atomicAdd(&s_M, 1);
+                if (slot < L.capm) {
+                    L.m_score[slot] = sc;
+                    L.m_info[slot] = L.c_info[t];
+                    L.m_jlo[slot] = (uint16_t)min(s_pref[bk], 0xFFFF);
+                } else {
+                    s_fail = 1;
+                }
+            }
+        }
+        __syncthreads();
+        if (s_fail) return -1;
+        ls = M;
+        M = s_M;
+        le = M;
+        if (ls == le) break;
+        __syncthreads();  // s_M, s_nbig and s_histc are rewritten by the next level
+    }
+    __syncthreads();
+
+    // ---- exact order of the members at or above the cut ----
+    const int hb = tid <= bstar ? s_hist[tid] : 0;
+    int total_alive;
+    const int start = build_block_scan(hb, s_w, &total_alive);
+    s_pref[tid] = start;
+    s_histc[tid] = 0;
+    if (tid == 0) {
+        s_pref[kLvBuckets] = total_alive;
+        s_histc[kLvBuckets] = 0;
+    }
+    if (bstar == kLvBuckets) total_alive += s_hist[kLvBuckets];
+    uint16_t *sorted = reinterpret_cast<uint16_t *>(L.c_info);
+    uint16_t *node_id = reinterpret_cast<uint16_t *>(L.c_score);
+    __syncthreads();
+    for (int m = 1 + tid; m < M; m += NT) {
+        const int bk = bucket_of(L.m_score[m]);
+        if (bk <= bstar) sorted[s_pref[bk] + atomicAdd(&s_histc[bk], 1)] = (uint16_t)m;
+    }
+    __syncthreads();
+    for (int e = tid; e < total_alive; e += NT) {
+        const int m = sorted[e];
+        const int bk = bucket_of(L.m_score[m]);
+        const int bs = s_pref[bk], nb = s_hist[bk];
+        int g = 0;
+        for (int j = 0; j < nb; ++j) {
+            const int o = sorted[bs + j];
+            g += (o != m && member_before(L.m_score, L.m_info, o, m)) ? 1 : 0;
+        }
+        const int pos = bs + g;
+        node_id[m] = (uint16_t)(pos < N ? pos + 1 : 0);
+    }
+    __syncthreads();
+    for (int e = tid; e < total_alive; e += NT) {
+        const int m = sorted[e];
+        const int id = node_id[m];
+        if (id == 0) continue;
+        const uint32_t info = L.m_info[m];
+        const int pm = member_parent(info);
+        s_node[id] = pack_node(pm == 0 ? 0 : node_id[pm], member_rank(info), member_depth(info));
+        s_score[id] = L.m_score[m];
+    }
+    __syncthreads();
+    return min(N, total_alive);
+}
+
 template <int NSLOT>
 __global__ __launch_bounds__(kBuildThreads) void build_kernel(
     const int32_t *__restrict__ topk_tok, const float *__restrict__ topk_lp, int B, int K, int N,
     const int32_t *__restrict__ root_token, int32_t *__restrict__ tokens,
     int32_t *__restrict__ parent, int32_t *__restrict__ depth, int32_t *__restrict__ rank,
     float *__restrict__ node_score, uint64_t *__restrict__ ancestor_mask,
-    int32_t *__restrict__ n_nodes)
+    int32_t *__restrict__ n_nodes, int algo, int capm, int capp, int capc)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int Kp = K + 3;
@@ -76,6 +486,18 @@ __global__ __launch_bounds__(kBuildThreads) void build_kernel(
     uint32_t *s_node = reinterpret_cast<uint32_t *>(s_lp + B * Kp);     // [T]
     float *s_score = reinterpret_cast<float *>(s_node + T);             // [T]
     uint16_t *s_chain = reinterpret_cast<uint16_t *>(s_score + T);      // [B+1][kBuildThreads]
+    // the level-synchronous construction's arrays share the space of s_chain (used afterwards)
+    LevelMem lv;
+    lv.capm = capm;
+    lv.capp = capp;
+    lv.capc = capc;
+    lv.m_score = reinterpret_cast<float *>(s_score + T);
+    lv.m_info = reinterpret_cast<uint32_t *>(lv.m_score + capm);
+    lv.c_score = reinterpret_cast<float *>(lv.m_info + capm);
+    lv.c_info = reinterpret_cast<uint32_t *>(lv.c_score + capc);
+    lv.m_jlo = reinterpret_cast<uint16_t *>(lv.c_info + capc);
+    lv.p_c = lv.m_jlo + capm;
+    lv.p_off = lv.p_c + capp;
     __shared__ int s_built;
 
     const int tid = threadIdx.x;
@@ -100,7 +522,32 @@ __global__ __launch_bounds__(kBuildThreads) void build_kernel(
     }
     __syncthreads();
 
-    if (tid < kWave) {
+    // Which construction: the sequential pops win on small budgets and on stars (nearly all nodes
+    // at depth 1: their sibling runs pop in batches); the level-synchronous construction wins on
+    // large budgets and wherever pops alternate between parents, each a step of its own.  A star
+    // is recognised by the top-1 chain falling below the worst useful rank of row 0 within two
+    // steps and by the best depth-1 node having fewer than four children above that rank.
+    // Both constructions give the same tree; algo 1 / 2 force one of them.
+    bool use_levels = capm > 0 && algo != DDTREE_BUILD_POPS;
+    if (use_levels && algo == DDTREE_BUILD_AUTO) {
+        const float worst = s_lp[min(K, N) - 1];
+        float chain = 0.0f;
+        int deep = 0;
+        for (int d = 0; d < B; ++d) {
+            chain += s_lp[d * Kp];
+            deep += chain >= worst ? 1 : 0;
+        }
+        const bool bushy = B >= 2 && s_lp[0] + s_lp[Kp + min(3, K - 1)] >= worst;
+        use_levels = N > 256 || (N >= 96 && (deep >= 3 || bushy));
+    }
+    int level_n = -1;
+    if (use_levels) {
+        level_n = level_build(s_lp, Kp, B, K, N, lv, s_node, s_score);
+        if (level_n < 0 && tid == 0) atomicAdd(&g_level_giveups, 1u);
+    }
+    if (level_n >= 0) {
+        if (tid == 0) s_built = level_n;
+    } else if (tid < kWave) {
         const int lane = tid;
         // lane d holds the first two log-probabilities of row d (children of a node at depth
         // d), -inf past the last row: what a fresh entry for a node at depth d needs
@@ -271,7 +718,9 @@ __global__ __launch_bounds__(kBuildThreads) void build_kernel(
             continue;
         }
         const uint32_t nd = s_node[i];
-        const int d = i == 0 ? 0 : node_depth(nd);
+        // (depth and rank are clamped to the table: whatever the records hold, every read below
+        // stays inside topk_tok and the chain scratch)
+        const int d = i == 0 ? 0 : min(max(node_depth(nd), 1), B);
         if (i == 0) {
             tokens[o] = root_token[seq];
             parent[o] = -1;
@@ -279,7 +728,7 @@ __global__ __launch_bounds__(kBuildThreads) void build_kernel(
             if (rank) rank[o] = -1;
             if (node_score) node_score[o] = 0.0f;
         } else {
-            tokens[o] = tk[(d - 1) * K + node_rank(nd)];
+            tokens[o] = tk[(d - 1) * K + min(node_rank(nd), K - 1)];
             parent[o] = node_parent(nd);
             depth[o] = d;
             if (rank) rank[o] = node_rank(nd);
@@ -308,12 +757,53 @@ static size_t build_lds_bytes(int B, int K, int N)
     return (size_t)B * (K + 3) * 4 + (size_t)(N + 1) * 8 + (size_t)(B + 1) * kBuildThreads * 2;
 }
 
+// Dynamic LDS of the kernel and the capacities of the level-synchronous construction (members,
+// candidates per level), which shares the space of the ancestor-chain scratch.  capm = 0: no room,
+// sequential pops only.
+struct BuildLds {
+    size_t bytes;
+    int capm, capp, capc;
+};
+static BuildLds build_lds_plan(int B, int K, int N, bool level)
+{
+    const size_t base = (size_t)B * (K + 3) * 4 + (size_t)(N + 1) * 8;
+    const size_t chain = (size_t)(B + 1) * kBuildThreads * 2;
+    BuildLds r{base + chain, 0, 0, 0};
+    if (!level) return r;
+    const size_t limit = 150 * 1024;
+    if (base >= limit) return r;
+    const size_t avail = limit - base;
+    const int capp = 2 * N + 256;       // members of one depth that can be parents
+    const int min_m = 2 * N + 64;
+    int capc = 4 * N + 512;             // candidates of one level
+    // large budgets leave little room beside the log-probability table: favour the members
+    if (4 * (size_t)capp + 8 * (size_t)capc + 10 * (size_t)(4 * N + 256) > avail) capc = 3 * N + 256;
+    if (4 * (size_t)capp + 8 * (size_t)capc + 10 * (size_t)min_m > avail) capc = 2 * N + 256;
+    const size_t fixed = 4 * (size_t)capp + 8 * (size_t)capc;
+    if (fixed + 10 * (size_t)min_m > avail) return r;
+    size_t capm = (avail - fixed) / 10 / 2 * 2;
+    if (capm > (size_t)8 * N + 256) capm = (size_t)8 * N + 256;
+    if (capm > 8192) capm = 8192;       // member ids are 13 bits wide
+    if (capm > 2 * (size_t)capc) capm = 2 * (size_t)capc;
+    if (capm > 2 * (size_t)capp) capm = 2 * (size_t)capp;
+    r.capm = (int)capm;
+    r.capp = capp;
+    r.capc = capc;
+    const size_t lv = 10 * capm + fixed;
+    r.bytes = base + (lv > chain ? lv : chain);
+    return r;
+}
+
+static std::atomic<int> g_build_algo{DDTREE_BUILD_AUTO};
+
 template <int NSLOT>
 static int launch_build(const int32_t *topk_tok, const float *topk_lp, int batch, int B, int K, int N,
                         const int32_t *root_token, int32_t *tokens, int32_t *parent, int32_t *depth,
                         int32_t *rank, float *node_score, uint64_t *ancestor_mask, int32_t *n_nodes,
                         hipStream_t st)
 {
+    const int algo = g_build_algo.load();
+    const BuildLds lds = build_lds_plan(B, K, N, algo != DDTREE_BUILD_POPS);
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(build_kernel<NSLOT>),
@@ -321,13 +811,29 @@ static int launch_build(const int32_t *topk_tok, const float *topk_lp, int batch
             return DDTREE_ERR_HIP;
         attr_set = true;
     }
-    DDT_LAUNCH(DDTREE_KERNEL_BUILD, st, build_kernel<NSLOT>, dim3(batch), dim3(kBuildThreads), build_lds_bytes(B, K, N),
+    DDT_LAUNCH(DDTREE_KERNEL_BUILD, st, build_kernel<NSLOT>, dim3(batch), dim3(kBuildThreads), lds.bytes,
                        st, topk_tok, topk_lp, B, K, N, root_token, tokens, parent, depth, rank,
-                       node_score, ancestor_mask, n_nodes);
+                       node_score, ancestor_mask, n_nodes, algo, lds.capm, lds.capp, lds.capc);
     return launch_status();
 }
 
 }  // namespace ddt
+
+extern "C" int ddtree_set_build_algorithm(int algo)
+{
+    if (algo != DDTREE_BUILD_AUTO && algo != DDTREE_BUILD_POPS && algo != DDTREE_BUILD_LEVELS)
+        return DDTREE_ERR_ARG;
+    ddt::g_build_algo.store(algo);
+    return DDTREE_OK;
+}
+
+extern "C" int ddtree_build_giveups(unsigned int *count)
+{
+    if (!count) return DDTREE_ERR_ARG;
+    if (hipMemcpyFromSymbol(count, HIP_SYMBOL(ddt::g_level_giveups), sizeof(unsigned int)) != hipSuccess)
+        return DDTREE_ERR_HIP;
+    return DDTREE_OK;
+}
 
 extern "C" int ddtree_build(const int32_t *topk_tok, const float *topk_lp, int batch, int B, int K,
                             int N, const int32_t *root_token, int32_t *tokens, int32_t *parent,

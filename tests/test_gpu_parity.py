@@ -101,6 +101,15 @@ def test_topk_batched():
 
 
 # ------------------------------------------------------------------------------- build
+@pytest.fixture(params=["auto", "pops", "levels"])
+def build_algo(request):
+    """Every build test runs under each construction: the choice may change speed, never the tree."""
+    import paper_2604_12989_amd as dd
+    dd.set_build_algorithm({"auto": dd.BUILD_AUTO, "pops": dd.BUILD_POPS, "levels": dd.BUILD_LEVELS}[request.param])
+    yield request.param
+    dd.set_build_algorithm(dd.BUILD_AUTO)
+
+
 def _peaked_logits(seed, B, V, spike):
     x = di.draft_logits(seed, B, V)
     rng = np.random.default_rng(seed)
@@ -122,7 +131,7 @@ def _check_build(tok, lp, N, root=5):
 
 
 @pytest.mark.parametrize("N", [1, 2, 16, 63, 64, 65, 128, 256, 512, 1024])
-def test_build_matches_oracle_on_workload_logits(N):
+def test_build_matches_oracle_on_workload_logits(N, build_algo):
     x = di.draft_logits(di.config_seed(2), 16, 20000)
     K = min(N, 20000)
     tok, lp = oracle.topk(x, K)
@@ -130,14 +139,40 @@ def test_build_matches_oracle_on_workload_logits(N):
 
 
 @pytest.mark.parametrize("spike,N", [(6.0, 64), (9.0, 256), (12.0, 256), (14.0, 512), (20.0, 100)])
-def test_build_deep_trees(spike, N):
+def test_build_deep_trees(spike, N, build_algo):
+    import paper_2604_12989_amd as dd
     x = _peaked_logits(21, 16, 8192, spike)
     tok, lp = oracle.topk(x, min(N, 8192))
+    before = dd.build_giveups()
     o = _check_build(tok, lp, N)
+    # tie-free logits: the level construction must carry these through on its own
+    assert dd.build_giveups() == before
     print(f"spike {spike}: max depth {o['depth'].max()}")
 
 
-def test_build_exact_ties_and_dry_heap():
+@pytest.mark.parametrize("spike,N", [(16.0, 1024), (24.0, 1024), (18.0, 768)])
+def test_build_large_budget_on_peaked_rows(spike, N, build_algo):
+    # deep trees at large budgets: the level construction has to squeeze dead members out
+    import paper_2604_12989_amd as dd
+    x = _peaked_logits(23, 16, 8192, spike)
+    tok, lp = oracle.topk(x, N)
+    before = dd.build_giveups()
+    o = _check_build(tok, lp, N)
+    assert o["depth"].max() == 16
+    assert dd.build_giveups() == before
+
+
+def test_build_rows_with_minus_infinity(build_algo):
+    # masked vocabulary: rows end in -inf log-probabilities, which never become nodes
+    rng = np.random.default_rng(9)
+    for K_live, N in ((5, 40), (12, 64), (3, 30)):
+        x = rng.normal(size=(6, 64)).astype(np.float32) * 2.0
+        x[:, K_live:] = -np.inf
+        tok, lp = oracle.topk(x, 32)
+        _check_build(tok, lp, N)
+
+
+def test_build_exact_ties_and_dry_heap(build_algo):
     rng = np.random.default_rng(5)
     for trial in range(20):
         B, K = int(rng.integers(1, 6)), int(rng.integers(1, 7))
@@ -148,7 +183,7 @@ def test_build_exact_ties_and_dry_heap():
             _check_build(tok, lp, N)
 
 
-def test_build_batched():
+def test_build_batched(build_algo):
     toks, lps = [], []
     for b in range(4):
         x = _peaked_logits(30 + b, 8, 4096, 5.0 + 3 * b)
