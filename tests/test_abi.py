@@ -95,6 +95,12 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     # profile hook: bad arguments
     assert lib.ddtree_profile_enable(1 << 20, 4) == ERR_ARG
     assert lib.ddtree_profile_read(99, p, 1) == ERR_ARG
+    # the construction selector takes its three values only, and is host-side state
+    assert lib.ddtree_set_build_algorithm(3) == ERR_ARG
+    assert lib.ddtree_set_build_algorithm(-1) == ERR_ARG
+    for algo in (2, 1, 0):
+        assert lib.ddtree_set_build_algorithm(algo) == 0
+    assert lib.ddtree_build_giveups(None) == ERR_ARG
 
 
 def test_product_path_does_not_import_the_oracle():
