@@ -36,6 +36,8 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 // Blocks of 32 query rows per wave.  1: eight waves of 32 rows, two waves per SIMD with 256
 // registers each, so that one wave's waits (LDS, matrix results, barrier) are filled by the other;
+// everything then fits the 256 architectural registers and no accumulation registers are used
+// (asking for any would make the compiler split the budget 128 / 128 and spill);
 // 2: four waves of 64 rows with 512 registers each (half the LDS reads per matrix instruction, but
 // nothing to fill a stall with; measured slower).
 constexpr int kCB = 1;
@@ -502,12 +504,6 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     for (;;) {
         if (n_tiles > 0) issue_tile(t_begin, 0);
         if (n_tiles > 1) issue_tile(t_begin + 1, 1);
-        // the query operand is only ever read by MFMA: park it in the accumulator file (here, so
-        // that the query loads and the first tile requests are in flight together)
-#pragma unroll
-        for (int cb = 0; cb < kCB; ++cb)
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+a"(qreg[cb][ks]));
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
         if (wave_active && n_tiles > 0) issue_k(lds_base + k_base, IC<0>{});
