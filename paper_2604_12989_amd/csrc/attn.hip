@@ -90,13 +90,43 @@ AttnPlan attn_plan(int batch, int T, int Hq, int Hkv, int D, long long sum_L, in
         }
     }
     p.splits = best_s;
+    p.part_splits = best_s;
+    // Uneven form: when the blocks are a few more than whole tiles of 8 (T = 257 with four heads per
+    // KV head: 33 blocks), even tiling leaves a fifth of the wave slots idle at no gain in time (a
+    // tile is as slow as its busiest SIMD).  Whole tiles plus one small tail tile, the tail cut
+    // into fewer key ranges because it runs about twice as fast per key tile, fills the 256 compute
+    // units with shorter key ranges.  Taken when everything fits one round and the model says so.
+    const int full = nblk / 8, rem = nblk % 8;
+    if (full >= 1 && rem >= 1 && rem <= 4) {
+        const double c_tail = 0.5;
+        const long long base_m = (long long)batch * Hkv * full, base_t = (long long)batch * Hkv;
+        for (int Sm = 1; Sm <= 32; ++Sm) {
+            if (Sm > 1 && (long long)Sm * 4 > tiles) break;
+            for (int St = 1; St <= 32; ++St) {
+                if (St > 1 && (long long)St * 4 > tiles) break;
+                if (base_m * Sm + base_t * St > 256) break;
+                const double t_m = (double)((tiles + Sm - 1) / Sm), t_t = c_tail * (double)((tiles + St - 1) / St);
+                const int smax = Sm > St ? Sm : St;
+                const double cost = (t_m > t_t ? t_m : t_t) / (double)(tiles > 0 ? tiles : 1) * (1.0 + 0.02 * (smax - 1));
+                if (cost < best_cost - 1e-12) {
+                    best_cost = cost;
+                    p.n_tiles = full + 1;
+                    p.blk_base = 8;
+                    p.blk_extra = rem;  // (read as: blocks of the tail tile)
+                    p.splits = Sm;
+                    p.tail_splits = St;
+                    p.part_splits = smax;
+                }
+            }
+        }
+    }
     size_t off = 0;
-    if (p.splits > 1) {
+    if (p.part_splits > 1 || p.tail_splits > 0) {
         const size_t rows = (size_t)batch * T * Hq;  // indexed by global row
         p.part_off = off;
-        off = align_up(off + (size_t)p.splits * rows * D * 2, 256);  // fp16 partials
+        off = align_up(off + (size_t)p.part_splits * rows * D * 2, 256);  // fp16 partials
         p.lse_off = off;
-        off = align_up(off + (size_t)p.splits * rows * 4, 256);
+        off = align_up(off + (size_t)p.part_splits * rows * 4, 256);
     }
     p.bytes = off;
     return p;
@@ -198,7 +228,8 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                       const uint16_t *__restrict__ v_cache, const uint16_t *__restrict__ k_tree,
                       const uint16_t *__restrict__ v_tree, const uint64_t *__restrict__ mask,
                       AttnArgs args, int batch_n, int T, int Hq, int Hkv, float scale_log2e, int n_tiles_m,
-                      int blk_base, int blk_extra, int splits, uint16_t *__restrict__ out,
+                      int blk_base, int blk_extra, int main_splits, int tail_splits, int part_splits,
+                      uint16_t *__restrict__ out,
                       uint16_t *__restrict__ part, float *__restrict__ lse)
 {
     // LDS: kAttnStages stages of {K tile, V tile}, filled by direct global->LDS loads.  One wave
@@ -215,14 +246,20 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     // 8 runs of per_xcd consecutive work items, run x being what XCD x executes, and consecutive
     // work items are the row tiles of one (group, key range): the row tiles that read the same K
     // and V rows share an L2, and those rows leave HBM once.
-    const int total = Hkv * batch_n * n_tiles_m * splits;
+    // The work items of a group are its main tiles, row tile fastest within a key range, then (in
+    // the uneven form) the key ranges of its tail tile.
+    const int main_tiles = tail_splits > 0 ? n_tiles_m - 1 : n_tiles_m;
+    const int per_grp = main_tiles * main_splits + tail_splits;
+    const int total = Hkv * batch_n * per_grp;
     const int per_xcd = (total + 7) >> 3;
     const int wid = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
     if (wid >= total) return;
-    const int mt = wid % n_tiles_m;
-    const int unit = wid / n_tiles_m;                     // (group, key range)
-    const int split = unit % splits;
-    const int grp = unit / splits;                        // (sequence, kv head) pair
+    const int grp = wid / per_grp;                        // (sequence, kv head) pair
+    const int wg = wid - grp * per_grp;
+    const bool tail = wg >= main_tiles * main_splits;
+    const int mt = tail ? main_tiles : wg % main_tiles;
+    const int split = tail ? wg - main_tiles * main_splits : wg / main_tiles;
+    const int splits = tail ? tail_splits : main_splits;  // key ranges of this tile
     const int hk = grp % Hkv;
     const int seq = grp / Hkv;
     const int G = Hq / Hkv;
@@ -231,8 +268,8 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     const int L0 = args.kv_offset[seq];
     const int L = args.kv_offset[seq + 1] - L0;
     // this tile's blocks of 32 rows: wave w owns blocks kCB*w .. kCB*w + kCB - 1 of the tile
-    const int first_blk = mt * blk_base + min(mt, blk_extra);
-    const int n_blk = blk_base + (mt < blk_extra ? 1 : 0);
+    const int first_blk = tail_splits > 0 ? mt * 8 : mt * blk_base + min(mt, blk_extra);
+    const int n_blk = tail_splits > 0 ? (tail ? blk_extra : 8) : blk_base + (mt < blk_extra ? 1 : 0);
     const int m0 = first_blk * 32;
     const int m_end = min(M, (first_blk + n_blk) * 32);
     const int last_node = min(T - 1, (m_end - 1) / G);
@@ -585,7 +622,7 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         if (!rvalid[cb]) continue;
         const bool real = real_[cb];
         const float inv = (real && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
-        if (splits == 1) {
+        if (part_splits == 0) {
             uint16_t *dst = out + (size_t)rowg_[cb] * kHD;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
@@ -612,9 +649,13 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                     val.y = f2h_pair(o[db][cb][4 * g4 + 2] * inv, o[db][cb][4 * g4 + 3] * inv);
                     *reinterpret_cast<uint2 *>(dst + dim) = val;
                 }
-            if (half == 0)
+            if (half == 0) {
                 lse[(size_t)split * n_rows + ridx] =
                     inv > 0.0f ? m_run[cb] + __builtin_amdgcn_logf(l_tot) : -INFINITY;
+                // key ranges this tile does not have (the other kind of tile has more): empty
+                if (split == 0)
+                    for (int sx = splits; sx < part_splits; ++sx) lse[(size_t)sx * n_rows + ridx] = -INFINITY;
+            }
         }
     }
 }
@@ -655,9 +696,9 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const uint16_t *__restr
             float l[kMergeBatch];
 #pragma unroll
             for (int j = 0; j < kMergeBatch; ++j) {
-                const bool on = s0 + j < splits;
-                l[j] = on ? lse[(size_t)(s0 + j) * n_rows] : -INFINITY;
-                v[j] = on ? *reinterpret_cast<const f16x8 *>(part + (size_t)(s0 + j) * pstride) : f16x8(0);
+                l[j] = s0 + j < splits ? lse[(size_t)(s0 + j) * n_rows] : -INFINITY;
+                // (an empty key range has no partial: nothing, not even its bits, is read)
+                v[j] = l[j] > -INFINITY ? *reinterpret_cast<const f16x8 *>(part + (size_t)(s0 + j) * pstride) : f16x8(0);
             }
 #pragma unroll
             for (int j = 0; j < kMergeBatch; ++j) {
@@ -815,18 +856,20 @@ extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void
                 return DDTREE_ERR_HIP;
             attr_set = true;
         }
-        const long long gx = ((long long)batch * Hkv * p.n_tiles * p.splits + 7) / 8 * 8;
+        const int main_tiles = p.tail_splits > 0 ? p.n_tiles - 1 : p.n_tiles;
+        const long long gx = ((long long)batch * Hkv * (main_tiles * p.splits + p.tail_splits) + 7) / 8 * 8;
+        const int part_splits = (p.part_splits > 1 || p.tail_splits > 0) ? p.part_splits : 0;
         DDT_LAUNCH(DDTREE_KERNEL_ATTN, st, attn_mfma_kernel, dim3((unsigned)gx), dim3(kAttnThreads),
                    kAttnLdsBytes, st, static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(k_cache),
                    static_cast<const uint16_t *>(v_cache), static_cast<const uint16_t *>(k_tree),
                    static_cast<const uint16_t *>(v_tree), ancestor_mask, args, batch, T, Hq, Hkv,
-                   softmax_scale * kLog2e, p.n_tiles, p.blk_base, p.blk_extra, p.splits,
+                   softmax_scale * kLog2e, p.n_tiles, p.blk_base, p.blk_extra, p.splits, p.tail_splits, part_splits,
                    static_cast<uint16_t *>(out), part, lse);
-        if (p.splits > 1) {
+        if (part_splits > 0) {
             const size_t n_rows = (size_t)batch * T * Hq;
             DDT_LAUNCH(DDTREE_KERNEL_ATTN_MERGE, st, attn_merge_kernel,
                        dim3((unsigned)((n_rows * 16 + 255) / 256)), dim3(256), 0, st, part, lse, n_rows,
-                       p.splits, static_cast<uint16_t *>(out));
+                       part_splits, static_cast<uint16_t *>(out));
         }
         return launch_status();
     }

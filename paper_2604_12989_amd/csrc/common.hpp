@@ -44,6 +44,11 @@ struct AttnPlan {
     // blocks.  The key range of every tile is cut into `splits` parts; partial results exist
     // only when splits > 1.
     int n_tiles, blk_base, blk_extra, splits;
+    // Uneven form (tail_splits > 0): the first n_tiles - 1 tiles hold 8 blocks and `splits` key
+    // ranges each; the last tile holds the few blocks left over (at most one wave per SIMD, so
+    // it runs about twice as fast per key tile) and `tail_splits` key ranges.  Partials are laid
+    // out for part_splits = max(splits, tail_splits) ranges.
+    int tail_splits, part_splits;
     size_t part_off, lse_off, bytes;
 };
 AttnPlan attn_plan(int batch, int T, int Hq, int Hkv, int D, long long sum_L, int dtype);
