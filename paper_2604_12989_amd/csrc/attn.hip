@@ -278,8 +278,9 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     const int nt = n_cache_tiles + n_tree_tiles;
     // key ranges rounded up, so that a surplus tile goes to the early ranges: the last range holds
     // the tree tiles, which carry the mask work on top
-    const int t_begin = (int)(((long long)nt * split + splits - 1) / splits);
-    const int t_end = (int)(((long long)nt * (split + 1) + splits - 1) / splits);
+    // (nt < 2^25 key tiles and at most 32 key ranges: 32-bit arithmetic is exact)
+    const int t_begin = (int)(((unsigned)nt * (unsigned)split + (unsigned)splits - 1u) / (unsigned)splits);
+    const int t_end = (int)(((unsigned)nt * (unsigned)(split + 1) + (unsigned)splits - 1u) / (unsigned)splits);
     const bool wave_active = m0 + wave * 32 * kCB < m_end;
 
     // this lane's two query rows (cb = 0, 1)
