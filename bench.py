@@ -60,7 +60,8 @@ def main():
     args = parse()
     if args.gpus != 1:
         log(f"bench.py: this build runs on ONE GPU (asked for --gpus {args.gpus}); the path has no "
-            "multi-GPU leg, see DESIGN.md for how it would shard")
+            "multi-GPU leg (it would shard over the vocabulary for top-K and argmax and over KV heads "
+            "for attention, with KB-sized exchanges)")
         sys.exit(2)
     import torch
 
