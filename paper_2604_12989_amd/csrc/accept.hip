@@ -115,6 +115,11 @@ __global__ __launch_bounds__(kArgmaxThreads) void accept_argmax_kernel(
     // unit, what it takes to cover the HBM latency at full bandwidth; the logits are read once,
     // so the loads are marked non-temporal
     constexpr int kInFlight = 8;
+    // Sampling: most elements are settled without their logarithms.  The noise is bounded from the
+    // hash alone, g = -ln(-ln u) <= -ln(1 - u) = ln(2^25 / w) with the odd integer
+    // w = 2^25 - 2k - 1, hence g <= ln2 * (clz(w) - 6); an element whose bound stays below a key
+    // this wave has already found (wb) cannot be the row's maximum, nor tie with it.
+    float wb = -INFINITY;
     for (int j0 = tid; j0 < nvec; j0 += kInFlight * kArgmaxThreads) {
         float4 x[kInFlight];
 #pragma unroll
@@ -130,10 +135,35 @@ __global__ __launch_bounds__(kArgmaxThreads) void accept_argmax_kernel(
                 x[u] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
             }
         }
+        if (SAMPLE) wb = wave_max_f32(bv);
 #pragma unroll
         for (int u = 0; u < kInFlight; ++u) {
             const int ia = start + head + 4 * (j0 + u * kArgmaxThreads);
-            if (SAMPLE && j0 + u * kArgmaxThreads >= nvec) continue;  // padding lanes draw no noise
+            if (SAMPLE) {
+                if (j0 + u * kArgmaxThreads >= nvec) continue;  // padding lanes draw no noise
+                const float xe[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
+                bool need[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t h = sample_mix(sample_mix((uint32_t)(ia + e) ^ sa.seed_lo) + row_term);
+                    const uint32_t w = 0x1FFFFFFu - ((h >> 8) << 1);
+                    const float g_max = 0.6931472f * (float)(__builtin_clz(w) - 6);
+                    // (the margin covers the rounding of the exact key, about 2e-6)
+                    need[e] = fmaf(xe[e], sa.inv_tau, g_max) + 2e-3f >= wb;
+                }
+                if (__ballot(need[0] || need[1] || need[2] || need[3]) != 0ull) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (need[e]) {
+                            const float ke = select_key<true>(xe[e], (uint32_t)(ia + e), row_term, sa);
+                            if (ke > bv) {
+                                bv = ke;
+                                bi = ia + e;
+                            }
+                        }
+                }
+                continue;
+            }
             const float k0 = select_key<SAMPLE>(x[u].x, (uint32_t)ia, row_term, sa);
             const float k1 = select_key<SAMPLE>(x[u].y, (uint32_t)ia + 1u, row_term, sa);
             const float k2 = select_key<SAMPLE>(x[u].z, (uint32_t)ia + 2u, row_term, sa);
