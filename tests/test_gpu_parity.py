@@ -497,7 +497,7 @@ def _check_sampled(tl, tokens, parent, depth, n_nodes, B, tau, seed, batch_rows=
     return got, close
 
 
-@pytest.mark.parametrize("tau", [0.3, 1.0, 2.0])
+@pytest.mark.parametrize("tau", [0.05, 0.3, 1.0, 2.0, 25.0])
 def test_accept_sampled_matches_oracle(tau):
     rng = np.random.default_rng(31)
     T, V, B = 65, 50001, 8
@@ -516,7 +516,8 @@ def test_accept_sampled_matches_oracle(tau):
     again = gu.gpu_accept(tl, tokens, par, depth, n, B, temperature=tau, seed=0xC0FFEE12345)
     other = gu.gpu_accept(tl, tokens, par, depth, n, B, temperature=tau, seed=7)
     assert np.array_equal(again["posterior"], got["posterior"])
-    assert np.mean(other["posterior"][0][: n + 1] == got["posterior"][0][: n + 1]) < 0.5
+    if tau >= 0.3:   # (close to greedy, the largest logit wins whatever the seed)
+        assert np.mean(other["posterior"][0][: n + 1] == got["posterior"][0][: n + 1]) < 0.5
 
 
 def test_accept_sampled_walks_down_a_planted_chain_and_batches():
