@@ -703,9 +703,22 @@ __global__ __launch_bounds__(kBuildThreads) void build_kernel(
     const int W = (T + 63) / 64;
     if (tid == 0) n_nodes[seq] = built;
 
-    for (int i0 = 0; i0 < T; i0 += kBuildThreads) {
+    // Node ids are dealt so that T = 257 (a budget of 256 and the root) takes one pass: the last
+    // thread also takes the root, whose row is trivial, before its own node.
+    for (int i0 = 1; i0 < T; i0 += kBuildThreads) {
         const int i = i0 + tid;
-        if (i >= T) break;
+        if (i0 == 1 && tid == kBuildThreads - 1) {
+            const size_t o0 = (size_t)seq * T;
+            tokens[o0] = root_token[seq];
+            parent[o0] = -1;
+            depth[o0] = 0;
+            if (rank) rank[o0] = -1;
+            if (node_score) node_score[o0] = 0.0f;
+            uint64_t *m0 = ancestor_mask + o0 * W;
+            m0[0] = 1ull;
+            for (int w = 1; w < W; ++w) m0[w] = 0ull;
+        }
+        if (i >= T) continue;
         const size_t o = (size_t)seq * T + i;
         uint64_t *mrow = ancestor_mask + o * W;
         if (i > built) {
@@ -720,20 +733,12 @@ __global__ __launch_bounds__(kBuildThreads) void build_kernel(
         const uint32_t nd = s_node[i];
         // (depth and rank are clamped to the table: whatever the records hold, every read below
         // stays inside topk_tok and the chain scratch)
-        const int d = i == 0 ? 0 : min(max(node_depth(nd), 1), B);
-        if (i == 0) {
-            tokens[o] = root_token[seq];
-            parent[o] = -1;
-            depth[o] = 0;
-            if (rank) rank[o] = -1;
-            if (node_score) node_score[o] = 0.0f;
-        } else {
-            tokens[o] = tk[(d - 1) * K + min(node_rank(nd), K - 1)];
-            parent[o] = node_parent(nd);
-            depth[o] = d;
-            if (rank) rank[o] = node_rank(nd);
-            if (node_score) node_score[o] = s_score[i];
-        }
+        const int d = min(max(node_depth(nd), 1), B);
+        tokens[o] = tk[(d - 1) * K + min(node_rank(nd), K - 1)];
+        parent[o] = node_parent(nd);
+        depth[o] = d;
+        if (rank) rank[o] = node_rank(nd);
+        if (node_score) node_score[o] = s_score[i];
         // ancestors of i (itself first, the root last): d + 1 ids, kept in this thread's
         // column of s_chain, then folded into the W mask words
         int j = i;
