@@ -65,6 +65,14 @@ size_t ddtree_workspace_bytes(int batch, int B, int V, int N, int Hq, int Hkv, i
                               int max_sum_L);
 
 /*
+ * Scratch that one ddtree_verify_attn call uses for exactly this shape and total cache length
+ * sum_L (0 for the shapes that take no scratch).  Never more than ddtree_workspace_bytes for the
+ * same shape and any cache length.  Pure host arithmetic.
+ */
+size_t ddtree_verify_attn_workspace_bytes(int batch, int T, int Hq, int Hkv, int D, int dtype,
+                                          long long sum_L);
+
+/*
  * Per-position log-probabilities and rank ordering (Section 4.3: q_i = softmax(l_i), tokens
  * ordered so that q_i^(1) >= q_i^(2) >= ..., and the scores sigma are sums of log q; Lemma 1
  * bounds the ranks that can matter by K).

@@ -20,6 +20,7 @@ _SIGNATURES = {
     "ddtree_version": (ctypes.c_int, []),
     "ddtree_error_string": (ctypes.c_char_p, [_i]),
     "ddtree_workspace_bytes": (_sz, [_i] * 8),
+    "ddtree_verify_attn_workspace_bytes": (_sz, [_i] * 6 + [ctypes.c_longlong]),
     "ddtree_topk": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
     "ddtree_build": (_i, [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
                           _sz, _vp]),
@@ -121,6 +122,11 @@ def _dev(t, dtype, what):
 
 def workspace_bytes(batch, B, V, N, Hq, Hkv, D, max_sum_L) -> int:
     return int(load().ddtree_workspace_bytes(batch, B, V, N, Hq, Hkv, D, max_sum_L))
+
+
+def verify_attn_workspace_bytes(batch, T, Hq, Hkv, D, dtype, sum_L):
+    """Scratch that one verify_attn call uses for this shape and total cache length."""
+    return int(load().ddtree_verify_attn_workspace_bytes(batch, T, Hq, Hkv, D, dtype, int(sum_L)))
 
 
 class Workspace:

@@ -63,6 +63,16 @@ extern "C" size_t ddtree_workspace_bytes(int batch, int B, int V, int N, int Hq,
     return need < 256 ? 256 : need;
 }
 
+extern "C" size_t ddtree_verify_attn_workspace_bytes(int batch, int T, int Hq, int Hkv, int D, int dtype,
+                                                    long long sum_L)
+{
+    using namespace ddt;
+    if (batch < 1 || batch > DDTREE_MAX_BATCH || T < 1 || T > DDTREE_MAX_N + 1 || Hq < 1 || Hkv < 1 ||
+        Hq % Hkv != 0 || D < 8 || D > 256 || D % 8 != 0 || sum_L < 0)
+        return 0;
+    return attn_plan(batch, T, Hq, Hkv, D, sum_L, dtype).bytes;
+}
+
 extern "C" int ddtree_profile_enable(unsigned kernel_mask, int capacity)
 {
     using namespace ddt;

@@ -97,8 +97,9 @@ AttnPlan attn_plan(int batch, int T, int Hq, int Hkv, int D, long long sum_L, in
     // into fewer key ranges because it runs about twice as fast per key tile, fills the 256 compute
     // units with shorter key ranges.  Taken when everything fits one round and the model says so.
     const int full = nblk / 8, rem = nblk % 8;
-    if (full >= 1 && rem >= 1 && rem <= 4) {
+    if (full >= 1 && rem >= 1 && rem <= 4 && tiles >= 1) {
         const double c_tail = 0.5;
+        best_cost *= 0.97;  // (the uneven form always goes through partials: it has to pay for them)
         const long long base_m = (long long)batch * Hkv * full, base_t = (long long)batch * Hkv;
         for (int Sm = 1; Sm <= 32; ++Sm) {
             if (Sm > 1 && (long long)Sm * 4 > tiles) break;
@@ -132,11 +133,29 @@ AttnPlan attn_plan(int batch, int T, int Hq, int Hkv, int D, long long sum_L, in
     return p;
 }
 
-// Upper bound of attn_plan(...).bytes over all sum_L: splits only shrink with shorter caches.
+// Upper bound of attn_plan(...).bytes over all sum_L.  In the even form the key ranges only shrink
+// in number with shorter caches; in the uneven form the rounding of key tiles per range moves the
+// optimum around, so the bound there is what one round of workgroups allows at all.
 size_t attn_ws_upper(int batch, int T, int Hq, int Hkv, int D)
 {
     AttnPlan p = attn_plan(batch, T, Hq, Hkv, D, (long long)1 << 40, DDTREE_DTYPE_BF16);
-    return p.bytes;
+    int cap = p.part_splits;
+    const int G = Hq / Hkv;
+    const int nblk = (int)(((long long)T * G + 31) / 32);
+    const int full = nblk / 8, rem = nblk % 8;
+    const long long base_m = (long long)batch * Hkv * full, base_t = (long long)batch * Hkv;
+    bool uneven_possible = false;
+    if (full >= 1 && rem >= 1 && rem <= 4 && base_m + base_t <= 256) {
+        uneven_possible = true;  // (it stores partials even with a single key range)
+        long long sm = (256 - base_t) / base_m;
+        if (sm > 32) sm = 32;
+        if ((int)sm > cap) cap = (int)sm;
+    }
+    if (cap <= 1 && !uneven_possible) return p.bytes;
+    const size_t rows = (size_t)batch * T * Hq;
+    size_t off = align_up((size_t)cap * rows * D * 2, 256);
+    off = align_up(off + (size_t)cap * rows * 4, 256);
+    return off > p.bytes ? off : p.bytes;
 }
 
 __device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xFFFFu) | (b << 16); }
@@ -697,15 +716,18 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const uint16_t *__restr
             float l[kMergeBatch];
 #pragma unroll
             for (int j = 0; j < kMergeBatch; ++j) {
-                l[j] = s0 + j < splits ? lse[(size_t)(s0 + j) * n_rows] : -INFINITY;
-                // (an empty key range has no partial: nothing, not even its bits, is read)
-                v[j] = l[j] > -INFINITY ? *reinterpret_cast<const f16x8 *>(part + (size_t)(s0 + j) * pstride) : f16x8(0);
+                const bool on = s0 + j < splits;
+                l[j] = on ? lse[(size_t)(s0 + j) * n_rows] : -INFINITY;
+                v[j] = on ? *reinterpret_cast<const f16x8 *>(part + (size_t)(s0 + j) * pstride) : f16x8(0);
             }
 #pragma unroll
             for (int j = 0; j < kMergeBatch; ++j) {
-                const float w = __builtin_amdgcn_exp2f(l[j] - mx);
+                // an empty key range (lse = -inf) has no partial behind it: whatever bits were
+                // read there must not reach the sum, not even times zero
+                const bool live = l[j] > -INFINITY;
+                const float w = live ? __builtin_amdgcn_exp2f(l[j] - mx) : 0.0f;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc[e] += w * (float)v[j][e];
+                for (int e = 0; e < 8; ++e) acc[e] += live ? w * (float)v[j][e] : 0.0f;
                 wsum += w;
             }
         }

@@ -57,6 +57,24 @@ def test_workspace_sizing_is_host_arithmetic(lib):
     assert dd.workspace_bytes(0, 16, 151936, 256, 32, 8, 128, 8192) == 0
 
 
+def test_attention_scratch_never_exceeds_the_workspace_bound(lib):
+    # ddtree_workspace_bytes must cover ddtree_verify_attn for every cache length: sweep budgets,
+    # head layouts and lengths (the split of the key range, hence the scratch, depends on all three)
+    import ctypes
+    lib.ddtree_verify_attn_workspace_bytes.restype = ctypes.c_size_t
+    lib.ddtree_verify_attn_workspace_bytes.argtypes = [ctypes.c_int] * 6 + [ctypes.c_longlong]
+    worst = 0.0
+    for batch, Hq, Hkv in ((1, 32, 8), (1, 8, 2), (1, 4, 4), (2, 16, 2), (4, 32, 8), (16, 64, 8), (1, 64, 8)):
+        for N in (1, 7, 8, 15, 16, 31, 32, 63, 64, 65, 100, 127, 128, 200, 255, 256, 257, 300, 511, 512, 1024):
+            bound = lib.ddtree_workspace_bytes(batch, 16, 151936, N, Hq, Hkv, 128, 1 << 30)
+            assert bound > 0
+            for L in (0, 1, 63, 64, 65, 200, 257, 1000, 2048, 4097, 8192, 20000, 32768, 100000, 1 << 20):
+                need = lib.ddtree_verify_attn_workspace_bytes(batch, N + 1, Hq, Hkv, 128, 0, batch * L)
+                assert need <= bound, (batch, Hq, Hkv, N, L, need, bound)
+                worst = max(worst, need / bound)
+    assert worst > 0.2   # the bound is not vacuous
+
+
 def test_bad_arguments_are_rejected_before_any_launch(lib):
     ERR_ARG, ERR_WS = -1, -2
     buf = ctypes.create_string_buffer(4096)
