@@ -220,8 +220,11 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
     s_hist[tid] = 0;
     if (tid == 0) s_hist[kLvBuckets] = 0;
     const float hi = s_lp[0];
+    // lower end of the bucket range: with K >= N the N-th rank of row 0 is a lower bound on the
+    // N-th best score; with fewer ranks than budget there is no such bound and a fixed span of 48
+    // (nats) below the best score stands in (scores further down share the overflow bucket)
     const float lo_raw = s_lp[min(K, N) - 1];
-    const float lo = lo_raw > kLvNeg ? lo_raw : hi - 64.0f;
+    const float lo = (K >= N && lo_raw > kLvNeg) ? lo_raw : hi - 48.0f;
     // lo itself maps to the middle of the last regular bucket; scores further down go to bucket
     // kLvBuckets.  Monotone in the score: subtraction, scaling, clamping and truncation all
     // preserve order.

@@ -172,6 +172,36 @@ def test_build_rows_with_minus_infinity(build_algo):
         _check_build(tok, lp, N)
 
 
+def test_build_randomized_shapes(build_algo):
+    # a seeded sweep over depths, rank counts (also fewer ranks than budget), budgets and kinds of
+    # rows: smooth, peaked, mixed sharpness per row, and rows with many exactly equal values
+    rng = np.random.default_rng(77)
+
+    def rows(B, K, kind):
+        if kind == "dyadic":
+            return (-np.sort(rng.integers(0, 8, size=(B, K)), axis=1) / 4.0).astype(np.float32)
+        if kind == "few":
+            x = rng.integers(0, 4, size=(B, K)).astype(np.float64) * 1.5
+        elif kind == "peaked":
+            x = rng.normal(size=(B, K)); x[:, 0] += rng.uniform(2, 12, size=B)
+        elif kind == "mixed":
+            x = rng.normal(size=(B, K)) * rng.uniform(0.2, 4, size=(B, 1)); x[:, 0] += rng.uniform(0, 10, size=B)
+        else:
+            x = rng.normal(size=(B, K))
+        x = -np.sort(-x, axis=1)
+        m = x.max(1, keepdims=True)
+        return (x - (np.log(np.exp(x - m).sum(1, keepdims=True)) + m)).astype(np.float32)
+
+    for case in range(150):
+        kind = ["flat", "peaked", "mixed", "dyadic", "few"][case % 5]
+        B = int(rng.integers(1, 17))
+        N = int(rng.choice([1, 2, 5, 17, 40, 64, 65, 100, 129, 200, 256, 300, 512, 777, 1024]))
+        K = int(min(N, rng.choice([1, 2, 3, 8, 50, 200, 1024])))
+        lp = rows(B, K, kind)
+        tok = rng.permutation(B * K).astype(np.int32).reshape(B, K)
+        _check_build(tok, lp, N, root=3)
+
+
 def test_build_exact_ties_and_dry_heap(build_algo):
     rng = np.random.default_rng(5)
     for trial in range(20):
