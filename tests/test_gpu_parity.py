@@ -352,6 +352,36 @@ def test_attn_batched_ragged():
         assert attn_err(got[b], refs[b]) < 1e-2
 
 
+def test_attn_randomized_shapes():
+    # seeded sweep over head layouts, row counts, ragged batches and cache lengths (every tiling
+    # and key split the planner can choose), checked on sampled (node, head) pairs
+    rng = np.random.default_rng(123)
+    worst = 0.0
+    for case in range(30):
+        Hkv = int(rng.choice([1, 2, 4, 8])); G = int(rng.choice([1, 2, 4, 8])); Hq = Hkv * G
+        T = int(rng.choice([2, 9, 17, 33, 40, 65, 66, 100, 129, 200, 257, 258, 300, 513]))
+        batch = int(rng.choice([1, 1, 1, 2, 3]))
+        Ls = [int(rng.choice([0, 1, 63, 64, 65, 200, 1000, 2048, 4100])) for _ in range(batch)]
+        off = np.concatenate([[0], np.cumsum(Ls)]).astype(np.int32)
+        qs, kcs, vcs, kts, vts, ms = [], [], [], [], [], []
+        for b in range(batch):
+            q, kc, vc, kt, vt = di.attn_tensors(5000 + 10 * case + b, T, Ls[b], Hq, Hkv, 128, "bf16")
+            par, n = _random_tree(rng, T, int(rng.integers(1, T)) if rng.random() < 0.3 else None)
+            qs.append(q); kcs.append(kc); vcs.append(vc); kts.append(kt); vts.append(vt)
+            ms.append(oracle.ancestor_mask(par, n, T=T))
+        got = gu.gpu_attn(np.concatenate(qs), np.concatenate(kcs), np.concatenate(vcs), np.concatenate(kts),
+                          np.concatenate(vts), np.stack(ms), off, batch, T, "bf16")
+        for b in range(batch):
+            pairs = np.stack([rng.integers(0, T, 32), rng.integers(0, Hq, 32)], axis=1).astype(np.int32)
+            pairs[0] = (T - 1, Hq - 1)
+            pairs[1] = (0, 0)
+            ref = oracle.verify_attn(qs[b], kcs[b], vcs[b], kts[b], vts[b], ms[b], pairs=pairs)
+            err = attn_err(got[b][pairs[:, 0], pairs[:, 1]], ref)
+            assert err < 1e-2, (case, b, T, Hq, Hkv, Ls, err)
+            worst = max(worst, err)
+    print(f"worst error over the sweep {worst:.2e}")
+
+
 # ------------------------------------------------------------------------------- accept
 def _tree_for_accept(seed, B, V, N, spike):
     x = _peaked_logits(seed, B, V, spike)
