@@ -80,8 +80,14 @@ size_t ddtree_verify_attn_workspace_bytes(int batch, int T, int Hq, int Hkv, int
  *   topk_tok  [device] int32 [batch, B, K]  token of rank k at position d; equal logits are
  *                                           ranked by ascending token id
  *   topk_lp   [device] fp32 [batch, B, K]   log q_d(topk_tok[d][k]) = logit - logsumexp(row),
- *                                           the log-sum-exp evaluated in fp64, rounded once
- * Requires 1 <= K <= min(V, DDTREE_MAX_N), 1 <= B <= DDTREE_MAX_B.
+ *                                           evaluated in fp64 as (logit - max) - log1p(sum of
+ *                                           exp(x - max) over every entry but the first maximum)
+ *                                           and rounded once: a token that holds nearly all the
+ *                                           probability keeps its tiny negative log-probability
+ * Requires 1 <= K <= min(V, DDTREE_MAX_N), 1 <= B <= DDTREE_MAX_B, and that the candidates of one
+ * row fit the merge workgroup's LDS: ceil(V / 12288) * min(K, 12288) <= 14336, i.e. any K up to
+ * V = 172032 (K = 1024), V <= 344064 at K = 512, V <= 688128 at K = 256.  Other shapes return
+ * DDTREE_ERR_ARG (and ddtree_workspace_bytes returns 0 for them).
  */
 int ddtree_topk(const float *logits, int batch, int B, int V, int K, int32_t *topk_tok,
                 float *topk_lp, void *workspace, size_t workspace_bytes, void *stream);

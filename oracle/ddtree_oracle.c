@@ -92,12 +92,21 @@ int oracle_topk(const float *logits, int B, int V, int K, int32_t *tok, float *l
             status = -2;
             continue;
         }
+        /* log-sum-exp as max + log1p(sum over every element but the first maximum): the same
+         * number as max + log(sum over all), without the cancellation that the leading 1 causes
+         * when one token holds nearly all the probability (its log-probability is -log1p(tiny)) */
         float m = row[0];
+        int vmax = 0;
         for (int v = 1; v < V; ++v)
-            if (row[v] > m) m = row[v];
-        double S = 0.0;
-        for (int v = 0; v < V; ++v) S += exp((double)row[v] - (double)m);
-        double lse = (double)m + log(S);
+            if (row[v] > m) {
+                m = row[v];
+                vmax = v;
+            }
+        double S1 = 0.0;
+        for (int v = 0; v < V; ++v)
+            if (v != vmax) S1 += exp((double)row[v] - (double)m);
+        const double excess = log1p(S1);
+        double lse = (double)m + excess;
         if (lse_out) lse_out[d] = lse;
         for (int v = 0; v < V; ++v) {
             e[v].logit = row[v];
@@ -106,7 +115,7 @@ int oracle_topk(const float *logits, int B, int V, int K, int32_t *tok, float *l
         qsort(e, (size_t)V, sizeof(tok_entry), cmp_tok_entry);
         for (int k = 0; k < K; ++k) {
             tok[(size_t)d * K + k] = e[k].id;
-            lp[(size_t)d * K + k] = (float)((double)e[k].logit - lse);
+            lp[(size_t)d * K + k] = (float)(((double)e[k].logit - (double)m) - excess);
         }
         free(e);
     }

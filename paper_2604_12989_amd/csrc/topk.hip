@@ -358,6 +358,7 @@ __global__ __launch_bounds__(kChunkThreads) void topk_chunk_kernel(
     __shared__ uint32_t s_bound[kChunkWaves];
     __shared__ float s_fmin[kChunkWaves];
     __shared__ double s_dsum[kChunkWaves];
+    __shared__ int s_neq[kChunkWaves];
     __shared__ double s_exp2[64];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -443,13 +444,27 @@ __global__ __launch_bounds__(kChunkThreads) void topk_chunk_kernel(
     }
     const float lo = (take_all || void_bound) ? cmin : key_float(t);
 
-    // ---- sum of exp(x - cmax) in fp64, fixed reduction order ----
+    // ---- sum of exp(x - cmax) in fp64, fixed reduction order, one instance of the maximum left
+    //      out: the row's log-sum-exp is formed as max + log1p(sum over everything else), which
+    //      stays accurate when one token holds nearly all the probability (its log-probability
+    //      is -log1p(tiny), and a sum that starts at 1 would have rounded the tiny part away).
+    //      Elements equal to the maximum are counted, not added.
     double acc = 0.0;
+    int neq = 0;
 #pragma unroll
     for (int s = 0; s < kSlots; ++s)
-        if ((active >> s) & 1u) acc += exp_nonpositive((double)x[s] - (double)cmax, s_exp2);
+        if ((active >> s) & 1u) {
+            const bool eq = x[s] == cmax;
+            neq += eq ? 1 : 0;
+            const double e = exp_nonpositive((double)x[s] - (double)cmax, s_exp2);
+            acc += eq ? 0.0 : e;
+        }
     acc = wave_sum_f64_lane63(acc);
-    if (lane == 63) s_dsum[wave] = acc;
+    neq = wave_scan_inclusive_i32(neq);
+    if (lane == 63) {
+        s_dsum[wave] = acc;
+        s_neq[wave] = neq;
+    }
 
     // ---- rank the elements that reach t ----
     const uint32_t base_id = (uint32_t)start;
@@ -466,10 +481,14 @@ __global__ __launch_bounds__(kChunkThreads) void topk_chunk_kernel(
     __syncthreads();
     if (tid == 0) {
         double S = s_dsum[0];
-        for (int w = 1; w < kChunkWaves; ++w) S += s_dsum[w];
+        int n_max = s_neq[0];
+        for (int w = 1; w < kChunkWaves; ++w) {
+            S += s_dsum[w];
+            n_max += s_neq[w];
+        }
         double *st = stat + (row * chunks + c) * 2;
         st[0] = (double)cmax;
-        st[1] = S;
+        st[1] = S + (double)(n_max - 1);  // everything but one instance of the chunk maximum
     }
     if (!done) {
         // exact radix select over the whole chunk, then all-pairs ranking of the kc selected
@@ -521,7 +540,7 @@ __global__ __launch_bounds__(kMergeThreads) void topk_merge_kernel(
     __shared__ unsigned long long s_T, s_top;
     __shared__ uint32_t s_mkey;
     __shared__ double s_part[kMergeWaves];
-    __shared__ double s_lse;
+    __shared__ double s_lse;  // log1p(sum over everything but the first maximum): lse - max
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t row = (size_t)blockIdx.y * gridDim.x + blockIdx.x;
@@ -570,30 +589,34 @@ __global__ __launch_bounds__(kMergeThreads) void topk_merge_kernel(
     }
     __syncthreads();
     // ---- log-sum-exp of the row from the chunk statistics (fp64, fixed order) ----
+    // The chunk sums leave one instance of their own maximum out; the chunk that holds the row's
+    // first maximum (its top candidate is the row's top candidate) stays that way, every other
+    // chunk gets its instance back: the total is the sum over everything but the row's first
+    // maximum, and the log-sum-exp is mx + log1p(total).
     const double mx = (double)key_float(s_mkey);
-    double part = tid < chunks ? c_sum * exp(c_max - mx) : 0.0;
+    double part = tid < chunks ? (c_sum + (c_top == s_top ? 0.0 : 1.0)) * exp(c_max - mx) : 0.0;
     for (int c = tid + kMergeThreads; c < chunks; c += kMergeThreads)
-        part += st[2 * c + 1] * exp(st[2 * c] - mx);
+        part += (st[2 * c + 1] + (in[(size_t)c * kc] == s_top ? 0.0 : 1.0)) * exp(st[2 * c] - mx);
     part = wave_sum_f64_lane63(part);
     // T == 0 (a chunk shorter than q): every candidate counts, which the radix select handles
     const float lo = s_T >> 32 ? key_float((uint32_t)(s_T >> 32)) : -INFINITY;
     const float hi = key_float((uint32_t)(s_top >> 32));
     // s_lse is read by emit() only after the barriers of the ranking
     if (chunks <= 64) {
-        if (tid == 63) s_lse = mx + log(part);
+        if (tid == 63) s_lse = log1p(part);
     } else {
         if (lane == 63) s_part[wave] = part;
         __syncthreads();
         if (tid == kMergeThreads - 1) {
             double S = s_part[0];
             for (int w = 1; w < kMergeWaves; ++w) S += s_part[w];
-            s_lse = mx + log(S);
+            s_lse = log1p(S);
         }
     }
     // ---- rank the candidates that reach T ----
     auto emit = [&](int rank, uint64_t cc) {
         topk_tok[row * (size_t)K + rank] = (int32_t)(~(uint32_t)cc);
-        topk_lp[row * (size_t)K + rank] = (float)((double)key_float((uint32_t)(cc >> 32)) - s_lse);
+        topk_lp[row * (size_t)K + rank] = (float)(((double)key_float((uint32_t)(cc >> 32)) - mx) - s_lse);
     };
     BucketScratch bs{s_cnt, s_start, s_list, s_wave, s_misc};
     int m;

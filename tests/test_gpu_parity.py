@@ -100,6 +100,59 @@ def test_topk_batched():
         assert ulp_diff(lp_g[b], lp_o).max() <= 2
 
 
+def test_topk_nearly_certain_rows():
+    """One token holds all but 1e-5 .. 1e-11 of the probability: its log-probability is a tiny
+    negative number that only survives when the log-sum-exp is formed as max + log1p(rest)."""
+    for V, K in ((7, 7), (64, 16), (1000, 16), (50001, 64)):
+        rng = np.random.default_rng(V)
+        x = rng.standard_normal((6, V)).astype(np.float32)
+        x[np.arange(6), rng.integers(0, V, 6)] += np.float32(25.0)
+        x[5, :] = x[5, :].min()                 # ... and a row whose maximum is repeated V times
+        tok_o, lp_o = oracle.topk(x, K)
+        tok_g, lp_g = gu.gpu_topk(x, K)
+        assert np.array_equal(tok_g[0], tok_o), V
+        assert np.all(lp_o[:5, 0] < 0) and np.all(lp_o[:5, 0] > -1e-3)
+        assert ulp_diff(lp_g[0], lp_o).max() <= 2, V
+
+
+def test_topk_randomized_shapes():
+    """Seeded sweep over vocabulary sizes (one element to several chunks with a ragged tail), K,
+    batch and row kinds; token ids bit-exact, log-probabilities within 2 ulp."""
+    rng = np.random.default_rng(2024)
+    worst = 0
+    for c in range(60):
+        V = int(rng.choice([1, 2, 7, 64, 1000, 4096, 12288, 12289, 20000, 50001, 151936, 200003]))
+        B = int(rng.integers(1, 17))
+        K = int(min(V, rng.choice([1, 2, 16, 64, 255, 256, 257, 512, 1024])))
+        kind = ["normal", "wide", "ints", "const", "spiky", "masked"][c % 6]
+        if kind == "normal":
+            x = rng.standard_normal((B, V))
+        elif kind == "wide":
+            x = rng.standard_normal((B, V)) * rng.uniform(0.1, 30, size=(B, 1))
+        elif kind == "ints":
+            x = rng.integers(-3, 4, size=(B, V)).astype(np.float64)
+        elif kind == "const":
+            x = np.full((B, V), float(rng.normal()))
+        elif kind == "spiky":
+            x = rng.standard_normal((B, V))
+            x[np.arange(B), rng.integers(0, V, B)] += 25.0
+        else:
+            x = rng.standard_normal((B, V))
+            x[:, rng.random(V) < 0.7] = -np.inf
+            x[:, 0] = 0.0
+        x = x.astype(np.float32)
+        tok_o, lp_o = oracle.topk(x, K)
+        tok_g, lp_g = gu.gpu_topk(x, K)
+        fin = np.isfinite(lp_o)
+        assert np.array_equal(tok_g[0], tok_o), (c, kind, B, V, K)
+        assert np.array_equal(np.isfinite(lp_g[0]), fin), (c, kind, B, V, K)
+        if fin.any():
+            u = int(ulp_diff(lp_g[0][fin], lp_o[fin]).max())
+            worst = max(worst, u)
+            assert u <= 2, (c, kind, B, V, K, u)
+    print(f"worst log-probability difference {worst} ulp")
+
+
 # ------------------------------------------------------------------------------- build
 @pytest.fixture(params=["auto", "pops", "levels"])
 def build_algo(request):

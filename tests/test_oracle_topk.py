@@ -82,3 +82,24 @@ def test_dominant_token_gives_zero_logprob():
     tok, lp = oracle.topk(x, 3)
     assert tok[0, 0] == 42 and lp[0, 0] == 0.0
     assert tok[0, 1] == 0 and tok[0, 2] == 1 and lp[0, 1] == -250.0
+
+
+def test_nearly_certain_token_closed_form():
+    """One logit c above V - 1 zeros: log q of the top token is -log1p((V - 1) e^-c) and of the
+    others -c - log1p((V - 1) e^-c); the first is far below one ulp of the row's log-sum-exp, so a
+    formulation that subtracts the log-sum-exp from the logit gets it wrong by many ulps."""
+    import math
+    from fractions import Fraction
+
+    for V, c in ((7, 25.0), (64, 25.0), (1000, 25.0), (1000, 12.0), (151936, 30.0)):
+        x = np.zeros((1, V), np.float32)
+        x[0, V // 3] = c
+        tok, lp = oracle.topk(x, 2)
+        # log1p(t) for tiny t by its alternating series in exact rationals (t < 1e-2: 12 terms
+        # leave < 1e-26 relative), with e^-c itself from math.exp (relative error < 1e-16)
+        t = Fraction(V - 1) * Fraction(math.exp(-c))
+        series = sum(Fraction((-1) ** (j + 1), j) * t**j for j in range(1, 13))
+        top = np.float32(-float(series))
+        assert tok[0, 0] == V // 3 and tok[0, 1] == 0
+        assert abs(int(lp[0, 0].view(np.int32)) - int(top.view(np.int32))) <= 1, (V, c, lp[0, 0], top)
+        assert lp[0, 1] == np.float32(-c - float(series))
