@@ -221,7 +221,9 @@ int ddtree_build_giveups(unsigned int *count);
  * kernel's bit is set in kernel_mask, every launch of that kernel is bracketed by a pair of HIP
  * events recorded on the launch stream, up to `capacity` launches per kernel; the events are
  * created here, never inside the hot calls.  kernel_mask = 0 switches the hook off and destroys
- * the events.  ddtree_profile_read copies the elapsed milliseconds of the recorded launches of
+ * the events.  ddtree_profile_enable_every times one launch in `every` (the first, the
+ * (every+1)-th, ...): a recorded event pair costs the stream about a microsecond, which a timed
+ * loop may not want to pay on every launch.  ddtree_profile_read copies the elapsed milliseconds of the recorded launches of
  * one kernel to host memory and returns how many there were (or a negative error); the caller
  * must have synchronised the stream(s) first.  ddtree_profile_reset forgets recorded launches.
  * Not thread-safe; meant for a single benchmarking thread.
@@ -236,6 +238,7 @@ int ddtree_build_giveups(unsigned int *count);
 #define DDTREE_KERNEL_ATTN_GENERIC 7
 #define DDTREE_KERNEL_COUNT 8
 int ddtree_profile_enable(unsigned kernel_mask, int capacity);
+int ddtree_profile_enable_every(unsigned kernel_mask, int capacity, int every);
 int ddtree_profile_reset(void);
 int ddtree_profile_read(int kernel_id, float *ms_out /* [host] */, int max_records);
 

@@ -34,6 +34,7 @@ _SIGNATURES = {
     "ddtree_set_build_algorithm": (_i, [_i]),
     "ddtree_build_giveups": (_i, [ctypes.POINTER(ctypes.c_uint)]),
     "ddtree_profile_enable": (_i, [ctypes.c_uint, _i]),
+    "ddtree_profile_enable_every": (_i, [ctypes.c_uint, _i, _i]),
     "ddtree_profile_reset": (_i, []),
     "ddtree_profile_read": (_i, [_i, _vp, _i]),
 }
@@ -263,12 +264,12 @@ def build_giveups():
     return int(n.value)
 
 
-def profile_enable(kernels, capacity):
-    """Time every launch of the named kernels (see KERNELS) with HIP events; [] switches it off."""
+def profile_enable(kernels, capacity, every=1):
+    """Time one launch in `every` of the named kernels (see KERNELS) with HIP events; [] switches it off."""
     mask = 0
     for k in kernels:
         mask |= 1 << KERNELS[k]
-    _check(load().ddtree_profile_enable(mask, int(capacity)), "ddtree_profile_enable")
+    _check(load().ddtree_profile_enable_every(mask, int(capacity), int(every)), "ddtree_profile_enable_every")
 
 
 def profile_reset():

@@ -23,10 +23,11 @@ static void profiler_destroy(Profiler &p)
             delete[] p.stop[k];
             p.start[k] = p.stop[k] = nullptr;
         }
-        p.count[k] = 0;
+        p.count[k] = p.seen[k] = 0;
     }
     p.mask = 0;
     p.capacity = 0;
+    p.every = 1;
 }
 }  // namespace ddt
 
@@ -75,13 +76,19 @@ extern "C" size_t ddtree_verify_attn_workspace_bytes(int batch, int T, int Hq, i
 
 extern "C" int ddtree_profile_enable(unsigned kernel_mask, int capacity)
 {
+    return ddtree_profile_enable_every(kernel_mask, capacity, 1);
+}
+
+extern "C" int ddtree_profile_enable_every(unsigned kernel_mask, int capacity, int every)
+{
     using namespace ddt;
     Profiler &p = profiler();
     profiler_destroy(p);
     if (kernel_mask == 0) return DDTREE_OK;
-    if (capacity < 1 || capacity > (1 << 20) || (kernel_mask >> DDTREE_KERNEL_COUNT) != 0)
+    if (capacity < 1 || capacity > (1 << 20) || (kernel_mask >> DDTREE_KERNEL_COUNT) != 0 || every < 1)
         return DDTREE_ERR_ARG;
     p.capacity = capacity;
+    p.every = every;
     for (int k = 0; k < DDTREE_KERNEL_COUNT; ++k) {
         if (!(kernel_mask & (1u << k))) continue;
         p.start[k] = new hipEvent_t[capacity];
@@ -97,7 +104,7 @@ extern "C" int ddtree_profile_enable(unsigned kernel_mask, int capacity)
 extern "C" int ddtree_profile_reset(void)
 {
     ddt::Profiler &p = ddt::profiler();
-    for (int k = 0; k < DDTREE_KERNEL_COUNT; ++k) p.count[k] = 0;
+    for (int k = 0; k < DDTREE_KERNEL_COUNT; ++k) p.count[k] = p.seen[k] = 0;
     return DDTREE_OK;
 }
 

@@ -65,6 +65,8 @@ AcceptPlan accept_plan(int batch, int T, int V);
 struct Profiler {
     unsigned mask = 0;
     int capacity = 0;
+    int every = 1;                          // time one launch in `every`
+    int seen[DDTREE_KERNEL_COUNT] = {};     // launches since the hook was switched on
     int count[DDTREE_KERNEL_COUNT] = {};
     hipEvent_t *start[DDTREE_KERNEL_COUNT] = {};
     hipEvent_t *stop[DDTREE_KERNEL_COUNT] = {};
@@ -75,6 +77,7 @@ inline int profile_begin(int id, hipStream_t st)
 {
     Profiler &p = profiler();
     if (!(p.mask & (1u << id)) || p.count[id] >= p.capacity) return -1;
+    if (p.seen[id]++ % p.every != 0) return -1;
     const int slot = p.count[id];
     (void)hipEventRecord(p.start[id][slot], st);
     return slot;

@@ -112,6 +112,7 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
                               None) == ERR_ARG
     # profile hook: bad arguments
     assert lib.ddtree_profile_enable(1 << 20, 4) == ERR_ARG
+    assert lib.ddtree_profile_enable_every(1, 4, 0) == ERR_ARG
     assert lib.ddtree_profile_read(99, p, 1) == ERR_ARG
     # the construction selector takes its three values only, and is host-side state
     assert lib.ddtree_set_build_algorithm(3) == ERR_ARG
