@@ -649,6 +649,50 @@ def test_accept_sampled_walks_down_a_planted_chain_and_batches():
     assert list(got["path"][0][:5]) == [0, 1, 2, 3, 4]
 
 
+def test_accept_randomized_shapes():
+    """Seeded sweep of the acceptance step over vocabulary sizes (one segment to many, ragged
+    tails), budgets, batch sizes with different node counts per sequence, tree shapes (bushy to
+    chains), how often the target agrees with the tree, and ties in the target's logits; greedy
+    rule bit-exact, sampled rule checked as in the tests above."""
+    rng = np.random.default_rng(777)
+    accepted = []
+    for case in range(36):
+        V = int(rng.choice([2, 7, 1000, 4096, 12289, 50001, 151936]))
+        B = int(rng.integers(1, 17))
+        N = int(rng.choice([1, 2, 15, 64, 100, 256]))
+        batch = int(rng.integers(1, 4)) if V * (N + 1) < 3e7 else 1
+        spike = float(rng.uniform(0.0, 14.0))
+        p = float(rng.choice([0.0, 0.5, 0.9, 1.0]))
+        xs, trees = [], []
+        for b in range(batch):
+            xl = _peaked_logits(1000 + 10 * case + b, B, V, spike)
+            K = int(min(V, N, rng.choice([1, 2, 4, N])))
+            tok, lp = oracle.topk(xl, K)
+            tree = oracle.build_tree(tok, lp, N, root_token=int(rng.integers(0, V)))
+            plant = di.planted_tokens(2000 + case, tree["depth"], tok[:, 0], B, p=p)
+            x = di.target_logits(2000 + case, N + 1, V, plant, batch_index=b)
+            if case % 4 == 3:                    # exact ties: the first maximum has to win
+                x = np.round(x * 2) / 2
+            xs.append(x.astype(np.float32))
+            trees.append(tree)
+        stack = lambda k: np.stack([t[k] for t in trees])
+        nn = [t["n_nodes"] for t in trees]
+        g = gu.gpu_accept(np.stack(xs), stack("tokens"), stack("parent"), stack("depth"), nn, B)
+        for b in range(batch):
+            o = oracle.accept(xs[b], trees[b]["tokens"], trees[b]["parent"], trees[b]["n_nodes"], B)
+            n = trees[b]["n_nodes"]
+            what = (case, b, V, B, N, batch, n)
+            assert np.array_equal(g["posterior"][b][:n], o["posterior"][:n]), what
+            assert np.array_equal(g["path"][b], o["path"]), what
+            assert int(g["n_accepted"][b]) == o["n_accepted"] and int(g["bonus_token"][b]) == o["bonus"], what
+            accepted.append(o["n_accepted"])
+        if case % 3 == 0 and V >= 1000:
+            tau = float(rng.choice([0.3, 1.0, 2.0]))
+            _check_sampled(np.stack(xs), stack("tokens"), stack("parent"), stack("depth"), nn, B, tau,
+                           seed=int(rng.integers(1, 2**62)))
+    print(f"accepted lengths seen: min {min(accepted)} max {max(accepted)}")
+
+
 def test_accept_sampled_rejects_bad_temperature():
     import paper_2604_12989_amd as dd
     x = np.zeros((1, 3, 8), np.float32)
