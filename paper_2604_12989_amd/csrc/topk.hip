@@ -500,15 +500,24 @@ __global__ __launch_bounds__(kChunkThreads) void topk_chunk_kernel(
         if (tid == 0) s_misc[7] = 0;
         __syncthreads();
         auto get = [&](int i) -> uint64_t { return composite(s_key[i], i); };
-        SelectScratch sc{hist, s_list, s_wave, s_misc, &s_thr};
-        const uint64_t thr = block_select_threshold<kChunkThreads>(get, n, kc, sc);  // n > kc here
-        for (int i = tid; i < n; i += kChunkThreads) {
-            const uint64_t cc = get(i);
-            if (cc >= thr) s_list[atomicAdd(&s_misc[7], 1)] = cc;  // exactly kc <= kCandCap
+        if (n <= kc) {
+            // a ragged last chunk no longer than kc (it holds real -inf entries, or it would have
+            // been ranked above): every element is a candidate; n <= kc <= kCandCap
+            for (int i = tid; i < n; i += kChunkThreads) s_list[i] = get(i);
+            __syncthreads();
+            block_rank_emit<kChunkThreads>(s_list, n, emit);
+            m = n;
+        } else {
+            SelectScratch sc{hist, s_list, s_wave, s_misc, &s_thr};
+            const uint64_t thr = block_select_threshold<kChunkThreads>(get, n, kc, sc);
+            for (int i = tid; i < n; i += kChunkThreads) {
+                const uint64_t cc = get(i);
+                if (cc >= thr) s_list[atomicAdd(&s_misc[7], 1)] = cc;  // exactly kc <= kCandCap
+            }
+            __syncthreads();
+            block_rank_emit<kChunkThreads>(s_list, kc, emit);
+            m = kc;
         }
-        __syncthreads();
-        block_rank_emit<kChunkThreads>(s_list, kc, emit);
-        m = kc;
     }
     for (int i = m + tid; i < kc; i += kChunkThreads) out[i] = 0ull;  // chunk shorter than kc
 }

@@ -91,6 +91,23 @@ def test_topk_masked_vocabulary():
     assert ulp_diff(lp_g[0][fin], lp_o[fin]).max() <= 2
 
 
+def test_topk_masked_rows_with_a_last_chunk_shorter_than_K():
+    """V = 12289 at K = 1024 is cut into 12 chunks of 1028 with a last chunk of 981 < K entries;
+    with masked (-inf) entries in it every one of its elements is a candidate."""
+    rng = np.random.default_rng(323)
+    for V, K in ((12289, 1024), (4100, 1024), (2049, 1024), (1030, 1024)):
+        x = rng.standard_normal((3, V)).astype(np.float32)
+        x[:, rng.random(V) < 0.7] = -np.inf
+        x[:, 0] = 0.0
+        x[2, V - 500:] = -np.inf                 # a last chunk that is masked altogether
+        tok_o, lp_o = oracle.topk(x, K)
+        tok_g, lp_g = gu.gpu_topk(x, K)
+        assert np.array_equal(tok_g[0], tok_o), (V, K)
+        fin = np.isfinite(lp_o)
+        assert np.array_equal(np.isfinite(lp_g[0]), fin)
+        assert ulp_diff(lp_g[0][fin], lp_o[fin]).max() <= 2
+
+
 def test_topk_batched():
     xs = np.stack([di.draft_logits(11, 4, 20000, batch_index=b) for b in range(3)])
     tok_g, lp_g = gu.gpu_topk(xs, 32)
