@@ -43,7 +43,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--config", type=int, default=3, help="workload (ddtree_inputs.CONFIGS), 1..4")
+    ap.add_argument("--config", type=int, default=3, help="workload (ddtree_inputs.CONFIGS), 1..5")
     ap.add_argument("--budget", type=int, default=0,
                     help="override the node budget N of the workload (budget sweep; 0 = the config's own)")
     ap.add_argument("--sets", type=int, default=0, help="input copies to rotate over (0 = auto)")
@@ -71,20 +71,27 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     c = dict(di.CONFIGS[args.config])
-    assert c["batch"] == 1, "bench.py times the single-sequence configurations"
     if args.budget > 0:
         c["N"] = args.budget
         c["name"] = f"{c['name']}, budget {args.budget}"
     seed = di.config_seed(args.config)
-    B, V, N, Hq, Hkv, D, L = c["B"], c["V"], c["N"], c["Hq"], c["Hkv"], c["D"], c["L"]
+    batch, B, V, N, Hq, Hkv, D, L = c["batch"], c["B"], c["V"], c["N"], c["Hq"], c["Hkv"], c["D"], c["L"]
     K, T = min(N, V), N + 1
+    # cache lengths: one sequence of L rows, or (batched configuration) seeded ragged lengths
+    Ls = np.array([L]) if batch == 1 else di.ragged_lengths(seed, batch, *L)
+    kv_off = [int(v) for v in np.concatenate([[0], np.cumsum(Ls)])]
+    sum_L = kv_off[-1]
     bf16 = c["dtype"] == "bf16"
     dtype_id = dd.DTYPE_BF16 if bf16 else dd.DTYPE_FP32
 
     # ------------------------------------------------------------------ inputs (host, seeded)
     t0 = time.time()
-    logits_h = di.draft_logits(seed, B, V)
-    q_h, kc_h, vc_h, kt_h, vt_h = di.attn_tensors(seed, T, L, Hq, Hkv, D, c["dtype"])
+    logits_h = np.stack([di.draft_logits(seed, B, V, batch_index=s) for s in range(batch)])
+    if batch == 1:
+        q_h, kc_h, vc_h, kt_h, vt_h = di.attn_tensors(seed, T, L, Hq, Hkv, D, c["dtype"])
+    else:  # queries and tree rows of all sequences, one packed ragged cache
+        q_h, _, _, kt_h, vt_h = di.attn_tensors(seed, batch * T, 0, Hq, Hkv, D, c["dtype"])
+        _, kc_h, vc_h, _, _ = di.attn_tensors(seed + 1, 1, sum_L, Hq, Hkv, D, c["dtype"])
     log(f"[bench] config {args.config} ({c['name']}): inputs generated in {time.time() - t0:.1f}s")
 
     def attn_dev(a):
@@ -93,16 +100,17 @@ def main():
             return torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
         return torch.from_numpy(a).to(dev)
 
-    ws = dd.Workspace(1, B, V, N, Hq, Hkv, D, L)
-    root = torch.tensor([11], dtype=torch.int32, device=dev)
-    logits0 = torch.from_numpy(logits_h).to(dev)[None].contiguous()
+    ws = dd.Workspace(batch, B, V, N, Hq, Hkv, D, sum_L)
+    root = torch.full((batch,), 11, dtype=torch.int32, device=dev)
+    logits0 = torch.from_numpy(logits_h).to(dev).contiguous()
     # the tree of this workload (needed to plant the target's argmax); setup, not timed
     tok0, lp0 = dd.topk(logits0, K, ws)
     tree0 = dd.build(tok0, lp0, N, root)
     torch.cuda.synchronize()
-    depth_h = tree0["depth"].cpu().numpy()[0]
-    plant = di.planted_tokens(seed, depth_h, tok0.cpu().numpy()[0][:, 0], B)
-    tl_h = di.target_logits(seed, T, V, plant)
+    depth_h = tree0["depth"].cpu().numpy()
+    top1_h = tok0.cpu().numpy()[:, :, 0]
+    tl_h = np.stack([di.target_logits(seed, T, V, di.planted_tokens(seed, depth_h[s], top1_h[s], B, batch_index=s),
+                                      batch_index=s) for s in range(batch)])
     log(f"[bench] tree: {int(tree0['n_nodes'][0])} nodes, max depth {int(depth_h.max())}; "
         f"all inputs ready after {time.time() - t0:.1f}s")
 
@@ -110,21 +118,20 @@ def main():
         q_h.size + kc_h.size + vc_h.size + kt_h.size + vt_h.size)
     n_sets = args.sets or max(2, int(np.ceil(2.2 * 256e6 / bytes_per_set)))
     sets = []
-    base = dict(logits=logits0, tl=torch.from_numpy(tl_h).to(dev)[None].contiguous(), q=attn_dev(q_h),
+    base = dict(logits=logits0, tl=torch.from_numpy(tl_h).to(dev).contiguous(), q=attn_dev(q_h),
                 kc=attn_dev(kc_h), vc=attn_dev(vc_h), kt=attn_dev(kt_h), vt=attn_dev(vt_h))
     for s in range(n_sets):
         sets.append(base if s == 0 else {k: v.clone() for k, v in base.items()})
     # outputs, allocated once
     out_attn = torch.empty_like(base["q"])
-    tok = torch.empty((1, B, K), dtype=torch.int32, device=dev)
-    lp = torch.empty((1, B, K), dtype=torch.float32, device=dev)
+    tok = torch.empty((batch, B, K), dtype=torch.int32, device=dev)
+    lp = torch.empty((batch, B, K), dtype=torch.float32, device=dev)
     tree = {k: torch.empty_like(v) for k, v in tree0.items()}
-    acc = dict(path=torch.empty((1, B + 1), dtype=torch.int32, device=dev),
-               n_accepted=torch.empty((1,), dtype=torch.int32, device=dev),
-               bonus_token=torch.empty((1,), dtype=torch.int32, device=dev),
-               posterior=torch.empty((1, T), dtype=torch.int32, device=dev))
+    acc = dict(path=torch.empty((batch, B + 1), dtype=torch.int32, device=dev),
+               n_accepted=torch.empty((batch,), dtype=torch.int32, device=dev),
+               bonus_token=torch.empty((batch,), dtype=torch.int32, device=dev),
+               posterior=torch.empty((batch, T), dtype=torch.int32, device=dev))
     scale = 1.0 / float(np.sqrt(D))
-    kv_off = [0, L]
 
     # one pre-marshalled call list per input set: the timed loop is four ctypes calls per step
     steps = []
@@ -133,7 +140,7 @@ def main():
             dd.topk(s["logits"], K, ws, tok, lp, defer=True),
             dd.build(tok, lp, N, root, ws, tree, defer=True),
             dd.verify_attn(s["q"], s["kc"], s["vc"], s["kt"], s["vt"], tree["ancestor_mask"], kv_off,
-                           1, T, Hq, Hkv, D, scale, dtype_id, ws, out_attn, defer=True),
+                           batch, T, Hq, Hkv, D, scale, dtype_id, ws, out_attn, defer=True),
             dd.accept(s["tl"], tree["tokens"], tree["parent"], tree["depth"], tree["n_nodes"], B, ws,
                       acc, defer=True),
         ])
@@ -169,12 +176,13 @@ def main():
     elapsed = t_stop - t_start
     ms_per_step = 1e3 * elapsed / args.steps
     steps_per_s = args.steps / elapsed
-    n_acc = int(acc["n_accepted"][0])
+    n_acc = [int(v) for v in acc["n_accepted"].cpu()]
+    n_acc = n_acc[0] if batch == 1 else n_acc
 
     # ------------------------------------------------------------------ roofline of the main kernel
-    depth_now = tree["depth"].cpu().numpy()[0]
+    depth_now = tree["depth"].cpu().numpy()
     vis_tree = int((depth_now[depth_now >= 0] + 1).sum())
-    flops = 4.0 * D * Hq * (float(T) * L + vis_tree)  # algorithmic: QK^T and PV over visible keys
+    flops = 4.0 * D * Hq * (float(T) * sum_L + vis_tree)  # algorithmic: QK^T and PV over visible keys
     k_avg_ms = float(kernel_ms.mean())
     achieved = flops / (k_avg_ms * 1e-3) / 1e12
     # HBM bytes per launch from committed rocprofv3 --pmc summaries (FETCH_SIZE + WRITE_SIZE, each
@@ -218,18 +226,21 @@ def main():
     if not args.no_cpu:
         import oracle
         t_cpu = []
-        for _ in range(args.cpu_reps):
+        cpu_reps = args.cpu_reps if batch == 1 else 1
+        for _ in range(cpu_reps):
             t1 = time.perf_counter()
-            tok_o, lp_o = oracle.topk(logits_h, K)
-            tr = oracle.build_tree(tok_o, lp_o, N, 11)
-            mask_o = oracle.ancestor_mask(tr["parent"], tr["n_nodes"], T=T)
-            oracle.verify_attn(q_h, kc_h, vc_h, kt_h, vt_h, mask_o)
-            oracle.accept(tl_h, tr["tokens"], tr["parent"], tr["n_nodes"], B)
+            for s in range(batch):
+                tok_o, lp_o = oracle.topk(logits_h[s], K)
+                tr = oracle.build_tree(tok_o, lp_o, N, 11)
+                mask_o = oracle.ancestor_mask(tr["parent"], tr["n_nodes"], T=T)
+                oracle.verify_attn(q_h[s * T:(s + 1) * T], kc_h[kv_off[s]:kv_off[s + 1]], vc_h[kv_off[s]:kv_off[s + 1]],
+                                   kt_h[s * T:(s + 1) * T], vt_h[s * T:(s + 1) * T], mask_o)
+                oracle.accept(tl_h[s], tr["tokens"], tr["parent"], tr["n_nodes"], B)
             t_cpu.append(time.perf_counter() - t1)
         cpu = dict(value=round(1.0 / float(np.mean(t_cpu)), 4), unit="tree steps/s",
                    cores=oracle.num_threads(), kind="oracle",
-                   sample=f"{args.cpu_reps} full steps of the same config-{args.config} inputs "
-                          f"(all {T}x{Hq} attention rows), mean {np.mean(t_cpu):.2f} s/step")
+                   sample=f"{cpu_reps} full steps of the same config-{args.config} inputs "
+                          f"(all {batch}x{T}x{Hq} attention rows), mean {np.mean(t_cpu):.2f} s/step")
 
     result = {
         "metric": "tree steps/s (topk+build+verify-attn+accept)",
@@ -245,7 +256,8 @@ def main():
         "dtype": "bf16" if bf16 else "f32",
         "data": "synthetic",
         "config": {"workload": f"config {args.config} ({c['name']}): B={B} V={V} N={N} Hq={Hq} "
-                               f"Hkv={Hkv} D={D} L={L}", "input_sets_rotated": n_sets,
+                               f"Hkv={Hkv} D={D} " + (f"L={L}" if batch == 1 else
+                               f"batch={batch} ragged L={min(Ls)}..{max(Ls)} (sum {sum_L})"), "input_sets_rotated": n_sets,
                    "launch": "eager, 4 C-ABI calls per step on one stream",
                    "n_accepted": n_acc},
         "roofline": roofline,
