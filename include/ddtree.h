@@ -25,7 +25,9 @@
  *   - `workspace` [device] is scratch of at least ddtree_workspace_bytes(...) bytes, 256-byte
  *     aligned, whose contents need not survive between calls.  Calls on different streams need
  *     different workspaces.
- *   - All arrays are dense, row-major, in the index order written next to them.
+ *   - All arrays are dense, row-major, in the index order written next to them, and aligned
+ *     to their element size; the q / k / v / out tensors of ddtree_verify_attn to 16 bytes
+ *     (DDTREE_ERR_ARG otherwise).
  *   - Logits must be finite (the paper assumes probabilities in (0,1), Section 4.2).
  */
 #ifndef DDTREE_H
@@ -127,7 +129,10 @@ int ddtree_build(const int32_t *topk_tok, const float *topk_lp, int batch, int B
  * reads KV head h / (Hq / Hkv).  Rows whose own mask bit is clear (padding rows) produce zeros.
  *   q          [device] [batch*T, Hq, D]
  *   k_cache, v_cache [device] [sum_L, Hkv, D]   sequence s owns rows kv_offset[s]..kv_offset[s+1]
- *   k_tree, v_tree   [device] [batch*T, Hkv, D] sequence s owns rows s*T..(s+1)*T
+ *   k_tree, v_tree   [device] [batch*T, Hkv, D] sequence s owns rows s*T..(s+1)*T; all T rows
+ *                                               must hold finite values, those of padding nodes
+ *                                               too: a key that a row does not see has weight
+ *                                               zero but is still multiplied (0 * NaN = NaN)
  *   ancestor_mask    [device] uint64 [batch, T, W]
  *   kv_offset        [host]   int32 [batch+1], non-decreasing, kv_offset[0] >= 0
  *   dtype      DDTREE_DTYPE_BF16 (bf16 in/out, fp32 accumulation and softmax) or

@@ -349,6 +349,8 @@ extern "C" int ddtree_compact(const void *k_tree, const void *v_tree, const int3
         return DDTREE_ERR_ARG;
     const long long row_bytes = (long long)Hkv * D * elem_bytes;
     if (row_bytes % 4 != 0) return DDTREE_ERR_ARG;
+    for (const void *t : {k_tree, v_tree, static_cast<const void *>(k_cache), static_cast<const void *>(v_cache)})
+        if (reinterpret_cast<uintptr_t>(t) & 3u) return DDTREE_ERR_ARG;  // rows are copied in 4-byte words
     CompactArgs args;
     for (int s = 0; s < batch; ++s) {
         if (dst_row[s] < 0) return DDTREE_ERR_ARG;

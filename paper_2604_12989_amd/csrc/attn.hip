@@ -752,6 +752,22 @@ __device__ __forceinline__ float ld_elem(const uint16_t *p)
 {
     return __uint_as_float((uint32_t)(*p) << 16);
 }
+// eight consecutive elements (32- or 16-byte aligned: rows are multiples of eight elements long)
+__device__ __forceinline__ void ld_elem8(const float *p, float (&o)[8])
+{
+    const float4 a = reinterpret_cast<const float4 *>(p)[0], b = reinterpret_cast<const float4 *>(p)[1];
+    o[0] = a.x, o[1] = a.y, o[2] = a.z, o[3] = a.w, o[4] = b.x, o[5] = b.y, o[6] = b.z, o[7] = b.w;
+}
+__device__ __forceinline__ void ld_elem8(const uint16_t *p, float (&o)[8])
+{
+    const uint4 a = *reinterpret_cast<const uint4 *>(p);
+    const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        o[2 * i] = __uint_as_float(w[i] << 16);
+        o[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+    }
+}
 __device__ __forceinline__ void st_elem(float *p, float v) { *p = v; }
 __device__ __forceinline__ void st_elem(uint16_t *p, float v)
 {
@@ -787,6 +803,8 @@ __global__ __launch_bounds__(kGenThreads) void attn_generic_kernel(
     __syncthreads();
     float m_run = -INFINITY, l_run = 0.0f, acc = 0.0f;
     const int total = L + T;
+    const int groups = kGenThreads / D;  // key groups of the P V product (D <= 256)
+    const int gd = tid % D, gg = tid / D;
     for (int j0 = 0; j0 < total; j0 += kGenThreads) {
         const int j = j0 + tid;
         float s = -INFINITY;
@@ -800,7 +818,23 @@ __global__ __launch_bounds__(kGenThreads) void attn_generic_kernel(
         }
         if (krow) {
             float dot = 0.0f;
-            for (int c = 0; c < D; ++c) dot = fmaf(s_q[c], ld_elem(krow + c), dot);
+            // the key row in 16 elements per step (D is a multiple of 8), summed in element order
+            int c = 0;
+            for (; c + 16 <= D; c += 16) {
+                float k0[8], k1[8];
+                ld_elem8(krow + c, k0);
+                ld_elem8(krow + c + 8, k1);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) dot = fmaf(s_q[c + u], k0[u], dot);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) dot = fmaf(s_q[c + 8 + u], k1[u], dot);
+            }
+            if (c < D) {
+                float k0[8];
+                ld_elem8(krow + c, k0);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) dot = fmaf(s_q[c + u], k0[u], dot);
+            }
             s = dot * scale;
         }
         // tile max
@@ -824,21 +858,36 @@ __global__ __launch_bounds__(kGenThreads) void attn_generic_kernel(
         psum = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
         l_run = l_run * alpha + psum;
         m_run = m_new;
-        if (tid < D) {
+        if (gg < groups) {
+            // thread (gd, gg) accumulates output element gd over the keys gg, gg + groups, ...
+            // of the tile, sixteen value rows in flight at a time; a masked key has weight 0 and
+            // its row (a real tree row) is read all the same, so that no load waits for a branch
             acc *= alpha;
             const int cnt = min(kGenThreads, total - j0);
-            for (int t = 0; t < cnt; ++t) {
-                const float pt = s_p[t];
-                if (pt == 0.0f) continue;
-                const int jj = j0 + t;
-                const TIO *vrow = jj < L ? v_cache + ((size_t)(L0 + jj) * Hkv + hk) * D
-                                         : v_tree + (((size_t)seq * T + (jj - L)) * Hkv + hk) * D;
-                acc = fmaf(pt, ld_elem(vrow + tid), acc);
+            auto vrow = [&](int jj) -> const TIO * {
+                return jj < L ? v_cache + ((size_t)(L0 + jj) * Hkv + hk) * D
+                              : v_tree + (((size_t)seq * T + (jj - L)) * Hkv + hk) * D;
+            };
+            int t = gg;
+            for (; t + 15 * groups < cnt; t += 16 * groups) {
+                float vv[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) vv[u] = ld_elem(vrow(j0 + t + u * groups) + gd);
+#pragma unroll
+                for (int u = 0; u < 16; ++u) acc = fmaf(s_p[t + u * groups], vv[u], acc);
             }
+            for (; t < cnt; t += groups) acc = fmaf(s_p[t], ld_elem(vrow(j0 + t) + gd), acc);
         }
         __syncthreads();
     }
-    if (tid < D) st_elem(orow + tid, l_run > 0.0f ? acc / l_run : 0.0f);
+    // the key groups' partial sums of each output element
+    s_p[tid] = gg < groups ? acc : 0.0f;
+    __syncthreads();
+    if (tid < D) {
+        float o = 0.0f;
+        for (int g = 0; g < groups; ++g) o += s_p[g * D + tid];
+        st_elem(orow + tid, l_run > 0.0f ? o / l_run : 0.0f);
+    }
 }
 
 }  // namespace ddt
@@ -851,6 +900,10 @@ extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void
 {
     using namespace ddt;
     if (!q || !k_tree || !v_tree || !ancestor_mask || !kv_offset || !out) return DDTREE_ERR_ARG;
+    // rows are read and written 16 bytes at a time
+    for (const void *t : {q, k_cache, v_cache, k_tree, v_tree, static_cast<const void *>(out)})
+        if (reinterpret_cast<uintptr_t>(t) & 15u) return DDTREE_ERR_ARG;
+    if (reinterpret_cast<uintptr_t>(ancestor_mask) & 7u) return DDTREE_ERR_ARG;
     if (batch < 1 || batch > DDTREE_MAX_BATCH || T < 1 || T > DDTREE_MAX_N + 1 || Hq < 1 || Hkv < 1 ||
         Hq % Hkv != 0 || D < 8 || D > 256 || D % 8 != 0)
         return DDTREE_ERR_ARG;

@@ -103,12 +103,20 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     off2 = (ctypes.c_int32 * 2)(0, 8192)
     assert lib.ddtree_verify_attn(p, p, p, p, p, p, ctypes.cast(off2, ctypes.c_void_p), 1, 257, 32, 8,
                                   128, 0.088, 0, p, None, 0, None) == ERR_WS
+    # tensors of the attention are read 16 bytes at a time: a misaligned one is refused
+    odd = ctypes.c_void_p(p.value + 2)
+    assert lib.ddtree_verify_attn(odd, p, p, p, p, p, ctypes.cast(off2, ctypes.c_void_p), 1, 257, 32, 8,
+                                  128, 0.088, 0, p, None, 0, None) == ERR_ARG
+    assert lib.ddtree_verify_attn(p, p, p, p, odd, p, ctypes.cast(off2, ctypes.c_void_p), 1, 257, 32, 8,
+                                  128, 0.088, 0, p, None, 0, None) == ERR_ARG
     # accept: workspace too small, null outputs
     assert lib.ddtree_accept(p, 1, 257, 151936, p, p, p, p, p, p, p, None, 16, p, 16, None) == ERR_WS
     assert lib.ddtree_accept(p, 1, 257, 151936, p, p, p, p, None, p, p, None, 16, p, 4096, None) == ERR_ARG
     # compact: bad element size
     dst = (ctypes.c_int32 * 1)(0)
     assert lib.ddtree_compact(p, p, p, p, ctypes.cast(dst, ctypes.c_void_p), 1, 17, 8, 1, 64, 3, p, p,
+                              None) == ERR_ARG
+    assert lib.ddtree_compact(odd, p, p, p, ctypes.cast(dst, ctypes.c_void_p), 1, 17, 8, 1, 64, 2, p, p,
                               None) == ERR_ARG
     # profile hook: bad arguments
     assert lib.ddtree_profile_enable(1 << 20, 4) == ERR_ARG
