@@ -89,7 +89,8 @@ size_t ddtree_verify_attn_workspace_bytes(int batch, int T, int Hq, int Hkv, int
  * Requires 1 <= K <= min(V, DDTREE_MAX_N), 1 <= B <= DDTREE_MAX_B, and that the candidates of one
  * row fit the merge workgroup's LDS: ceil(V / 12288) * min(K, 12288) <= 14336, i.e. any K up to
  * V = 172032 (K = 1024), V <= 344064 at K = 512, V <= 688128 at K = 256.  Other shapes return
- * DDTREE_ERR_ARG (and ddtree_workspace_bytes returns 0 for them).
+ * DDTREE_ERR_ARG (and ddtree_workspace_bytes returns 0 for them).  Calls with batch * B >= 128
+ * rows scan each row with one workgroup and have no such limit.
  */
 int ddtree_topk(const float *logits, int batch, int B, int V, int K, int32_t *topk_tok,
                 float *topk_lp, void *workspace, size_t workspace_bytes, void *stream);

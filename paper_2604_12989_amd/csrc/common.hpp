@@ -32,7 +32,9 @@ struct TopkPlan {
     int kc;         // candidates kept per chunk = min(K, chunk_len)
     size_t cand_off, stat_off, bytes;
     bool ok;
+    bool row_kernel;  // many rows: one workgroup scans a whole row, no chunks and no scratch
 };
+constexpr int kTopkRowKernelMinRows = 128;
 constexpr int kTopkChunkMax = 12288;      // keys held in LDS by one chunk workgroup
 constexpr int kTopkMergeMaxCand = 14336;  // u64 candidates held in LDS by the merge workgroup
 TopkPlan topk_plan(int batch, int B, int V, int K);

@@ -25,6 +25,16 @@ TopkPlan topk_plan(int batch, int B, int V, int K)
     p.ok = false;
     if (batch < 1 || B < 1 || V < 1 || K < 1 || K > V) return p;
     long long rows = (long long)batch * B;
+    if (rows >= kTopkRowKernelMinRows) {  // one workgroup per row, no scratch
+        p.row_kernel = true;
+        p.chunks = 1;
+        p.chunk_len = V;
+        p.kc = K;
+        p.cand_off = p.stat_off = 0;
+        p.bytes = 256;
+        p.ok = true;
+        return p;
+    }
     int c_min = (V + kTopkChunkMax - 1) / kTopkChunkMax;
     int want = (int)((256 + rows - 1) / rows);
     int c_cap = V / 1024 > 0 ? V / 1024 : 1;  // keep chunks at least 1024 long
@@ -652,6 +662,264 @@ __global__ __launch_bounds__(kMergeThreads) void topk_merge_kernel(
     block_rank_emit<kMergeThreads>(s_list, K, emit);
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Row kernel: with a row for every compute unit (many sequences per call) one workgroup scans a
+// whole row, the chunk / merge pair and its scratch are not needed, and the scan is bound by HBM
+// and the fp64 exponentials instead of by the latency chain of a single chunk.
+//   pass 1  every thread streams its share of the row keeping a running maximum, the fp64 sum of
+//           exp(x - maximum) over the entries that differ from it and the count of those equal to
+//           it (a new maximum rescales sum + count); the workgroup merges these into the row
+//           maximum and the sum over everything but one instance of it.  The smallest of the
+//           maxima of groups of adjacent threads bounds the K-th largest entry from below.
+//   pass 2  the row is read again (it is still in the last-level cache), entries that reach the
+//           bound go to a list in LDS, a radix select over the list finds the K-th largest, and
+//           the K selected are ranked all-pairs.
+// A list that overflows (heavy ties, a void bound) falls back to the radix select over the row.
+// ------------------------------------------------------------------------------------------
+constexpr int kRowThreads = 1024;
+constexpr int kRowWaves = kRowThreads / 64;
+constexpr int kRowCap = 8192;  // candidates held in LDS
+constexpr int kRowBatch = 4;   // 16-byte loads in flight per thread
+constexpr size_t kRowLdsBytes = (size_t)kRowCap * 8 + (size_t)kListCap * 8 + (size_t)kHistBins * 4;
+
+template <int N>
+__device__ __forceinline__ void row_absorb(const float (&x)[N], float &tmax, double &S, int &neq,
+                                           const double *s_exp2)
+{
+    float bmax = x[0];
+#pragma unroll
+    for (int i = 1; i < N; ++i) bmax = fmaxf(bmax, x[i]);
+    if (bmax > tmax) {
+        // what was summed against the old maximum, its own instances included, moves to the new one
+        S = tmax > -INFINITY ? (S + (double)neq) * exp_nonpositive((double)tmax - (double)bmax, s_exp2) : 0.0;
+        neq = 0;
+        tmax = bmax;
+    }
+    if (tmax > -INFINITY) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const bool eq = x[i] == tmax;
+            const double e = exp_nonpositive((double)x[i] - (double)tmax, s_exp2);
+            neq += eq ? 1 : 0;
+            S += eq ? 0.0 : e;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kRowThreads) void topk_row_kernel(const float *__restrict__ logits, int V, int K,
+                                                               int32_t *__restrict__ topk_tok,
+                                                               float *__restrict__ topk_lp)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint64_t *s_list = reinterpret_cast<uint64_t *>(smem);       // [kRowCap]
+    uint64_t *s_sel = s_list + kRowCap;                          // [kListCap] >= K
+    uint32_t *s_hist = reinterpret_cast<uint32_t *>(s_sel + kListCap);  // [kHistBins]
+    __shared__ int s_wave[kRowWaves + 1];
+    __shared__ int s_misc[8];
+    __shared__ uint64_t s_thr;
+    __shared__ float s_fmax[kRowWaves];
+    __shared__ uint32_t s_bound[kRowWaves];
+    __shared__ double s_dsum[kRowWaves];
+    __shared__ double s_exp2[64];
+    __shared__ double s_exc;
+    __shared__ int s_owner, s_cnt;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const size_t row = blockIdx.x;
+    const float *p = logits + row * (size_t)V;
+    int head = (int)((4 - ((reinterpret_cast<uintptr_t>(p) >> 2) & 3)) & 3);
+    if (head > V) head = V;
+    const int nvec = (V - head) >> 2;
+    const int tail0 = head + 4 * nvec;
+    const float4 *pv = reinterpret_cast<const float4 *>(p + head);
+    const bool edge = tid < head || tid < V - tail0;  // this thread holds a head or tail element
+    if (tid < 64) s_exp2[tid] = kExp2Table[tid];
+    if (tid == 0) {
+        s_owner = kRowThreads;
+        s_cnt = 0;
+    }
+    __syncthreads();
+
+    const bool any = tid < nvec || edge;
+    const bool take_all = V <= kRowCap || nvec < kRowThreads;  // some thread may hold no element
+    int group = 64;  // lanes per group: the largest power of two with waves * (64 / group) >= K
+    while (group > 1 && kRowWaves * (64 / group) < K) group >>= 1;
+    // Lower bound on the row's K-th largest entry from what the threads have seen so far: the
+    // smallest of the maxima of groups of adjacent threads (waves * 64 / group >= K distinct
+    // entries reach it).  It only grows as the scan proceeds.
+    float tmax = -INFINITY;
+    auto bound_now = [&]() -> float {
+        const uint32_t bound = wave_min_of_group_max(any ? float_key(tmax) : 0u, group);
+        if (lane == 63) s_bound[wave] = bound;
+        __syncthreads();
+        uint32_t t = s_bound[0];
+#pragma unroll
+        for (int w = 1; w < kRowWaves; ++w) t = min(t, s_bound[w]);
+        __syncthreads();
+        return key_float(t);
+    };
+    float lo = -INFINITY;  // entries >= lo go to the list
+    auto composite = [&](float x, int i) -> uint64_t {
+        return ((uint64_t)float_key(x) << 32) | (uint64_t)(uint32_t)(~(uint32_t)i);
+    };
+    auto push = [&](bool on, float x, int i) {
+        const bool take = on && x >= lo;
+        const uint64_t bal = __ballot(take);
+        if (bal == 0) return;  // uniform over the wave
+        const int n_take = __popcll(bal);
+        int base = 0;
+        if (lane == __builtin_ctzll(bal)) base = atomicAdd(&s_cnt, n_take);
+        base = __shfl(base, __builtin_ctzll(bal), 64);
+        const int pos = base + __popcll(bal & ((1ull << lane) - 1ull));
+        if (take && pos < kRowCap) s_list[pos] = composite(x, i);
+    };
+    // the same for the sixteen entries of a batch with one list reservation per wave
+    auto push_batch = [&](const float (&x)[4 * kRowBatch], int base) {
+        int n = 0;
+#pragma unroll
+        for (int u = 0; u < kRowBatch; ++u) {
+            const bool on = base + u * kRowThreads + tid < nvec;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) n += (on && x[4 * u + e] >= lo) ? 1 : 0;
+        }
+        const int incl = wave_scan_inclusive_i32(n);
+        const int total = __builtin_amdgcn_readlane(incl, 63);
+        if (total == 0) return;  // uniform over the wave
+        int first = 0;
+        if (lane == 63) first = atomicAdd(&s_cnt, total);
+        int pos = __builtin_amdgcn_readlane(first, 63) + incl - n;
+#pragma unroll
+        for (int u = 0; u < kRowBatch; ++u) {
+            const int j = base + u * kRowThreads + tid;
+            const bool on = j < nvec;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (on && x[4 * u + e] >= lo) {
+                    if (pos < kRowCap) s_list[pos] = composite(x[4 * u + e], head + 4 * j + e);
+                    ++pos;
+                }
+        }
+    };
+    auto push_edges = [&]() {  // head and tail elements live in the first lanes of wave 0
+        if (wave == 0) {
+            push(tid < head, tid < head ? p[tid] : 0.0f, tid);
+            push(tid < V - tail0, tid < V - tail0 ? p[tail0 + tid] : 0.0f, tail0 + tid);
+        }
+    };
+
+    // ---- the scan: running maximum, sum and count per thread; entries that reach the bound of
+    //      the moment (refreshed after 1, 2 and 4 batches) are appended to the list, a superset
+    //      of what the final bound admits ----
+    double S = 0.0;
+    int neq = 0;
+    int batch_no = 0;
+    // the loads of the next batch are requested before the exponentials of this one
+    auto load_batch = [&](int base, float4 (&v)[kRowBatch]) {
+#pragma unroll
+        for (int u = 0; u < kRowBatch; ++u) {
+            const int j = base + u * kRowThreads + tid;
+            v[u] = j < nvec ? pv[j] : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+        }
+    };
+    float4 nxt[kRowBatch];
+    load_batch(0, nxt);
+    for (int base = 0; base < nvec; base += kRowBatch * kRowThreads, ++batch_no) {
+        float x[4 * kRowBatch];
+#pragma unroll
+        for (int u = 0; u < kRowBatch; ++u) {
+            x[4 * u + 0] = nxt[u].x;
+            x[4 * u + 1] = nxt[u].y;
+            x[4 * u + 2] = nxt[u].z;
+            x[4 * u + 3] = nxt[u].w;
+        }
+        load_batch(base + kRowBatch * kRowThreads, nxt);  // past the end: nothing is read
+        row_absorb(x, tmax, S, neq, s_exp2);
+        if (!take_all && (batch_no == 0 || batch_no == 1 || batch_no == 3)) lo = bound_now();
+        push_batch(x, base);
+    }
+    if (edge) {
+        const float x[2] = {tid < head ? p[tid] : -INFINITY, tid < V - tail0 ? p[tail0 + tid] : -INFINITY};
+        row_absorb(x, tmax, S, neq, s_exp2);
+    }
+    push_edges();
+
+    // ---- row maximum and the sum over everything but one instance of it ----
+    const float wmax = wave_max_f32(tmax);
+    if (lane == 63) s_fmax[wave] = wmax;
+    __syncthreads();
+    float m = s_fmax[0];
+#pragma unroll
+    for (int w = 1; w < kRowWaves; ++w) m = fmaxf(m, s_fmax[w]);
+    if (any && tmax == m) atomicMin(&s_owner, tid);  // one thread gives up one instance of the maximum
+    __syncthreads();
+    double c = 0.0;
+    if (tmax > -INFINITY)
+        c = (S + (double)(neq - (tid == s_owner ? 1 : 0))) * exp_nonpositive((double)tmax - (double)m, s_exp2);
+    c = wave_sum_f64_lane63(c);
+    if (lane == 63) s_dsum[wave] = c;
+    __syncthreads();
+    if (tid == 0) {
+        double S1 = s_dsum[0];
+        for (int w = 1; w < kRowWaves; ++w) S1 += s_dsum[w];
+        s_exc = log1p(S1);  // read by emit() after later barriers
+    }
+
+    // ---- a list that overflowed is filled again with the final bound, from the row in cache ----
+    if (s_cnt > kRowCap && !take_all) {
+        lo = bound_now();  // also orders the reads of s_cnt above before its reset
+        if (tid == 0) s_cnt = 0;
+        __syncthreads();
+        for (int base = 0; base < nvec; base += kRowBatch * kRowThreads) {
+            float4 v[kRowBatch];
+            load_batch(base, v);
+            float x[4 * kRowBatch];
+#pragma unroll
+            for (int u = 0; u < kRowBatch; ++u) {
+                x[4 * u + 0] = v[u].x;
+                x[4 * u + 1] = v[u].y;
+                x[4 * u + 2] = v[u].z;
+                x[4 * u + 3] = v[u].w;
+            }
+            push_batch(x, base);
+        }
+        push_edges();
+    }
+    if (tid == 0) s_misc[7] = 0;
+    __syncthreads();
+    const int cnt = s_cnt;  // at least K: the bound is reached by K entries, or everything was taken
+
+    // ---- the K largest of the list (or, on overflow, of the row), then their exact order ----
+    SelectScratch sc{s_hist, s_sel, s_wave, s_misc, &s_thr};
+    if (cnt <= kRowCap) {
+        auto get = [&](int i) -> uint64_t { return s_list[i]; };
+        const uint64_t thr = cnt > K ? block_select_threshold<kRowThreads>(get, cnt, K, sc) : 0ull;
+        for (int i = tid; i < cnt; i += kRowThreads) {
+            const uint64_t cc = s_list[i];
+            if (cc >= thr) {
+                const int pos = atomicAdd(&s_misc[7], 1);
+                if (pos < kListCap) s_sel[pos] = cc;  // exactly K
+            }
+        }
+    } else {
+        auto get = [&](int i) -> uint64_t { return composite(p[i], i); };
+        const uint64_t thr = block_select_threshold<kRowThreads>(get, V, K, sc);
+        for (int i = tid; i < V; i += kRowThreads) {
+            const uint64_t cc = get(i);
+            if (cc >= thr) {
+                const int pos = atomicAdd(&s_misc[7], 1);
+                if (pos < kListCap) s_sel[pos] = cc;  // exactly K
+            }
+        }
+    }
+    __syncthreads();
+    auto emit = [&](int rank, uint64_t cc) {
+        topk_tok[row * (size_t)K + rank] = (int32_t)(~(uint32_t)cc);
+        topk_lp[row * (size_t)K + rank] =
+            (float)(((double)key_float((uint32_t)(cc >> 32)) - (double)m) - s_exc);
+    };
+    block_rank_emit<kRowThreads>(s_sel, K, emit);
+}
 }  // namespace ddt
 
 extern "C" int ddtree_topk(const float *logits, int batch, int B, int V, int K, int32_t *topk_tok,
@@ -668,6 +936,19 @@ extern "C" int ddtree_topk(const float *logits, int batch, int B, int V, int K, 
     uint64_t *cand = reinterpret_cast<uint64_t *>(static_cast<char *>(workspace) + p.cand_off);
     double *stat = reinterpret_cast<double *>(static_cast<char *>(workspace) + p.stat_off);
 
+    hipStream_t st = as_stream(stream);
+    if (p.row_kernel) {
+        static bool row_attr_set = false;
+        if (!row_attr_set) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(topk_row_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRowLdsBytes) != hipSuccess)
+                return DDTREE_ERR_HIP;
+            row_attr_set = true;
+        }
+        DDT_LAUNCH(DDTREE_KERNEL_TOPK_CHUNK, st, topk_row_kernel, dim3(batch * B), dim3(kRowThreads), kRowLdsBytes,
+                   st, logits, V, K, topk_tok, topk_lp);
+        return launch_status();
+    }
     static bool attr_set = false;
     const size_t lds_chunk = (size_t)p.chunk_len * 4 + kHistBins * 4;
     const size_t lds_merge = (size_t)p.chunks * p.kc * 8 + kHistBins * 4;
@@ -679,7 +960,6 @@ extern "C" int ddtree_topk(const float *logits, int batch, int B, int V, int K, 
             return DDTREE_ERR_HIP;
         attr_set = true;
     }
-    hipStream_t st = as_stream(stream);
     DDT_LAUNCH(DDTREE_KERNEL_TOPK_CHUNK, st, topk_chunk_kernel, dim3(p.chunks, B, batch), dim3(kChunkThreads), lds_chunk, st,
                        logits, V, p.chunk_len, p.kc, p.chunks, cand, stat);
     DDT_LAUNCH(DDTREE_KERNEL_TOPK_MERGE, st, topk_merge_kernel, dim3(B, batch), dim3(kMergeThreads), lds_merge, st, cand,

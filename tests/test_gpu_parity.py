@@ -117,6 +117,36 @@ def test_topk_batched():
         assert ulp_diff(lp_g[b], lp_o).max() <= 2
 
 
+def test_topk_many_rows():
+    """128 rows or more take the one-workgroup-per-row kernel: vocabulary sizes from one element
+    to several passes per thread with ragged heads and tails, K up to 1024, row kinds that overflow
+    its candidate list (flat rows, heavy ties, masked rows) and rows with one dominant token."""
+    rng = np.random.default_rng(4242)
+    worst = 0
+    for case, (V, K) in enumerate(((1, 1), (7, 7), (1000, 16), (4097, 256), (8191, 1024), (8193, 64),
+                                   (20000, 1024), (50001, 256), (151936, 128), (151936, 1024))):
+        batch, B = (8, 16) if V < 100000 else (16, 16)
+        x = rng.standard_normal((batch, B, V)).astype(np.float32) * np.float32(3.0)
+        x[0, 0] = 1.25                                        # flat row: every entry ties
+        x[0, 1] = np.round(x[0, 1])                           # heavy ties
+        x[0, 2, rng.random(V) < 0.7] = -np.inf                # masked row
+        x[0, 2, 0] = 0.0
+        x[0, 3, rng.integers(0, V)] += np.float32(40.0)       # nearly certain token
+        x[0, 4] = -np.arange(V, dtype=np.float32) * np.float32(1e-3)   # strictly decreasing
+        x[0, 5] = np.arange(V, dtype=np.float32) * np.float32(1e-3)    # strictly increasing
+        tok_g, lp_g = gu.gpu_topk(x, K)
+        for b in range(batch):
+            tok_o, lp_o = oracle.topk(x[b], K)
+            assert np.array_equal(tok_g[b], tok_o), (V, K, b)
+            fin = np.isfinite(lp_o)
+            assert np.array_equal(np.isfinite(lp_g[b]), fin), (V, K, b)
+            if fin.any():
+                u = int(ulp_diff(lp_g[b][fin], lp_o[fin]).max())
+                worst = max(worst, u)
+                assert u <= 2, (V, K, b, u)
+    print(f"worst log-probability difference {worst} ulp")
+
+
 def test_topk_nearly_certain_rows():
     """One token holds all but 1e-5 .. 1e-11 of the probability: its log-probability is a tiny
     negative number that only survives when the log-sum-exp is formed as max + log1p(rest)."""
