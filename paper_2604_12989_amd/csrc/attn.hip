@@ -25,6 +25,8 @@
 // reads and the transposing V reads are free of bank conflicts.
 // The ancestor mask touches only the tree tiles (the last ceil(T/64) tiles): one 64-bit word per
 // (row, tile), bit test per score.  Cache tiles carry no mask work at all.
+#include <algorithm>
+
 #include "common.hpp"
 
 namespace ddt {
@@ -59,6 +61,10 @@ constexpr int kAttnLdsBytes = kAttnStages * kStageBytes;
 
 struct AttnArgs {
     int32_t kv_offset[DDTREE_MAX_BATCH + 1];
+    // matrix-core kernel only: the sequences longest cache first, and the first work item of
+    // each of the 8 XCDs' runs (run x = work items xcd_start[x] .. xcd_start[x + 1] - 1)
+    uint8_t order[DDTREE_MAX_BATCH];
+    int32_t xcd_start[9];
 };
 
 AttnPlan attn_plan(int batch, int T, int Hq, int Hkv, int D, long long sum_L, int dtype)
@@ -262,17 +268,18 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
     // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  The grid is read as
-    // 8 runs of per_xcd consecutive work items, run x being what XCD x executes, and consecutive
+    // 8 runs of consecutive work items, run x being what XCD x executes, and consecutive
     // work items are the row tiles of one (group, key range): the row tiles that read the same K
-    // and V rows share an L2, and those rows leave HBM once.
+    // and V rows share an L2, and those rows leave HBM once.  The host cuts the runs so that
+    // each holds an eighth of the keys to visit (sequences of a ragged batch differ in length)
+    // and lists the sequences longest first, so that an XCD's long work items start early.
     // The work items of a group are its main tiles, row tile fastest within a key range, then (in
     // the uneven form) the key ranges of its tail tile.
     const int main_tiles = tail_splits > 0 ? n_tiles_m - 1 : n_tiles_m;
     const int per_grp = main_tiles * main_splits + tail_splits;
-    const int total = Hkv * batch_n * per_grp;
-    const int per_xcd = (total + 7) >> 3;
-    const int wid = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
-    if (wid >= total) return;
+    const int xcd = (int)blockIdx.x & 7;
+    const int wid = args.xcd_start[xcd] + ((int)blockIdx.x >> 3);
+    if (wid >= args.xcd_start[xcd + 1]) return;
     const int grp = wid / per_grp;                        // (sequence, kv head) pair
     const int wg = wid - grp * per_grp;
     const bool tail = wg >= main_tiles * main_splits;
@@ -280,7 +287,7 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     const int split = tail ? wg - main_tiles * main_splits : wg / main_tiles;
     const int splits = tail ? tail_splits : main_splits;  // key ranges of this tile
     const int hk = grp % Hkv;
-    const int seq = grp / Hkv;
+    const int seq = args.order[grp / Hkv];
     const int G = Hq / Hkv;
     const int W = (T + 63) >> 6;
     const int M = T * G;
@@ -933,7 +940,46 @@ extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void
             attr_set = true;
         }
         const int main_tiles = p.tail_splits > 0 ? p.n_tiles - 1 : p.n_tiles;
-        const long long gx = ((long long)batch * Hkv * (main_tiles * p.splits + p.tail_splits) + 7) / 8 * 8;
+        // Work items in launch order: sequences longest first, then kv head, then the items of
+        // the group.  An item visits about (L + T) / splits keys; the 8 runs are cut where the
+        // running sum of that passes each eighth of the total.
+        const long long per_seq = (long long)Hkv * (main_tiles * p.splits + p.tail_splits);
+        const long long total = per_seq * batch;
+        if (total > (1ll << 28)) return DDTREE_ERR_ARG;
+        for (int i = 0; i < batch; ++i) args.order[i] = (uint8_t)i;
+        std::stable_sort(args.order, args.order + batch, [&](uint8_t a, uint8_t b) {
+            return kv_offset[a + 1] - kv_offset[a] > kv_offset[b + 1] - kv_offset[b];
+        });
+        long long work_total = 0;
+        for (int i = 0; i < batch; ++i) work_total += per_seq * ((long long)kv_offset[i + 1] - kv_offset[i] + T);
+        {
+            long long done = 0, first = 0;  // work and items before sequence position `pos`
+            int pos = 0, x = 1;
+            args.xcd_start[0] = 0;
+            while (x < 8) {
+                const long long target = (work_total * x + 7) / 8;
+                const int sq = args.order[pos];
+                const long long w = (long long)kv_offset[sq + 1] - kv_offset[sq] + T;
+                if (pos < batch - 1 && done + per_seq * w < target) {
+                    done += per_seq * w;
+                    first += per_seq;
+                    ++pos;
+                    continue;
+                }
+                long long k = (target - done + w - 1) / w;  // items of this sequence before the cut
+                if (k < 0) k = 0;
+                if (k > per_seq) k = per_seq;
+                args.xcd_start[x++] = (int32_t)(first + k);
+            }
+            args.xcd_start[8] = (int32_t)total;
+        }
+        long long run_max = 0;
+        for (int x = 0; x < 8; ++x) {
+            if (args.xcd_start[x + 1] < args.xcd_start[x]) args.xcd_start[x + 1] = args.xcd_start[x];
+            const long long run = args.xcd_start[x + 1] - args.xcd_start[x];
+            if (run > run_max) run_max = run;
+        }
+        const long long gx = run_max * 8;
         const int part_splits = (p.part_splits > 1 || p.tail_splits > 0) ? p.part_splits : 0;
         DDT_LAUNCH(DDTREE_KERNEL_ATTN, st, attn_mfma_kernel, dim3((unsigned)gx), dim3(kAttnThreads),
                    kAttnLdsBytes, st, static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(k_cache),
