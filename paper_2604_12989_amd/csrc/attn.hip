@@ -105,7 +105,7 @@ AttnPlan attn_plan(int batch, int T, int Hq, int Hkv, int D, long long sum_L, in
     const int full = nblk / 8, rem = nblk % 8;
     if (full >= 1 && rem >= 1 && rem <= 4 && tiles >= 1) {
         const double c_tail = 0.5;
-        best_cost *= 0.97;  // (the uneven form always goes through partials: it has to pay for them)
+        best_cost *= 0.97;  // (with key ranges the uneven form goes through partials: it has to pay for them)
         const long long base_m = (long long)batch * Hkv * full, base_t = (long long)batch * Hkv;
         for (int Sm = 1; Sm <= 32; ++Sm) {
             if (Sm > 1 && (long long)Sm * 4 > tiles) break;
@@ -128,7 +128,7 @@ AttnPlan attn_plan(int batch, int T, int Hq, int Hkv, int D, long long sum_L, in
         }
     }
     size_t off = 0;
-    if (p.part_splits > 1 || p.tail_splits > 0) {
+    if (p.part_splits > 1) {
         const size_t rows = (size_t)batch * T * Hq;  // indexed by global row
         p.part_off = off;
         off = align_up(off + (size_t)p.part_splits * rows * D * 2, 256);  // fp16 partials
@@ -980,7 +980,7 @@ extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void
             if (run > run_max) run_max = run;
         }
         const long long gx = run_max * 8;
-        const int part_splits = (p.part_splits > 1 || p.tail_splits > 0) ? p.part_splits : 0;
+        const int part_splits = p.part_splits > 1 ? p.part_splits : 0;
         DDT_LAUNCH(DDTREE_KERNEL_ATTN, st, attn_mfma_kernel, dim3((unsigned)gx), dim3(kAttnThreads),
                    kAttnLdsBytes, st, static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(k_cache),
                    static_cast<const uint16_t *>(v_cache), static_cast<const uint16_t *>(k_tree),
