@@ -508,17 +508,33 @@ __global__ __launch_bounds__(kBuildThreads) void build_kernel(
     const float *lp = topk_lp + (size_t)seq * B * K;
     const int32_t *tk = topk_tok + (size_t)seq * B * K;
 
-    // log-probabilities into LDS, rows padded with -inf; four rows' loads in flight together
-    for (int d0 = 0; d0 < B; d0 += 4)
-        for (int k0 = 0; k0 < Kp; k0 += kBuildThreads) {
-            const int k = k0 + tid;
-            float v[4];
+    // log-probabilities into LDS, rows padded with -inf.  The [B][K] table is contiguous: thread
+    // t takes elements t, t + 256, ..., sixteen loads in flight at a time (one round trip to
+    // memory at B = 16, K = 256), and keeps (row, column) of its element by stepping both.
+    {
+        const int n_el = B * K;
+        const int dq = kBuildThreads / K, dr = kBuildThreads % K;  // one step of 256 elements
+        int d = tid / K, k = tid % K;
+        for (int e0 = tid; e0 < n_el; e0 += 16 * kBuildThreads) {
+            float v[16];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) v[r] = (d0 + r < B && k < K) ? lp[(d0 + r) * K + k] : -INFINITY;
+            for (int u = 0; u < 16; ++u) {
+                const int e = e0 + u * kBuildThreads;
+                v[u] = e < n_el ? lp[e] : 0.0f;
+            }
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (d0 + r < B && k < Kp) s_lp[(d0 + r) * Kp + k] = v[r];
+            for (int u = 0; u < 16; ++u) {
+                if (e0 + u * kBuildThreads < n_el) s_lp[d * Kp + k] = v[u];
+                d += dq;
+                k += dr;
+                if (k >= K) {
+                    k -= K;
+                    ++d;
+                }
+            }
         }
+        for (int i = tid; i < 3 * B; i += kBuildThreads) s_lp[(i / 3) * Kp + K + i % 3] = -INFINITY;
+    }
     if (tid == 0) {
         s_node[0] = pack_node(0, 0, 0);
         s_score[0] = 0.0f;
