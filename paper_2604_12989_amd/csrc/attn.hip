@@ -932,13 +932,9 @@ extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void
         char *wsb = static_cast<char *>(workspace);
         uint16_t *part = reinterpret_cast<uint16_t *>(wsb + p.part_off);
         float *lse = reinterpret_cast<float *>(wsb + p.lse_off);
-        static bool attr_set = false;
-        if (!attr_set) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(attn_mfma_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsBytes) != hipSuccess)
-                return DDTREE_ERR_HIP;
-            attr_set = true;
-        }
+        static std::atomic<bool> lds_allowed{false};
+        if (!allow_dynamic_lds(reinterpret_cast<const void *>(attn_mfma_kernel), kAttnLdsBytes, lds_allowed))
+            return DDTREE_ERR_HIP;
         const int main_tiles = p.tail_splits > 0 ? p.n_tiles - 1 : p.n_tiles;
         // Work items in launch order: sequences longest first, then kv head, then the items of
         // the group.  An item visits about (L + T) / splits keys; the 8 runs are cut where the

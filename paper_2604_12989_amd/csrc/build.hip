@@ -828,13 +828,9 @@ static int launch_build(const int32_t *topk_tok, const float *topk_lp, int batch
 {
     const int algo = g_build_algo.load();
     const BuildLds lds = build_lds_plan(B, K, N, algo != DDTREE_BUILD_POPS);
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(build_kernel<NSLOT>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024) != hipSuccess)
-            return DDTREE_ERR_HIP;
-        attr_set = true;
-    }
+    static std::atomic<bool> lds_allowed{false};
+    if (!allow_dynamic_lds(reinterpret_cast<const void *>(build_kernel<NSLOT>), 150 * 1024, lds_allowed))
+        return DDTREE_ERR_HIP;
     DDT_LAUNCH(DDTREE_KERNEL_BUILD, st, build_kernel<NSLOT>, dim3(batch), dim3(kBuildThreads), lds.bytes,
                        st, topk_tok, topk_lp, B, K, N, root_token, tokens, parent, depth, rank,
                        node_score, ancestor_mask, n_nodes, algo, lds.capm, lds.capp, lds.capc);

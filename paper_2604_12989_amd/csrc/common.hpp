@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "ddtree.h"
 
 namespace ddt {
@@ -20,6 +22,16 @@ inline int launch_status()
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Raises a kernel's dynamic-LDS limit, once per process.  The call is idempotent, so two host
+// threads that race here simply both make it.  False if the runtime refuses.
+inline bool allow_dynamic_lds(const void *kernel, size_t bytes, std::atomic<bool> &done)
+{
+    if (done.load(std::memory_order_acquire)) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
+        return false;
+    done.store(true, std::memory_order_release);
+    return true;
+}
 inline bool ws_ok(const void *ws, size_t have, size_t need)
 {
     return need == 0 || (ws != nullptr && (reinterpret_cast<uintptr_t>(ws) & 255u) == 0 && have >= need);

@@ -938,28 +938,21 @@ extern "C" int ddtree_topk(const float *logits, int batch, int B, int V, int K, 
 
     hipStream_t st = as_stream(stream);
     if (p.row_kernel) {
-        static bool row_attr_set = false;
-        if (!row_attr_set) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(topk_row_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRowLdsBytes) != hipSuccess)
-                return DDTREE_ERR_HIP;
-            row_attr_set = true;
-        }
+        static std::atomic<bool> row_lds_allowed{false};
+        if (!allow_dynamic_lds(reinterpret_cast<const void *>(topk_row_kernel), kRowLdsBytes, row_lds_allowed))
+            return DDTREE_ERR_HIP;
         DDT_LAUNCH(DDTREE_KERNEL_TOPK_CHUNK, st, topk_row_kernel, dim3(batch * B), dim3(kRowThreads), kRowLdsBytes,
                    st, logits, V, K, topk_tok, topk_lp);
         return launch_status();
     }
-    static bool attr_set = false;
+    static std::atomic<bool> chunk_lds_allowed{false}, merge_lds_allowed{false};
     const size_t lds_chunk = (size_t)p.chunk_len * 4 + kHistBins * 4;
     const size_t lds_merge = (size_t)p.chunks * p.kc * 8 + kHistBins * 4;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(topk_chunk_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kTopkChunkMax * 4 + kHistBins * 4) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void *>(topk_merge_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kTopkMergeMaxCand * 8 + kHistBins * 4) != hipSuccess)
-            return DDTREE_ERR_HIP;
-        attr_set = true;
-    }
+    if (!allow_dynamic_lds(reinterpret_cast<const void *>(topk_chunk_kernel), kTopkChunkMax * 4 + kHistBins * 4,
+                           chunk_lds_allowed) ||
+        !allow_dynamic_lds(reinterpret_cast<const void *>(topk_merge_kernel), kTopkMergeMaxCand * 8 + kHistBins * 4,
+                           merge_lds_allowed))
+        return DDTREE_ERR_HIP;
     DDT_LAUNCH(DDTREE_KERNEL_TOPK_CHUNK, st, topk_chunk_kernel, dim3(p.chunks, B, batch), dim3(kChunkThreads), lds_chunk, st,
                        logits, V, p.chunk_len, p.kc, p.chunks, cand, stat);
     DDT_LAUNCH(DDTREE_KERNEL_TOPK_MERGE, st, topk_merge_kernel, dim3(B, batch), dim3(kMergeThreads), lds_merge, st, cand,
