@@ -690,11 +690,11 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 // Merge of the split-KV partials: out = sum_s 2^(lse_s - max) O_s / sum_s 2^(lse_s - max).
 // Partials are normalised per split and stored as fp16 (outputs are averages of V entries, far
 // inside the fp16 range for any KV cache a bf16 model produces; eps 2^-11 is below the bf16
-// rounding of the result).  One thread per (row, 8 dims); the loads of 8 splits are in flight
-// together.
+// rounding of the result).  One thread per (row, 8 dims); the loads of kMergeBatch splits are in
+// flight together: 8 for up to 8 key ranges, 16 beyond (small budgets on long caches).
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-constexpr int kMergeBatch = 8;
 
+template <int kMergeBatch>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const uint16_t *__restrict__ part_all,
                                                          const float *__restrict__ lse_all, size_t n_rows,
                                                          int splits, uint16_t *__restrict__ out)
@@ -707,36 +707,39 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const uint16_t *__restr
     const float *lse = lse_all + row;
     const size_t pstride = n_rows * kHD;
 
+    // one pass: the weights are taken against the largest lse seen so far and what has been
+    // summed is rescaled when a batch brings a larger one
     float mx = -INFINITY;
-    for (int s0 = 0; s0 < splits; s0 += kMergeBatch) {
-        float l[kMergeBatch];
-#pragma unroll
-        for (int j = 0; j < kMergeBatch; ++j) l[j] = s0 + j < splits ? lse[(size_t)(s0 + j) * n_rows] : -INFINITY;
-#pragma unroll
-        for (int j = 0; j < kMergeBatch; ++j) mx = fmaxf(mx, l[j]);
-    }
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     float wsum = 0.0f;
-    if (mx > -INFINITY) {
-        for (int s0 = 0; s0 < splits; s0 += kMergeBatch) {
-            f16x8 v[kMergeBatch];
-            float l[kMergeBatch];
+    for (int s0 = 0; s0 < splits; s0 += kMergeBatch) {
+        f16x8 v[kMergeBatch];
+        float l[kMergeBatch];
 #pragma unroll
-            for (int j = 0; j < kMergeBatch; ++j) {
-                const bool on = s0 + j < splits;
-                l[j] = on ? lse[(size_t)(s0 + j) * n_rows] : -INFINITY;
-                v[j] = on ? *reinterpret_cast<const f16x8 *>(part + (size_t)(s0 + j) * pstride) : f16x8(0);
-            }
+        for (int j = 0; j < kMergeBatch; ++j) {
+            const bool on = s0 + j < splits;
+            l[j] = on ? lse[(size_t)(s0 + j) * n_rows] : -INFINITY;
+            v[j] = on ? *reinterpret_cast<const f16x8 *>(part + (size_t)(s0 + j) * pstride) : f16x8(0);
+        }
+        float bm = l[0];
 #pragma unroll
-            for (int j = 0; j < kMergeBatch; ++j) {
-                // an empty key range (lse = -inf) has no partial behind it: whatever bits were
-                // read there must not reach the sum, not even times zero
-                const bool live = l[j] > -INFINITY;
-                const float w = live ? __builtin_amdgcn_exp2f(l[j] - mx) : 0.0f;
+        for (int j = 1; j < kMergeBatch; ++j) bm = fmaxf(bm, l[j]);
+        if (bm > mx) {
+            const float r = mx > -INFINITY ? __builtin_amdgcn_exp2f(mx - bm) : 0.0f;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc[e] += live ? w * (float)v[j][e] : 0.0f;
-                wsum += w;
-            }
+            for (int e = 0; e < 8; ++e) acc[e] *= r;
+            wsum *= r;
+            mx = bm;
+        }
+#pragma unroll
+        for (int j = 0; j < kMergeBatch; ++j) {
+            // an empty key range (lse = -inf) has no partial behind it: whatever bits were
+            // read there must not reach the sum, not even times zero
+            const bool live = l[j] > -INFINITY;
+            const float w = live ? __builtin_amdgcn_exp2f(l[j] - mx) : 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += live ? w * (float)v[j][e] : 0.0f;
+            wsum += w;
         }
     }
     const float inv = wsum > 0.0f ? 1.0f / wsum : 0.0f;
@@ -985,9 +988,14 @@ extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void
                    static_cast<uint16_t *>(out), part, lse);
         if (part_splits > 0) {
             const size_t n_rows = (size_t)batch * T * Hq;
-            DDT_LAUNCH(DDTREE_KERNEL_ATTN_MERGE, st, attn_merge_kernel,
-                       dim3((unsigned)((n_rows * 16 + 255) / 256)), dim3(256), 0, st, part, lse, n_rows,
-                       part_splits, static_cast<uint16_t *>(out));
+            if (part_splits <= 8)
+                DDT_LAUNCH(DDTREE_KERNEL_ATTN_MERGE, st, attn_merge_kernel<8>,
+                           dim3((unsigned)((n_rows * 16 + 255) / 256)), dim3(256), 0, st, part, lse, n_rows,
+                           part_splits, static_cast<uint16_t *>(out));
+            else
+                DDT_LAUNCH(DDTREE_KERNEL_ATTN_MERGE, st, attn_merge_kernel<16>,
+                           dim3((unsigned)((n_rows * 16 + 255) / 256)), dim3(256), 0, st, part, lse, n_rows,
+                           part_splits, static_cast<uint16_t *>(out));
         }
         return launch_status();
     }
