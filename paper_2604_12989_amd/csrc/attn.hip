@@ -628,6 +628,7 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         }
         // Retry (rare): some row outgrew its reference.  All tiles have been seen, so m_seen holds
         // the true row maxima; with those as references the second pass cannot outgrow anything.
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): no LDS read of this wave is still in flight
         if (!__syncthreads_or(overflow ? 1 : 0)) break;
         overflow = false;
 #pragma unroll
@@ -643,46 +644,55 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 
     if (!wave_active) return;
     // ---- epilogue ----
+    // A lane holds, of its row, sixteen groups of four output elements 8 bytes wide: stored from
+    // there a row would leave in 32 pieces.  The block is staged row-major in this wave's share
+    // of the ring (idle now: every wave has passed the barrier above with its tiles consumed, and
+    // no DMA is in flight) and leaves in whole rows, 16 bytes per lane and four rows per store.
+    static_assert(kCB == 1, "the staged epilogue handles one block per wave");
+    constexpr int kEpiRow = kHD * 2 + 16;  // bytes per staged row: 16-byte aligned, rows 4 banks apart
+    static_assert(kWaves * 32 * kEpiRow <= kAttnLdsBytes, "staging fits the ring");
+    unsigned char *stg = smem + wave * (32 * kEpiRow);
+    const size_t n_rows = (size_t)batch_n * T * Hq;
+    {
+        const float l_tot = l_run[0] + __shfl_xor(l_run[0], 32, 64);
+        const float inv = (rvalid[0] && real_[0] && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
 #pragma unroll
-    for (int cb = 0; cb < kCB; ++cb) {
-        const float l_tot = l_run[cb] + __shfl_xor(l_run[cb], 32, 64);
-        if (!rvalid[cb]) continue;
-        const bool real = real_[cb];
-        const float inv = (real && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
-        if (part_splits == 0) {
-            uint16_t *dst = out + (size_t)rowg_[cb] * kHD;
+        for (int db = 0; db < 4; ++db)
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
-#pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4) {
-                    const int dim = db * 32 + g4 * 8 + half * 4;
-                    uint2 val;
-                    val.x = f2bf_pair(o[db][cb][4 * g4 + 0] * inv, o[db][cb][4 * g4 + 1] * inv);
-                    val.y = f2bf_pair(o[db][cb][4 * g4 + 2] * inv, o[db][cb][4 * g4 + 3] * inv);
-                    *reinterpret_cast<uint2 *>(dst + dim) = val;
-                }
-        } else {
-            // partial result of this split, indexed by global row: normalised O and log2-sum-exp
-            const size_t n_rows = (size_t)batch_n * T * Hq;
-            const size_t ridx = (size_t)rowg_[cb];
-            uint16_t *dst = part + ((size_t)split * n_rows + ridx) * kHD;
-#pragma unroll
-            for (int db = 0; db < 4; ++db)
-#pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4) {
-                    const int dim = db * 32 + g4 * 8 + half * 4;
-                    uint2 val;
-                    val.x = f2h_pair(o[db][cb][4 * g4 + 0] * inv, o[db][cb][4 * g4 + 1] * inv);
-                    val.y = f2h_pair(o[db][cb][4 * g4 + 2] * inv, o[db][cb][4 * g4 + 3] * inv);
-                    *reinterpret_cast<uint2 *>(dst + dim) = val;
-                }
-            if (half == 0) {
-                lse[(size_t)split * n_rows + ridx] =
-                    inv > 0.0f ? m_run[cb] + __builtin_amdgcn_logf(l_tot) : -INFINITY;
-                // key ranges this tile does not have (the other kind of tile has more): empty
-                if (split == 0)
-                    for (int sx = splits; sx < part_splits; ++sx) lse[(size_t)sx * n_rows + ridx] = -INFINITY;
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int dim = db * 32 + g4 * 8 + half * 4;
+                const float a0 = o[db][0][4 * g4 + 0] * inv, a1 = o[db][0][4 * g4 + 1] * inv;
+                const float a2 = o[db][0][4 * g4 + 2] * inv, a3 = o[db][0][4 * g4 + 3] * inv;
+                uint2 val;  // bf16 for the output itself, fp16 for the partial of a key range
+                val.x = part_splits == 0 ? f2bf_pair(a0, a1) : f2h_pair(a0, a1);
+                val.y = part_splits == 0 ? f2bf_pair(a2, a3) : f2h_pair(a2, a3);
+                *reinterpret_cast<uint2 *>(stg + l32 * kEpiRow + dim * 2) = val;
             }
+        if (part_splits != 0 && rvalid[0] && half == 0) {
+            // log2-sum-exp of this key range, indexed by global row
+            const size_t ridx = (size_t)rowg_[0];
+            lse[(size_t)split * n_rows + ridx] = inv > 0.0f ? m_run[0] + __builtin_amdgcn_logf(l_tot) : -INFINITY;
+            // key ranges this tile does not have (the other kind of tile has more): empty
+            if (split == 0)
+                for (int sx = splits; sx < part_splits; ++sx) lse[(size_t)sx * n_rows + ridx] = -INFINITY;
+        }
+    }
+    uint16_t *dst_base = part_splits == 0 ? out : part + (size_t)split * n_rows * kHD;
+    const int chunk = lane & 15;
+    int r = m0 + wave * 32 + (lane >> 4);  // rows lane >> 4, + 4, + 8, ... of the block
+    int node = r / G, g = r - node * G;
+#pragma unroll
+    for (int rr = 0; rr < 8; ++rr) {
+        if (r < m_end) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(stg + (rr * 4 + (lane >> 4)) * kEpiRow + chunk * 16);
+            const size_t rg = (size_t)(seq * T + node) * Hq + hk * G + g;
+            *reinterpret_cast<uint4 *>(dst_base + rg * kHD + chunk * 8) = v;
+        }
+        r += 4;
+        g += 4;
+        while (g >= G) {
+            g -= G;
+            ++node;
         }
     }
 }
