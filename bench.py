@@ -161,8 +161,8 @@ def main():
     for i in range(args.warmup):
         run_step(i)
     torch.cuda.synchronize()
-    # the main kernel is timed live with HIP events on its stream, one launch in `every`: an event
-    # pair costs the stream about a microsecond or two, and the step time is the headline number
+    # the main kernel is timed live with HIP events that take the time stamps of its own dispatch
+    # (ddtree_profile_enable_every), one launch in `every` of the timed loop
     every = max(1, min(8, args.steps // 32))
     dd.profile_enable([main_kernel], args.steps // every + 1, every)
     torch.cuda.synchronize()

@@ -224,12 +224,12 @@ int ddtree_build_giveups(unsigned int *count);
 
 /*
  * Kernel timing hook for benchmarks (no passage of the paper: measurement only).  While a
- * kernel's bit is set in kernel_mask, every launch of that kernel is bracketed by a pair of HIP
- * events recorded on the launch stream, up to `capacity` launches per kernel; the events are
- * created here, never inside the hot calls.  kernel_mask = 0 switches the hook off and destroys
+ * kernel's bit is set in kernel_mask, every launch of that kernel carries a pair of HIP events
+ * that take the begin and end time stamps of the dispatch itself (no marker packets on the
+ * stream), up to `capacity` launches per kernel; the events are created here, never inside the
+ * hot calls.  kernel_mask = 0 switches the hook off and destroys
  * the events.  ddtree_profile_enable_every times one launch in `every` (the first, the
- * (every+1)-th, ...): a recorded event pair costs the stream about a microsecond, which a timed
- * loop may not want to pay on every launch.  ddtree_profile_read copies the elapsed milliseconds of the recorded launches of
+ * (every+1)-th, ...), for timed loops that want to be disturbed as little as possible.  ddtree_profile_read copies the elapsed milliseconds of the recorded launches of
  * one kernel to host memory and returns how many there were (or a negative error); the caller
  * must have synchronised the stream(s) first.  ddtree_profile_reset forgets recorded launches.
  * Not thread-safe; meant for a single benchmarking thread.

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -86,28 +87,25 @@ struct Profiler {
     hipEvent_t *stop[DDTREE_KERNEL_COUNT] = {};
 };
 Profiler &profiler();
-// Records the start event if launches of kernel `id` are being timed; returns the slot or -1.
-inline int profile_begin(int id, hipStream_t st)
+// The slot that times this launch of kernel `id`, or -1 if the launch is not timed.
+inline int profile_slot(int id)
 {
     Profiler &p = profiler();
     if (!(p.mask & (1u << id)) || p.count[id] >= p.capacity) return -1;
     if (p.seen[id]++ % p.every != 0) return -1;
-    const int slot = p.count[id];
-    (void)hipEventRecord(p.start[id][slot], st);
-    return slot;
+    return p.count[id]++;
 }
-inline void profile_end(int id, int slot, hipStream_t st)
-{
-    if (slot < 0) return;
-    Profiler &p = profiler();
-    (void)hipEventRecord(p.stop[id][slot], st);
-    p.count[id] = slot + 1;
-}
-#define DDT_LAUNCH(id, st, ...)                        \
-    do {                                               \
-        const int _slot = ::ddt::profile_begin(id, st); \
-        hipLaunchKernelGGL(__VA_ARGS__);               \
-        ::ddt::profile_end(id, _slot, st);             \
+// A timed launch hands its two events to the launch itself: they take the begin and end time
+// stamps of the dispatch, with no marker packets of their own on the stream (a pair of recorded
+// events reads about 5 us with nothing between them, and delays the kernels around it).
+#define DDT_LAUNCH(id, st, kernel, grid, block, lds, stream, ...)                                    \
+    do {                                                                                             \
+        const int _slot = ::ddt::profile_slot(id);                                                   \
+        if (_slot < 0)                                                                               \
+            hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                       \
+        else                                                                                         \
+            hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, ::ddt::profiler().start[id][_slot], \
+                                  ::ddt::profiler().stop[id][_slot], 0, __VA_ARGS__);                 \
     } while (0)
 
 #if defined(__HIPCC__)
