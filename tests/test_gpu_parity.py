@@ -363,6 +363,58 @@ def test_attn_bf16_mfma_matches_oracle(T, L, Hq, Hkv, seed):
     assert err < 1e-2
 
 
+def test_attn_largest_tree():
+    """T = DDTREE_MAX_N + 1 = 1025 rows (17 mask words per row), checked on sampled (node, head)
+    pairs that include the last node and rows of every mask word."""
+    T, L, Hq, Hkv, D = 1025, 1500, 8, 2, 128
+    q, kc, vc, kt, vt, mask = _attn_case(77, T, L, Hq, Hkv, D, "bf16")
+    got = gu.gpu_attn(q, kc, vc, kt, vt, mask[None], [0, L], 1, T, "bf16")[0]
+    rng = np.random.default_rng(77)
+    nodes = np.concatenate([[0, 1, 63, 64, 65, 1023, 1024], rng.integers(0, T, 57)])
+    pairs = np.stack([nodes, rng.integers(0, Hq, nodes.size)], axis=1).astype(np.int32)
+    ref = oracle.verify_attn(q, kc, vc, kt, vt, mask, pairs=pairs)
+    assert attn_err(got[pairs[:, 0], pairs[:, 1]], ref) < 1e-2
+
+
+def test_largest_batch_through_every_stage():
+    """DDTREE_MAX_BATCH = 64 sequences in one call of each stage (ragged caches, the last empty)."""
+    batch, B, V, N, Hq, Hkv, D = 64, 4, 3000, 20, 4, 2, 128
+    K, T = N, N + 1
+    rng = np.random.default_rng(64)
+    xs = np.stack([_peaked_logits(640 + s, B, V, 6.0) for s in range(batch)])
+    tok_g, lp_g = gu.gpu_topk(xs, K)
+    roots = np.arange(batch, dtype=np.int32)
+    tree_g = gu.gpu_build(tok_g, lp_g, N, roots)
+    Ls = rng.integers(0, 300, batch)
+    Ls[-1] = 0
+    off = np.concatenate([[0], np.cumsum(Ls)]).astype(np.int32)
+    q, _, _, kt, vt = di.attn_tensors(64, batch * T, 0, Hq, Hkv, D, "bf16")
+    _, kc, vc, _, _ = di.attn_tensors(65, 1, int(off[-1]), Hq, Hkv, D, "bf16")
+    trees, tls = [], []
+    for s in range(batch):
+        tok_o, lp_o = oracle.topk(xs[s], K)
+        assert np.array_equal(tok_g[s], tok_o), s
+        assert ulp_diff(lp_g[s], lp_o).max() <= 2
+        t = oracle.build_tree(tok_o, lp_g[s], N, root_token=int(roots[s]))
+        for key in ("tokens", "parent", "depth"):
+            assert np.array_equal(tree_g[key][s], t[key]), (s, key)
+        assert np.array_equal(tree_g["ancestor_mask"][s], oracle.ancestor_mask(t["parent"], t["n_nodes"], T=T)), s
+        trees.append(t)
+        plant = di.planted_tokens(700 + s, t["depth"], tok_o[:, 0], B, p=0.9, batch_index=s)
+        tls.append(di.target_logits(700 + s, T, V, plant, batch_index=s))
+    got = gu.gpu_attn(q, kc, vc, kt, vt, tree_g["ancestor_mask"], off, batch, T, "bf16")
+    for s in (0, 1, 31, 62, 63):
+        ref = oracle.verify_attn(q[s * T:(s + 1) * T], kc[off[s]:off[s + 1]], vc[off[s]:off[s + 1]],
+                                 kt[s * T:(s + 1) * T], vt[s * T:(s + 1) * T], tree_g["ancestor_mask"][s])
+        assert attn_err(got[s], ref) < 1e-2, s
+    acc = gu.gpu_accept(np.stack(tls), tree_g["tokens"], tree_g["parent"], tree_g["depth"],
+                        tree_g["n_nodes"], B)
+    for s in range(batch):
+        o = oracle.accept(tls[s], trees[s]["tokens"], trees[s]["parent"], trees[s]["n_nodes"], B)
+        assert np.array_equal(acc["path"][s], o["path"]), s
+        assert int(acc["n_accepted"][s]) == o["n_accepted"] and int(acc["bonus_token"][s]) == o["bonus"], s
+
+
 def test_attn_fp32_config1():
     c = di.CONFIGS[1]
     T = c["N"] + 1
