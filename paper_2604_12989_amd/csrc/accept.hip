@@ -21,7 +21,7 @@ AcceptPlan accept_plan(int batch, int T, int V)
 {
     AcceptPlan p{};
     long long rows = (long long)batch * T;
-    int S = (int)((1024 + rows - 1) / rows);
+    int S = (int)((3072 + rows - 1) / rows);  // about 3000 workgroups stream closest to the HBM rate
     int s_cap = V / 8192 > 0 ? V / 8192 : 1;  // keep segments at least 8192 long
     if (S > s_cap) S = s_cap;
     if (S < 1) S = 1;
@@ -219,14 +219,21 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(
     for (int i = tid; i < T; i += kWalkThreads) {
         int post = -1;
         if (i <= n) {
+            // the row's segments, eight partial results in flight at a time
             const ArgPart *pp = part + (base + i) * splits;
-            float bv = pp[0].val;
-            post = pp[0].idx;
-            for (int s = 1; s < splits; ++s)
-                if (pp[s].val > bv) {  // later segments hold higher ids: strict > keeps the first
-                    bv = pp[s].val;
-                    post = pp[s].idx;
-                }
+            float bv = -INFINITY;
+            for (int s0 = 0; s0 < splits; s0 += 8) {
+                ArgPart a[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) a[u] = s0 + u < splits ? pp[s0 + u] : ArgPart{-INFINITY, -1};
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (s0 + u < splits && (post < 0 || a[u].val > bv)) {
+                        // later segments hold higher ids: strict > keeps the first maximum
+                        bv = a[u].val;
+                        post = a[u].idx;
+                    }
+            }
         }
         s_post[i] = post;
         s_tok[i] = i <= n ? tokens[base + i] : -1;
