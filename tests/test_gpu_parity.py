@@ -480,6 +480,34 @@ def test_attn_chain_tree_and_no_cache():
         assert np.array_equal(got[0, h], vt[0, h // 2])
 
 
+def test_attn_generic_randomized_shapes():
+    """Seeded sweep of the generic kernel (fp32 at any head size, bf16 at head sizes other than 128):
+    head sizes from 8 to 256, head layouts, ragged batches, short and empty caches, padded trees."""
+    rng = np.random.default_rng(808)
+    worst = {"fp32": 0.0, "bf16": 0.0}
+    for case in range(40):
+        dtype = "fp32" if case % 2 == 0 else "bf16"
+        D = int(rng.choice([8, 16, 40, 64, 72, 96, 128, 200, 256] if dtype == "fp32" else [8, 16, 40, 64, 72, 200, 256]))
+        Hkv = int(rng.choice([1, 2, 3])); Hq = Hkv * int(rng.choice([1, 2, 4]))
+        T = int(rng.choice([1, 2, 9, 33, 70, 130])); batch = int(rng.choice([1, 2, 3]))
+        Ls = [int(rng.choice([0, 1, 7, 100, 255, 256, 257, 600])) for _ in range(batch)]
+        off = np.concatenate([[0], np.cumsum(Ls)]).astype(np.int32)
+        qs, kcs, vcs, kts, vts, ms = [], [], [], [], [], []
+        for b in range(batch):
+            q, kc, vc, kt, vt = di.attn_tensors(9000 + 10 * case + b, T, Ls[b], Hq, Hkv, D, dtype)
+            par, n = _random_tree(rng, T, int(rng.integers(0, T)) if rng.random() < 0.3 else None)
+            qs.append(q); kcs.append(kc); vcs.append(vc); kts.append(kt); vts.append(vt)
+            ms.append(oracle.ancestor_mask(par, n, T=T))
+        got = gu.gpu_attn(np.concatenate(qs), np.concatenate(kcs), np.concatenate(vcs), np.concatenate(kts),
+                          np.concatenate(vts), np.stack(ms), off, batch, T, dtype)
+        for b in range(batch):
+            ref = oracle.verify_attn(qs[b], kcs[b], vcs[b], kts[b], vts[b], ms[b])
+            err = attn_err(got[b], ref)
+            assert err < (1e-5 if dtype == "fp32" else 1e-2), (case, dtype, D, Hq, Hkv, T, Ls, b, err)
+            worst[dtype] = max(worst[dtype], err)
+    print(f"worst error fp32 {worst['fp32']:.2e}, bf16 {worst['bf16']:.2e}")
+
+
 def test_attn_padding_rows_are_zero():
     T, L, Hq, Hkv, D = 80, 50, 4, 2, 128
     q, kc, vc, kt, vt, mask = _attn_case(6, T, L, Hq, Hkv, D, "bf16", n_nodes=40)
