@@ -706,6 +706,59 @@ def test_end_to_end_chain(config):
         assert int(ga["bonus_token"][0]) == acc_o["bonus"]
 
 
+def test_decoding_rounds_with_a_growing_cache():
+    """Five consecutive rounds on one sequence: top-K, build, attention over the cache as it stands,
+    accept, and compaction of the accepted path into the cache, whose new length the host reads back
+    as a serving loop would.  Every round is compared with the oracle's round on the oracle's own
+    cache; after the last round both caches hold the same rows."""
+    import paper_2604_12989_amd as dd
+    B, V, N, Hq, Hkv, D, L0, rounds = 8, 5000, 40, 8, 2, 128, 100, 5
+    K, T = N, N + 1
+    cap = L0 + rounds * (B + 1)
+    _, kc0, vc0, _, _ = di.attn_tensors(900, 1, L0, Hq, Hkv, D, "bf16")
+    cache_k_o = np.zeros((cap, Hkv, D), np.float32); cache_k_o[:L0] = kc0
+    cache_v_o = np.zeros((cap, Hkv, D), np.float32); cache_v_o[:L0] = vc0
+    cache_k_g = gu.bf16_dev(cache_k_o); cache_v_g = gu.bf16_dev(cache_v_o)
+    ws = dd.Workspace(1, B, V, N, Hq, Hkv, D, cap)
+    L, root, lengths = L0, 7, []
+    for r in range(rounds):
+        x = _peaked_logits(910 + r, B, V, 7.0)
+        tok_o, lp_o = oracle.topk(x, K)
+        tree = oracle.build_tree(tok_o, lp_o, N, root_token=root)
+        mask_o = oracle.ancestor_mask(tree["parent"], tree["n_nodes"], T=T)
+        q, _, _, kt, vt = di.attn_tensors(920 + r, T, 0, Hq, Hkv, D, "bf16")
+        plant = di.planted_tokens(930 + r, tree["depth"], tok_o[:, 0], B, p=0.85)
+        tl = di.target_logits(930 + r, T, V, plant)
+        ref = oracle.verify_attn(q, cache_k_o[:L], cache_v_o[:L], kt, vt, mask_o)
+        acc_o = oracle.accept(tl, tree["tokens"], tree["parent"], tree["n_nodes"], B)
+        # the same round on the GPU, each stage fed by the stage before it
+        tok_g, lp_g = dd.topk(gu.to_dev(x[None]), K, ws)
+        tree_g = dd.build(tok_g, lp_g, N, gu.to_dev(np.array([root], np.int32)), ws)
+        out = dd.verify_attn(gu.bf16_dev(q), cache_k_g, cache_v_g, gu.bf16_dev(kt), gu.bf16_dev(vt),
+                             tree_g["ancestor_mask"], [0, L], 1, T, Hq, Hkv, D, 1.0 / np.sqrt(D), dd.DTYPE_BF16, ws)
+        acc_g = dd.accept(gu.to_dev(tl[None]), tree_g["tokens"], tree_g["parent"], tree_g["depth"],
+                          tree_g["n_nodes"], B, ws)
+        kt_g, vt_g = gu.bf16_dev(kt), gu.bf16_dev(vt)
+        dd.compact(kt_g, vt_g, acc_g["path"], acc_g["n_accepted"], [L], 1, T, B, Hkv, D, cache_k_g, cache_v_g)
+        torch.cuda.synchronize()
+        assert np.array_equal(tree_g["parent"].cpu().numpy()[0], tree["parent"]), r
+        assert np.array_equal(tree_g["tokens"].cpu().numpy()[0], tree["tokens"]), r
+        assert attn_err(out.float().cpu().numpy().reshape(T, Hq, D), ref) < 1e-2, r
+        n_acc = int(acc_g["n_accepted"][0])            # the host learns the new length here
+        assert n_acc == acc_o["n_accepted"], r
+        assert np.array_equal(acc_g["path"].cpu().numpy()[0], acc_o["path"]), r
+        assert int(acc_g["bonus_token"][0]) == acc_o["bonus"], r
+        oracle.compact(kt, acc_o["path"], n_acc, cache_k_o, L)
+        oracle.compact(vt, acc_o["path"], n_acc, cache_v_o, L)
+        L += n_acc + 1
+        root = acc_o["bonus"]
+        lengths.append(n_acc)
+    assert max(lengths) >= 2, lengths
+    assert np.array_equal(cache_k_g.float().cpu().numpy()[:L], cache_k_o[:L])
+    assert np.array_equal(cache_v_g.float().cpu().numpy()[:L], cache_v_o[:L])
+    print(f"accepted per round {lengths}, cache grew from {L0} to {L} rows")
+
+
 # ------------------------------------------------------------------------------- sampled walk
 # fp32 keys on the GPU against fp64 keys in the oracle: a selection is compared where the oracle's
 # gap between winner and runner-up exceeds what fp32 can blur (logit/tau up to ~50 in magnitude:
