@@ -149,6 +149,21 @@ int ddtree_verify_attn(const void *q, const void *k_cache, const void *v_cache,
                        size_t workspace_bytes, void *stream);
 
 /*
+ * The same attention with each sequence's cache rows given as a span: sequence s owns rows
+ * kv_start[s] .. kv_start[s] + kv_len[s] - 1 of k_cache / v_cache ([host] int32 [batch] each,
+ * kv_start >= 0, kv_len >= 0).  The spans need not touch or be ordered, so a serving loop can keep
+ * room behind every sequence and let ddtree_compact append the accepted rows in place
+ * (Section 4.4, last sentence); ddtree_verify_attn is this call with kv_start = kv_offset[s] and
+ * kv_len = kv_offset[s + 1] - kv_offset[s].  Workspace as for ddtree_verify_attn, with the sum of
+ * the lengths in place of sum_L.
+ */
+int ddtree_verify_attn_spans(const void *q, const void *k_cache, const void *v_cache,
+                             const void *k_tree, const void *v_tree, const uint64_t *ancestor_mask,
+                             const int32_t *kv_start, const int32_t *kv_len, int batch, int T, int Hq,
+                             int Hkv, int D, float softmax_scale, int dtype, void *out,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Greedy verifier walk (Section 4.4, second paragraph; Figure 1b): posterior[i] is the argmax
  * of the target's logits at node i (lowest id among equal maxima).  Starting at the root, the
  * walk moves to the child of the current node whose token equals the posterior of the current

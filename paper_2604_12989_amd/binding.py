@@ -31,6 +31,8 @@ _SIGNATURES = {
     "ddtree_accept_sampled": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, ctypes.c_float,
                                    ctypes.c_uint64, _vp, _vp, _vp, _vp, _i, _vp, _sz, _vp]),
     "ddtree_compact": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp]),
+    "ddtree_verify_attn_spans": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i,
+                                      ctypes.c_float, _i, _vp, _vp, _sz, _vp]),
     "ddtree_set_build_algorithm": (_i, [_i]),
     "ddtree_build_giveups": (_i, [ctypes.POINTER(ctypes.c_uint)]),
     "ddtree_profile_enable": (_i, [ctypes.c_uint, _i]),
@@ -209,6 +211,31 @@ def verify_attn(q, k_cache, v_cache, k_tree, v_tree, ancestor_mask, kv_offset, b
             dtype, _ptr(out), p, n, _stream())
     run = _call("ddtree_verify_attn", args, out, defer)
     return _keepalive(run, off) if defer else run
+
+
+def verify_attn_spans(q, k_cache, v_cache, k_tree, v_tree, ancestor_mask, kv_start, kv_len, batch, T, Hq,
+                      Hkv, D, softmax_scale, dtype, ws, out=None, defer=False):
+    """verify_attn with sequence s owning cache rows kv_start[s] .. kv_start[s] + kv_len[s] - 1
+    (host int32 sequences of batch entries each; the spans need not touch)."""
+    tdt = torch.bfloat16 if dtype == DTYPE_BF16 else torch.float32
+    for name, t in (("q", q), ("k_tree", k_tree), ("v_tree", v_tree)):
+        _dev(t, tdt, name)
+    if k_cache is not None:
+        _dev(k_cache, tdt, "k_cache")
+        _dev(v_cache, tdt, "v_cache")
+    _dev(ancestor_mask, torch.int64, "ancestor_mask")
+    start = np.ascontiguousarray(np.asarray(kv_start, dtype=np.int32))
+    length = np.ascontiguousarray(np.asarray(kv_len, dtype=np.int32))
+    if start.shape != (batch,) or length.shape != (batch,):
+        raise DDTreeError("kv_start and kv_len must have batch entries each")
+    if out is None:
+        out = torch.empty_like(q)
+    p, n = _ws(ws)
+    args = (_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_tree), _ptr(v_tree), _ptr(ancestor_mask),
+            start.ctypes.data_as(ctypes.c_void_p), length.ctypes.data_as(ctypes.c_void_p), batch, T, Hq,
+            Hkv, D, ctypes.c_float(softmax_scale), dtype, _ptr(out), p, n, _stream())
+    run = _call("ddtree_verify_attn_spans", args, out, defer)
+    return _keepalive(run, start, length) if defer else run
 
 
 def accept(target_logits, tokens, parent, depth, n_nodes, B, ws, out=None, want_posterior=True,

@@ -60,7 +60,8 @@ constexpr int kStageBytes = kKTileBytes + kVTileBytes;
 constexpr int kAttnLdsBytes = kAttnStages * kStageBytes;
 
 struct AttnArgs {
-    int32_t kv_offset[DDTREE_MAX_BATCH + 1];
+    int32_t kv_start[DDTREE_MAX_BATCH];  // first cache row of each sequence
+    int32_t kv_len[DDTREE_MAX_BATCH];    // its number of cache rows
     // matrix-core kernel only: the sequences longest cache first, and the first work item of
     // each of the 8 XCDs' runs (run x = work items xcd_start[x] .. xcd_start[x + 1] - 1)
     uint8_t order[DDTREE_MAX_BATCH];
@@ -291,8 +292,8 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     const int G = Hq / Hkv;
     const int W = (T + 63) >> 6;
     const int M = T * G;
-    const int L0 = args.kv_offset[seq];
-    const int L = args.kv_offset[seq + 1] - L0;
+    const int L0 = args.kv_start[seq];
+    const int L = args.kv_len[seq];
     // this tile's blocks of 32 rows: wave w owns blocks kCB*w .. kCB*w + kCB - 1 of the tile
     const int first_blk = tail_splits > 0 ? mt * 8 : mt * blk_base + min(mt, blk_extra);
     const int n_blk = tail_splits > 0 ? (tail ? blk_extra : 8) : blk_base + (mt < blk_extra ? 1 : 0);
@@ -809,8 +810,8 @@ __global__ __launch_bounds__(kGenThreads) void attn_generic_kernel(
     const int h = blockIdx.x, i = blockIdx.y, seq = blockIdx.z;
     const int G = Hq / Hkv, hk = h / G;
     const int W = (T + 63) >> 6;
-    const int L0 = args.kv_offset[seq];
-    const int L = args.kv_offset[seq + 1] - L0;
+    const int L0 = args.kv_start[seq];
+    const int L = args.kv_len[seq];
     const size_t qrow = ((size_t)seq * T + i) * Hq + h;
     const uint64_t *mrow = mask + ((size_t)seq * T + i) * W;
     TIO *orow = out + qrow * D;
@@ -912,14 +913,14 @@ __global__ __launch_bounds__(kGenThreads) void attn_generic_kernel(
 
 }  // namespace ddt
 
-extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void *v_cache,
-                                  const void *k_tree, const void *v_tree,
-                                  const uint64_t *ancestor_mask, const int32_t *kv_offset, int batch,
-                                  int T, int Hq, int Hkv, int D, float softmax_scale, int dtype,
-                                  void *out, void *workspace, size_t workspace_bytes, void *stream)
+static int verify_attn_impl(const void *q, const void *k_cache, const void *v_cache, const void *k_tree,
+                            const void *v_tree, const uint64_t *ancestor_mask, const int32_t *kv_start,
+                            const int32_t *kv_len, int batch, int T, int Hq, int Hkv, int D,
+                            float softmax_scale, int dtype, void *out, void *workspace,
+                            size_t workspace_bytes, void *stream)
 {
     using namespace ddt;
-    if (!q || !k_tree || !v_tree || !ancestor_mask || !kv_offset || !out) return DDTREE_ERR_ARG;
+    if (!q || !k_tree || !v_tree || !ancestor_mask || !kv_start || !kv_len || !out) return DDTREE_ERR_ARG;
     // rows are read and written 16 bytes at a time
     for (const void *t : {q, k_cache, v_cache, k_tree, v_tree, static_cast<const void *>(out)})
         if (reinterpret_cast<uintptr_t>(t) & 15u) return DDTREE_ERR_ARG;
@@ -930,13 +931,15 @@ extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void
     if (dtype != DDTREE_DTYPE_BF16 && dtype != DDTREE_DTYPE_FP32) return DDTREE_ERR_ARG;
     if (!(softmax_scale > 0.0f) || !(softmax_scale < 1e30f)) return DDTREE_ERR_ARG;
     AttnArgs args;
-    if (kv_offset[0] < 0) return DDTREE_ERR_ARG;
-    for (int s = 0; s <= batch; ++s) {
-        if (s > 0 && kv_offset[s] < kv_offset[s - 1]) return DDTREE_ERR_ARG;
-        args.kv_offset[s] = kv_offset[s];
+    long long sum_L = 0;
+    for (int s = 0; s < batch; ++s) {
+        if (kv_start[s] < 0 || kv_len[s] < 0 || (long long)kv_start[s] + kv_len[s] > 0x7FFFFFFFll)
+            return DDTREE_ERR_ARG;
+        args.kv_start[s] = kv_start[s];
+        args.kv_len[s] = kv_len[s];
+        sum_L += kv_len[s];
     }
-    const long long sum_L = (long long)kv_offset[batch] - kv_offset[0];
-    if (kv_offset[batch] > 0 && (!k_cache || !v_cache)) return DDTREE_ERR_ARG;
+    if (sum_L > 0 && (!k_cache || !v_cache)) return DDTREE_ERR_ARG;
     hipStream_t st = as_stream(stream);
 
     if (dtype == DDTREE_DTYPE_BF16 && D == kHD) {
@@ -957,10 +960,10 @@ extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void
         if (total > (1ll << 28)) return DDTREE_ERR_ARG;
         for (int i = 0; i < batch; ++i) args.order[i] = (uint8_t)i;
         std::stable_sort(args.order, args.order + batch, [&](uint8_t a, uint8_t b) {
-            return kv_offset[a + 1] - kv_offset[a] > kv_offset[b + 1] - kv_offset[b];
+            return kv_len[a] > kv_len[b];
         });
         long long work_total = 0;
-        for (int i = 0; i < batch; ++i) work_total += per_seq * ((long long)kv_offset[i + 1] - kv_offset[i] + T);
+        for (int i = 0; i < batch; ++i) work_total += per_seq * ((long long)kv_len[i] + T);
         {
             long long done = 0, first = 0;  // work and items before sequence position `pos`
             int pos = 0, x = 1;
@@ -968,7 +971,7 @@ extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void
             while (x < 8) {
                 const long long target = (work_total * x + 7) / 8;
                 const int sq = args.order[pos];
-                const long long w = (long long)kv_offset[sq + 1] - kv_offset[sq] + T;
+                const long long w = (long long)kv_len[sq] + T;
                 if (pos < batch - 1 && done + per_seq * w < target) {
                     done += per_seq * w;
                     first += per_seq;
@@ -1024,3 +1027,31 @@ extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void
     return launch_status();
 }
 
+extern "C" int ddtree_verify_attn(const void *q, const void *k_cache, const void *v_cache,
+                                  const void *k_tree, const void *v_tree,
+                                  const uint64_t *ancestor_mask, const int32_t *kv_offset, int batch,
+                                  int T, int Hq, int Hkv, int D, float softmax_scale, int dtype,
+                                  void *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!kv_offset || batch < 1 || batch > DDTREE_MAX_BATCH || kv_offset[0] < 0) return DDTREE_ERR_ARG;
+    int32_t start[DDTREE_MAX_BATCH], len[DDTREE_MAX_BATCH];
+    for (int s = 0; s < batch; ++s) {
+        if (kv_offset[s + 1] < kv_offset[s]) return DDTREE_ERR_ARG;
+        start[s] = kv_offset[s];
+        len[s] = kv_offset[s + 1] - kv_offset[s];
+    }
+    return verify_attn_impl(q, k_cache, v_cache, k_tree, v_tree, ancestor_mask, start, len, batch, T, Hq,
+                            Hkv, D, softmax_scale, dtype, out, workspace, workspace_bytes, stream);
+}
+
+extern "C" int ddtree_verify_attn_spans(const void *q, const void *k_cache, const void *v_cache,
+                                        const void *k_tree, const void *v_tree,
+                                        const uint64_t *ancestor_mask, const int32_t *kv_start,
+                                        const int32_t *kv_len, int batch, int T, int Hq, int Hkv, int D,
+                                        float softmax_scale, int dtype, void *out, void *workspace,
+                                        size_t workspace_bytes, void *stream)
+{
+    if (batch < 1 || batch > DDTREE_MAX_BATCH) return DDTREE_ERR_ARG;
+    return verify_attn_impl(q, k_cache, v_cache, k_tree, v_tree, ancestor_mask, kv_start, kv_len, batch, T,
+                            Hq, Hkv, D, softmax_scale, dtype, out, workspace, workspace_bytes, stream);
+}

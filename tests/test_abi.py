@@ -109,6 +109,15 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
                                   128, 0.088, 0, p, None, 0, None) == ERR_ARG
     assert lib.ddtree_verify_attn(p, p, p, p, odd, p, ctypes.cast(off2, ctypes.c_void_p), 1, 257, 32, 8,
                                   128, 0.088, 0, p, None, 0, None) == ERR_ARG
+    # spans of the cache: negative start or length
+    st_ = (ctypes.c_int32 * 1)(-1)
+    ln_ = (ctypes.c_int32 * 1)(5)
+    assert lib.ddtree_verify_attn_spans(p, p, p, p, p, p, ctypes.cast(st_, ctypes.c_void_p),
+                                        ctypes.cast(ln_, ctypes.c_void_p), 1, 17, 2, 1, 64, ctypes.c_float(0.125), 1, p,
+                                        None, 0, None) == ERR_ARG
+    assert lib.ddtree_verify_attn_spans(p, p, p, p, p, p, ctypes.cast(ln_, ctypes.c_void_p),
+                                        ctypes.cast(st_, ctypes.c_void_p), 1, 17, 2, 1, 64, ctypes.c_float(0.125), 1, p,
+                                        None, 0, None) == ERR_ARG
     # accept: workspace too small, null outputs
     assert lib.ddtree_accept(p, 1, 257, 151936, p, p, p, p, p, p, p, None, 16, p, 16, None) == ERR_WS
     assert lib.ddtree_accept(p, 1, 257, 151936, p, p, p, p, None, p, p, None, 16, p, 4096, None) == ERR_ARG

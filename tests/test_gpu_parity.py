@@ -759,6 +759,68 @@ def test_decoding_rounds_with_a_growing_cache():
     print(f"accepted per round {lengths}, cache grew from {L0} to {L} rows")
 
 
+def test_batched_decoding_rounds_with_cache_spans():
+    """Three sequences, each with its own region of the cache and room behind it; four rounds of
+    attention (ddtree_verify_attn_spans), accept and in-place compaction, the regions listed out of
+    order and with gaps.  Compared per sequence and round with the oracle on its own cache copy."""
+    import paper_2604_12989_amd as dd
+    batch, B, V, N, Hq, Hkv, D, rounds = 3, 6, 4000, 30, 8, 2, 128, 4
+    K, T = N, N + 1
+    room = rounds * (B + 1)
+    L = [150, 0, 75]
+    start = [500, 20, 900]                       # regions out of order, gaps between them
+    rows = 900 + 75 + room + 10
+    cache_k_o = np.zeros((rows, Hkv, D), np.float32); cache_v_o = np.zeros_like(cache_k_o)
+    for s in range(batch):
+        _, kc, vc, _, _ = di.attn_tensors(1200 + s, 1, L[s], Hq, Hkv, D, "bf16")
+        cache_k_o[start[s]:start[s] + L[s]] = kc
+        cache_v_o[start[s]:start[s] + L[s]] = vc
+    cache_k_g = gu.bf16_dev(cache_k_o); cache_v_g = gu.bf16_dev(cache_v_o)
+    ws = dd.Workspace(batch, B, V, N, Hq, Hkv, D, sum(L) + batch * room)
+    roots = np.array([3, 4, 5], np.int32)
+    total_accepted = 0
+    for r in range(rounds):
+        xs = np.stack([_peaked_logits(1300 + 10 * r + s, B, V, 7.0) for s in range(batch)])
+        q, _, _, kt, vt = di.attn_tensors(1400 + r, batch * T, 0, Hq, Hkv, D, "bf16")
+        trees, tls, refs, accs = [], [], [], []
+        for s in range(batch):
+            tok_o, lp_o = oracle.topk(xs[s], K)
+            t = oracle.build_tree(tok_o, lp_o, N, root_token=int(roots[s]))
+            m = oracle.ancestor_mask(t["parent"], t["n_nodes"], T=T)
+            plant = di.planted_tokens(1500 + 10 * r + s, t["depth"], tok_o[:, 0], B, p=0.85, batch_index=s)
+            tl = di.target_logits(1500 + 10 * r + s, T, V, plant, batch_index=s)
+            sl = slice(start[s], start[s] + L[s])
+            refs.append(oracle.verify_attn(q[s * T:(s + 1) * T], cache_k_o[sl], cache_v_o[sl],
+                                           kt[s * T:(s + 1) * T], vt[s * T:(s + 1) * T], m))
+            accs.append(oracle.accept(tl, t["tokens"], t["parent"], t["n_nodes"], B))
+            trees.append(t); tls.append(tl)
+        tok_g, lp_g = dd.topk(gu.to_dev(xs), K, ws)
+        tree_g = dd.build(tok_g, lp_g, N, gu.to_dev(roots), ws)
+        kt_g, vt_g = gu.bf16_dev(kt), gu.bf16_dev(vt)
+        out = dd.verify_attn_spans(gu.bf16_dev(q), cache_k_g, cache_v_g, kt_g, vt_g, tree_g["ancestor_mask"],
+                                   start, L, batch, T, Hq, Hkv, D, 1.0 / np.sqrt(D), dd.DTYPE_BF16, ws)
+        acc_g = dd.accept(gu.to_dev(np.stack(tls)), tree_g["tokens"], tree_g["parent"], tree_g["depth"],
+                          tree_g["n_nodes"], B, ws)
+        dd.compact(kt_g, vt_g, acc_g["path"], acc_g["n_accepted"], [start[s] + L[s] for s in range(batch)],
+                   batch, T, B, Hkv, D, cache_k_g, cache_v_g)
+        torch.cuda.synchronize()
+        got = out.float().cpu().numpy().reshape(batch, T, Hq, D)
+        n_acc = acc_g["n_accepted"].cpu().numpy()
+        for s in range(batch):
+            assert np.array_equal(tree_g["parent"][s].cpu().numpy(), trees[s]["parent"]), (r, s)
+            assert attn_err(got[s], refs[s]) < 1e-2, (r, s)
+            assert int(n_acc[s]) == accs[s]["n_accepted"], (r, s)
+            assert np.array_equal(acc_g["path"][s].cpu().numpy(), accs[s]["path"]), (r, s)
+            oracle.compact(kt[s * T:(s + 1) * T], accs[s]["path"], int(n_acc[s]), cache_k_o[start[s]:], L[s])
+            oracle.compact(vt[s * T:(s + 1) * T], accs[s]["path"], int(n_acc[s]), cache_v_o[start[s]:], L[s])
+            L[s] += int(n_acc[s]) + 1
+            roots[s] = accs[s]["bonus"]
+            total_accepted += int(n_acc[s])
+    assert total_accepted >= rounds
+    assert np.array_equal(cache_k_g.float().cpu().numpy(), cache_k_o)
+    assert np.array_equal(cache_v_g.float().cpu().numpy(), cache_v_o)
+
+
 # ------------------------------------------------------------------------------- sampled walk
 # fp32 keys on the GPU against fp64 keys in the oracle: a selection is compared where the oracle's
 # gap between winner and runner-up exceeds what fp32 can blur (logit/tau up to ~50 in magnitude:
