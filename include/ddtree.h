@@ -21,7 +21,10 @@
  *   - Pointers marked [device] are device memory owned by the caller; the library never
  *     allocates, frees or retains them.  Pointers marked [host] are read during the call only.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
- *     work on it and never synchronise; consecutive calls on one stream are ordered.
+ *     kernels on it (no allocation, no memset or copy, no synchronisation); consecutive calls
+ *     on one stream are ordered.  A caller may therefore record them into a HIP graph; the
+ *     [host] arrays of a call (kv_offset, kv_start, kv_len, dst_row) travel as kernel arguments
+ *     and are fixed in a recorded graph.
  *   - `workspace` [device] is scratch of at least ddtree_workspace_bytes(...) bytes, 256-byte
  *     aligned, whose contents need not survive between calls.  Calls on different streams need
  *     different workspaces.
