@@ -220,6 +220,16 @@ def main():
         stages["accept_argmax_GBs"] = round(tl_h.nbytes / (stages["accept_argmax_us"] * 1e-6) / 1e9, 1)
     if "topk_chunk_us" in stages:
         stages["topk_chunk_GBs"] = round(logits_h.nbytes / (stages["topk_chunk_us"] * 1e-6) / 1e9, 1)
+    # each stage against the roofline that bounds it (the build is a latency chain: no roofline)
+    stages["frac_of_roofline"] = {
+        k: v for k, v in (
+            ("topk_hbm", round(logits_h.nbytes / (1e-6 * (stages.get("topk_chunk_us", 0) + stages.get("topk_merge_us", 0))
+                                                  or float("inf")) / 1e9 / PEAK_HBM_GBS, 4)),
+            ("attn_mfma" if main_kernel == "attn" else "attn_fp32_alu",
+             round(flops / (stages[main_kernel + "_us"] * 1e-6) / 1e12 / (PEAK_BF16_TFLOPS if main_kernel == "attn" else 157.3), 4)),
+            ("accept_hbm", round(tl_h.nbytes / (1e-6 * (stages.get("accept_argmax_us", 0) + stages.get("accept_walk_us", 0))
+                                                or float("inf")) / 1e9 / PEAK_HBM_GBS, 4)),
+        )}
 
     # ------------------------------------------------------------------ CPU oracle baseline
     cpu = None
