@@ -119,8 +119,11 @@ __global__ __launch_bounds__(kArgmaxThreads) void accept_argmax_kernel(
     // hash alone, g = -ln(-ln u) <= -ln(1 - u) = ln(2^25 / w) with the odd integer
     // w = 2^25 - 2k - 1, hence g <= ln2 * (clz(w) - 6); an element whose bound stays below a key
     // this wave has already found (wb) cannot be the row's maximum, nor tie with it.
+    // The loop bound is uniform over the wave (its lanes leave the loop together): the wave
+    // maximum below reads lane 63, which must have taken part in every round.
     float wb = -INFINITY;
-    for (int j0 = tid; j0 < nvec; j0 += kInFlight * kArgmaxThreads) {
+    for (int jb = tid & ~63; jb < nvec; jb += kInFlight * kArgmaxThreads) {
+        const int j0 = jb + (tid & 63);
         float4 x[kInFlight];
 #pragma unroll
         for (int u = 0; u < kInFlight; ++u) {

@@ -875,6 +875,26 @@ def test_accept_sampled_matches_oracle(tau):
         assert np.mean(other["posterior"][0][: n + 1] == got["posterior"][0][: n + 1]) < 0.5
 
 
+@pytest.mark.parametrize("V", [5, 70, 300, 1000, 1027, 2500])
+def test_accept_sampled_small_vocabularies(V):
+    """Rows shorter than one round of a scan workgroup (fewer than 256 groups of four logits): some
+    waves of the workgroup are only partly filled, or idle, from the first round on."""
+    rng = np.random.default_rng(V)
+    T, B = 40, 8
+    n = T - 1
+    par = np.full(T, -1, np.int32)
+    depth = np.zeros(T, np.int32)
+    for i in range(1, T):
+        ok = np.flatnonzero(depth[:i] < B)
+        par[i] = rng.choice(ok)
+        depth[i] = depth[par[i]] + 1
+    tokens = rng.integers(0, V, T).astype(np.int32)
+    for rep in range(3):
+        tl = (rng.standard_normal((T, V)) * 2.0).astype(np.float32)
+        _check_sampled(tl, tokens, par, depth, n, B, float(rng.choice([0.3, 1.0, 2.0])),
+                       seed=int(rng.integers(1, 2**62)))
+
+
 def test_accept_sampled_walks_down_a_planted_chain_and_batches():
     # two sequences; in the first a chain of tokens dominates its rows (logit + 60: sampled with
     # probability ~1 at tau = 1), so the walk must descend it; the second has nothing planted
