@@ -17,11 +17,14 @@ namespace ddt {
 constexpr int kArgmaxThreads = 256;
 constexpr int kWalkThreads = 256;
 
-AcceptPlan accept_plan(int batch, int T, int V)
+AcceptPlan accept_plan(int batch, int T, int V, bool sampled)
 {
     AcceptPlan p{};
     long long rows = (long long)batch * T;
-    int S = (int)((3072 + rows - 1) / rows);  // about 3000 workgroups stream closest to the HBM rate
+    // about 3000 workgroups stream closest to the HBM rate; the sampled scan prunes key evaluations
+    // against the best key a wave has found so far, which longer segments serve better
+    const int target = sampled ? 1024 : 3072;
+    int S = (int)((target + rows - 1) / rows);
     int s_cap = V / 8192 > 0 ? V / 8192 : 1;  // keep segments at least 8192 long
     if (S > s_cap) S = s_cap;
     if (S < 1) S = 1;
@@ -307,7 +310,7 @@ static int accept_impl(const float *target_logits, int batch, int T, int V, cons
     if (batch < 1 || batch > DDTREE_MAX_BATCH || T < 2 || T > DDTREE_MAX_N + 1 || V < 1 || B < 1 ||
         B > DDTREE_MAX_B)
         return DDTREE_ERR_ARG;
-    AcceptPlan p = accept_plan(batch, T, V);
+    AcceptPlan p = accept_plan(batch, T, V, sample);
     if (!ws_ok(workspace, workspace_bytes, p.bytes)) return DDTREE_ERR_WORKSPACE;
     ArgPart *part = reinterpret_cast<ArgPart *>(static_cast<char *>(workspace) + p.part_off);
     hipStream_t st = as_stream(stream);

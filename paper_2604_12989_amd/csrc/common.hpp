@@ -74,7 +74,7 @@ struct AcceptPlan {
     int seg_len; // elements per segment (multiple of 4)
     size_t part_off, bytes;
 };
-AcceptPlan accept_plan(int batch, int T, int V);
+AcceptPlan accept_plan(int batch, int T, int V, bool sampled = false);  // the greedy plan needs the larger scratch
 
 // ---- optional event timing around kernel launches (see ddtree_profile_enable) ----
 struct Profiler {
