@@ -45,11 +45,8 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kCB = 1;
 constexpr int kWaves = 8 / kCB;
 constexpr int kAttnThreads = 64 * kWaves;
-constexpr int kMT = 256;       // query rows per workgroup
 constexpr int kKT = 64;        // keys per tile
 constexpr int kHD = 128;       // head dim of the MFMA path
-constexpr int kKStride = kHD + 8;   // bf16 elements per K row in LDS (272 B)
-constexpr int kVStride = kHD + 16;  // bf16 elements per V row in LDS (288 B)
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kAttnStages = 3;
 constexpr int kKRowBytes = 272;                  // K tile row in LDS: 256 B + 16 B pad (17 chunks)

@@ -205,7 +205,7 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
     __shared__ int s_pref[kLvBuckets + 1];    // exclusive prefix of s_histc, later of s_hist
     __shared__ int s_w[kBuildThreads / 64];
     __shared__ int s_w2[2][kBuildThreads / 64];
-    __shared__ int s_M, s_fail, s_nbig, s_bstar, s_cum;
+    __shared__ int s_M, s_fail, s_nbig, s_bstar;
     __shared__ uint16_t s_big[kLvBigCap];
     constexpr int NT = kBuildThreads;
     const int tid = threadIdx.x;
