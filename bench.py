@@ -253,7 +253,8 @@ def main():
                           f"(all {batch}x{T}x{Hq} attention rows), mean {np.mean(t_cpu):.2f} s/step")
 
     result = {
-        "metric": "tree steps/s (topk+build+verify-attn+accept)",
+        "metric": ("tree steps/s (topk+build+verify-attn+accept) at N=256, L=8192; % roofline"
+                   if args.config == 3 and args.budget == 0 else "tree steps/s (topk+build+verify-attn+accept)"),
         "value": round(steps_per_s, 1),
         "unit": "tree steps/s",
         "n_gpus": 1,
