@@ -348,7 +348,9 @@ def _attn_case(seed, T, L, Hq, Hkv, D, dtype, n_nodes=None):
 ATTN_BF16 = [(17, 128, 4, 1, 1), (65, 100, 8, 2, 2), (257, 333, 8, 2, 3), (129, 1000, 16, 2, 4),
              (257, 0, 4, 4, 5), (64, 64, 32, 8, 6), (513, 2048, 8, 2, 7), (40, 4100, 32, 8, 8),
              # row counts a few blocks past whole tiles of 8 (uneven tiling: 2, 3 and 4 spare blocks)
-             (75, 3000, 16, 4, 9), (273, 5000, 32, 8, 10), (90, 700, 8, 2, 11)]
+             (75, 3000, 16, 4, 9), (273, 5000, 32, 8, 10), (90, 700, 8, 2, 11),
+             # query heads per KV head that are not powers of two (3, 5, 12)
+             (65, 500, 6, 2, 12), (129, 300, 10, 2, 13), (40, 1000, 12, 1, 14)]
 
 
 @pytest.mark.parametrize("T,L,Hq,Hkv,seed", ATTN_BF16)
