@@ -118,6 +118,20 @@ def draft_logits(seed: int, B: int, V: int, batch_index: int = 0) -> np.ndarray:
     return x.astype(np.float32)
 
 
+def peaked_draft_logits(seed: int, B: int, V: int, p: float, batch_index: int = 0) -> np.ndarray:
+    """draft_logits() with the spiked token of every row raised until it holds probability p of
+    that row (a confident drafter: trees then reach the last position).  The height comes from
+    the log-sum-exp of the row's other entries; that calibrates the input distribution and is
+    not a step of the method."""
+    x = draft_logits(seed, B, V, batch_index).astype(np.float64)
+    spike = randint(seed, 1000 + 10 * batch_index + 1, B, V)
+    for d in range(B):
+        others = np.delete(x[d], spike[d])
+        m = others.max()
+        x[d, spike[d]] = m + np.log(np.exp(others - m).sum()) + np.log(p / (1.0 - p))
+    return x.astype(np.float32)
+
+
 def attn_tensors(seed: int, T: int, L: int, Hq: int, Hkv: int, D: int, dtype: str,
                  batch_index: int = 0):
     """q [T,Hq,D], k_cache/v_cache [L,Hkv,D], k_tree/v_tree [T,Hkv,D] as fp32 arrays.

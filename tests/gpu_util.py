@@ -9,6 +9,28 @@ import paper_2604_12989_amd as dd
 DEV = "cuda:0"
 
 
+def attn_err(got, ref):
+    """Worst attention error in the units of the tolerance: |got - ref| where |ref| < 4 (the
+    literal max-abs bound), |got - ref| / |ref| for elements of magnitude 4 or more."""
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    d = np.abs(got - ref)
+    a = np.abs(ref)
+    big = a >= 4.0
+    err = float(d[~big].max()) if (~big).any() else 0.0
+    if big.any():
+        err = max(err, float((d[big] / a[big]).max()))
+    return err
+
+
+def attn_err_over_rms(got, ref):
+    """max-abs error divided by rms(ref): how large the error is on the scale of the outputs
+    themselves (long contexts average unit-variance values down to rms ~ 1/sqrt(L))."""
+    ref = np.asarray(ref, np.float64)
+    rms = float(np.sqrt((ref ** 2).mean()))
+    return float(np.abs(np.asarray(got, np.float64) - ref).max()) / max(rms, 1e-30), rms
+
+
 def to_dev(a, dtype=None):
     t = torch.from_numpy(np.ascontiguousarray(a))
     if dtype is not None:

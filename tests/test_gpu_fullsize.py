@@ -1,8 +1,7 @@
 """GPU parity at the full workload sizes, in the launch configuration bench.py times (batch,
-shapes, workspace from ddtree_workspace_bytes).  Top-K, tree, mask and walk are compared in full
-(the oracle is fast enough); attention on sampled (node, head) rows that the oracle computes one
-by one, always including the root, the last node and nodes around the 64-node mask-word and
-256-row tile boundaries."""
+shapes, workspace from ddtree_workspace_bytes).  Every stage is compared in full: top-K, tree,
+mask, walk, and every (node, head) row of the attention output against the fp64 oracle, with the
+error also reported on the scale of the outputs (max-abs / rms of the reference)."""
 import numpy as np
 import pytest
 
@@ -23,16 +22,11 @@ def _need_gpu():
         pytest.fail("GPU tests selected but no GPU is visible")
 
 
-def _sample_pairs(rng, T, Hq, n):
-    nodes = {0, 1, T - 1, T // 2}
-    for b in (63, 64, 65, 127, 128, 255, 256, 257, 511, 512):
-        if b < T:
-            nodes.add(b)
-    pairs = [(i, int(rng.integers(0, Hq))) for i in sorted(nodes)]
-    pairs += [(i, h) for i in (0, T - 1) for h in (0, Hq - 1)]
-    while len(pairs) < n:
-        pairs.append((int(rng.integers(0, T)), int(rng.integers(0, Hq))))
-    return np.array(pairs, np.int32)
+# at these context lengths the outputs are averages of thousands of unit-variance rows (rms
+# 0.01 .. 0.03), so the absolute bound alone would be loose: the error is also held to a fraction
+# of that rms (bf16 rounding of such an output is 2**-9 of its own size, a few per cent of the rms
+# for the largest elements; measured 0.017 .. 0.029 on these workloads)
+RMS_FRACTION = 0.05
 
 
 @pytest.mark.parametrize("config,spike", [(3, 0.0), (3, 20.0), (4, 0.0), (2, 25.0)])
@@ -67,7 +61,7 @@ def test_single_sequence_configs_full_size(config, spike):
     assert np.array_equal(tg["ancestor_mask"].view(np.uint64), mask_o)
     assert int(tg["n_nodes"]) == tree_o["n_nodes"] == N
 
-    # attention, sampled rows
+    # attention, every (node, head) row
     q, kc, vc, kt, vt = di.attn_tensors(seed, T, L, Hq, Hkv, D, "bf16")
     out = dd.verify_attn(gu.bf16_dev(q), gu.bf16_dev(kc), gu.bf16_dev(vc), gu.bf16_dev(kt),
                          gu.bf16_dev(vt), tree_g["ancestor_mask"], [0, L], 1, T, Hq, Hkv, D,
@@ -75,12 +69,13 @@ def test_single_sequence_configs_full_size(config, spike):
     torch.cuda.synchronize()
     got = out.float().cpu().numpy().reshape(T, Hq, D)
     assert np.isfinite(got).all()
-    pairs = _sample_pairs(np.random.default_rng(config), T, Hq, 160)
-    ref = oracle.verify_attn(q, kc, vc, kt, vt, mask_o, pairs=pairs)
-    err = max(float((np.abs(got[i, h] - ref[r]) / np.maximum(1.0, np.abs(ref[r]))).max())
-              for r, (i, h) in enumerate(pairs))
-    print(f"  attention: {len(pairs)} sampled rows, max err {err:.2e}", flush=True)
+    ref = oracle.verify_attn(q, kc, vc, kt, vt, mask_o)
+    err = gu.attn_err(got, ref)
+    frac, rms = gu.attn_err_over_rms(got, ref)
+    print(f"  attention: all {T * Hq} rows, max-abs err {err:.2e}, rms(ref) {rms:.4f}, "
+          f"max-abs / rms {frac:.3f}", flush=True)
     assert err < 1e-2
+    assert frac < RMS_FRACTION
 
     # accept, full
     plant = di.planted_tokens(seed, tree_o["depth"], tok_o[:, 0], B, p=0.9 if spike else 0.8)
@@ -147,16 +142,16 @@ def test_batched_ragged_config_full_size():
     torch.cuda.synchronize()
     got = out.float().cpu().numpy().reshape(batch, T, Hq, D)
     assert np.isfinite(got).all()
-    rng = np.random.default_rng(5)
-    worst = 0.0
+    worst, worst_frac = 0.0, 0.0
     for s in range(batch):
-        pairs = _sample_pairs(rng, T, Hq, 24)
         ref = oracle.verify_attn(q[s * T:(s + 1) * T], kc[off[s]:off[s + 1]], vc[off[s]:off[s + 1]],
-                                 kt[s * T:(s + 1) * T], vt[s * T:(s + 1) * T], masks[s], pairs=pairs)
-        for r, (i, h) in enumerate(pairs):
-            worst = max(worst, float((np.abs(got[s, i, h] - ref[r]) / np.maximum(1.0, np.abs(ref[r]))).max()))
-    print(f"  ragged attention: max err {worst:.2e} over {batch * 24} sampled rows", flush=True)
+                                 kt[s * T:(s + 1) * T], vt[s * T:(s + 1) * T], masks[s])
+        worst = max(worst, gu.attn_err(got[s], ref))
+        worst_frac = max(worst_frac, gu.attn_err_over_rms(got[s], ref)[0])
+    print(f"  ragged attention: all {batch * T * Hq} rows, max-abs err {worst:.2e}, "
+          f"max-abs / rms {worst_frac:.3f}", flush=True)
     assert worst < 1e-2
+    assert worst_frac < RMS_FRACTION
 
     # accept on [16*129, V]
     tbase = di.target_logits(seed, T, V, np.full(T, -1))
@@ -192,7 +187,7 @@ def test_attention_retry_when_scores_outgrow_the_reference():
     ref = oracle.verify_attn(q, kc, vc, kt, vt, mask)
     got = gu.gpu_attn(q, kc, vc, kt, vt, mask[None], [0, L], 1, T, "bf16")[0]
     assert np.isfinite(got).all()
-    err = float((np.abs(got - ref) / np.maximum(1.0, np.abs(ref))).max())
+    err = gu.attn_err(got, ref)
     print(f"retry case: max err {err:.2e}")
     assert err < 1e-2
 
