@@ -190,6 +190,28 @@ int ddtree_accept(const float *target_logits, int batch, int T, int V, const int
                   int B, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * ddtree_accept for callers that cannot allocate device memory or bring a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid the allocator): the same kernels,
+ * with the partial argmaxes kept in a static device array inside the library, DDTREE_NOALLOC_SCRATCH_BYTES
+ * (256 KiB) on every GPU the library runs on, held until the process ends.  The call allocates and
+ * frees nothing.  Arguments and results as in ddtree_accept, without the workspace.
+ *   - Shapes whose partials exceed the array return DDTREE_ERR_WORKSPACE and launch nothing:
+ *     batch * T * segments * 8 bytes must fit, segments = min(ceil(3072 / (batch * T)), max(1, V / 8192))
+ *     (the headline shape, 257 rows of 151936 logits, takes 24 KB; 16 sequences of 129 rows 33 KB;
+ *     the largest call the other entry points accept, 64 sequences of 1025 rows, 525 KB, is refused).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ *     streams or host threads) race and must be serialised by the caller.  Nothing in the array
+ *     needs clearing between calls: every entry a call reads it has written itself.
+ *   - The array's device address is looked up on the first call on each device (with that device
+ *     current); DDTREE_ERR_HIP if the runtime refuses.
+ */
+#define DDTREE_NOALLOC_SCRATCH_BYTES ((size_t)256 << 10)
+int ddtree_accept_noalloc(const float *target_logits, int batch, int T, int V, const int32_t *tokens,
+                          const int32_t *parent, const int32_t *depth, const int32_t *n_nodes,
+                          int32_t *path, int32_t *n_accepted, int32_t *bonus_token,
+                          int32_t *posterior, int B, void *stream);
+
+/*
  * The same walk at temperature > 0 (Section 4.4, second paragraph: verification follows the
  * target model's own decoding rule, greedy or temperature-based sampling).  The token the target
  * selects at node i is a sample from softmax(target_logits[i] / temperature), drawn by the

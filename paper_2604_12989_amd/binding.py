@@ -28,6 +28,7 @@ _SIGNATURES = {
                                 ctypes.c_float, _i, _vp, _vp, _sz, _vp]),
     "ddtree_accept": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _sz,
                            _vp]),
+    "ddtree_accept_noalloc": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp]),
     "ddtree_accept_sampled": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, ctypes.c_float,
                                    ctypes.c_uint64, _vp, _vp, _vp, _vp, _i, _vp, _sz, _vp]),
     "ddtree_compact": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp]),
@@ -263,6 +264,18 @@ def accept(target_logits, tokens, parent, depth, n_nodes, B, ws, out=None, want_
             _ptr(n_nodes), _ptr(out["path"]), _ptr(out["n_accepted"]), _ptr(out["bonus_token"]),
             _ptr(out.get("posterior")), B, p, n, _stream())
     return _call("ddtree_accept", args, out, defer)
+
+
+def accept_noalloc(target_logits, tokens, parent, depth, n_nodes, B, out, defer=False):
+    """ddtree_accept_noalloc: the greedy walk with its scratch in the library's static device
+    array.  `out` (dict of path, n_accepted, bonus_token, posterior-or-None) is supplied by the
+    caller: this path allocates nothing, here or in the library."""
+    _dev(target_logits, torch.float32, "target_logits")
+    batch, T, V = target_logits.shape
+    args = (_ptr(target_logits), batch, T, V, _ptr(tokens), _ptr(parent), _ptr(depth),
+            _ptr(n_nodes), _ptr(out["path"]), _ptr(out["n_accepted"]), _ptr(out["bonus_token"]),
+            _ptr(out.get("posterior")), B, _stream())
+    return _call("ddtree_accept_noalloc", args, out, defer)
 
 
 def compact(k_tree, v_tree, path, n_accepted, dst_row, batch, T, B, Hkv, D, k_cache, v_cache):

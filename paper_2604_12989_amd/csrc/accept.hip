@@ -297,6 +297,31 @@ __global__ __launch_bounds__(256) void compact_kernel(
 
 }  // namespace ddt
 
+// Scratch of ddtree_accept_noalloc: the partial argmaxes live in this array instead of a caller's
+// workspace.  Every GPU the library runs on holds its own copy until the process ends.  In host
+// code the array's name is only a handle for hipGetSymbolAddress; the device address it returns
+// (one per device) is what the kernels are given.
+namespace ddt {
+constexpr size_t kNoAllocScratchBytes = DDTREE_NOALLOC_SCRATCH_BYTES;  // 32768 (value, index) partials
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+constexpr int kNoAllocMaxDevices = 64;
+}  // namespace ddt
+
+// Device address of the scratch array on the current device, looked up once per device.
+static int noalloc_scratch(void **out)
+{
+    static std::atomic<void *> ptrs[ddt::kNoAllocMaxDevices];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= ddt::kNoAllocMaxDevices) return DDTREE_ERR_HIP;
+    void *p = ptrs[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(ddt::scratch)) != hipSuccess || !p) return DDTREE_ERR_HIP;
+        ptrs[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return DDTREE_OK;
+}
+
 static int accept_impl(const float *target_logits, int batch, int T, int V, const int32_t *tokens,
                        const int32_t *parent, const int32_t *depth, const int32_t *n_nodes,
                        int32_t *path, int32_t *n_accepted, int32_t *bonus_token, int32_t *posterior,
@@ -333,6 +358,29 @@ extern "C" int ddtree_accept(const float *target_logits, int batch, int T, int V
 {
     return accept_impl(target_logits, batch, T, V, tokens, parent, depth, n_nodes, path, n_accepted,
                        bonus_token, posterior, B, workspace, workspace_bytes, stream, false,
+                       ddt::SampleArgs{0.0f, 0u, 0u});
+}
+
+extern "C" int ddtree_accept_noalloc(const float *target_logits, int batch, int T, int V,
+                                     const int32_t *tokens, const int32_t *parent, const int32_t *depth,
+                                     const int32_t *n_nodes, int32_t *path, int32_t *n_accepted,
+                                     int32_t *bonus_token, int32_t *posterior, int B, void *stream)
+{
+    using namespace ddt;
+    if (!target_logits || !tokens || !parent || !depth || !n_nodes || !path || !n_accepted || !bonus_token)
+        return DDTREE_ERR_ARG;
+    if (batch < 1 || batch > DDTREE_MAX_BATCH || T < 2 || T > DDTREE_MAX_N + 1 || V < 1 || B < 1 ||
+        B > DDTREE_MAX_B)
+        return DDTREE_ERR_ARG;
+    // the partials of this shape must fit the static array (nothing here can grow it)
+    if (accept_plan(batch, T, V, false).bytes > kNoAllocScratchBytes) return DDTREE_ERR_WORKSPACE;
+    void *ws = nullptr;
+    const int rc = noalloc_scratch(&ws);
+    if (rc != DDTREE_OK) return rc;
+    // Every partial the walk reads is written by the scan of the same call (rows up to n_nodes,
+    // all segments), so nothing in the array has to start at zero.
+    return accept_impl(target_logits, batch, T, V, tokens, parent, depth, n_nodes, path, n_accepted,
+                       bonus_token, posterior, B, ws, kNoAllocScratchBytes, stream, false,
                        ddt::SampleArgs{0.0f, 0u, 0u});
 }
 

@@ -121,6 +121,10 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     # accept: workspace too small, null outputs
     assert lib.ddtree_accept(p, 1, 257, 151936, p, p, p, p, p, p, p, None, 16, p, 16, None) == ERR_WS
     assert lib.ddtree_accept(p, 1, 257, 151936, p, p, p, p, None, p, p, None, 16, p, 4096, None) == ERR_ARG
+    # the variant with its scratch in the library's static array: null output, and a shape whose
+    # partials exceed the array (64 sequences of 1025 rows), refused before any GPU call
+    assert lib.ddtree_accept_noalloc(p, 1, 257, 151936, p, p, p, p, None, p, p, None, 16, None) == ERR_ARG
+    assert lib.ddtree_accept_noalloc(p, 64, 1025, 151936, p, p, p, p, p, p, p, None, 16, None) == ERR_WS
     # compact: bad element size
     dst = (ctypes.c_int32 * 1)(0)
     assert lib.ddtree_compact(p, p, p, p, ctypes.cast(dst, ctypes.c_void_p), 1, 17, 8, 1, 64, 3, p, p,
