@@ -35,20 +35,20 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 
-// Blocks of 32 query rows per wave.  1: eight waves of 32 rows, two waves per SIMD with 256
-// registers each, so that one wave's waits (LDS, matrix results, barrier) are filled by the other;
-// everything then fits the 256 architectural registers and no accumulation registers are used
-// (asking for any would make the compiler split the budget 128 / 128 and spill);
-// 2: four waves of 64 rows with 512 registers each (half the LDS reads per matrix instruction, but
-// nothing to fill a stall with; measured slower).
-constexpr int kCB = 1;
-constexpr int kWaves = 8 / kCB;
+// Eight waves of 32 query rows, two waves per SIMD with 256 registers each, so that one wave's
+// waits (LDS, matrix results, barrier) are filled by the other; everything fits the 256
+// architectural registers and no accumulation registers are used (asking for any would make the
+// compiler split the budget 128 / 128 and spill).  Four waves of 64 rows with 512 registers each
+// read half as much from LDS per matrix instruction but have nothing to fill a stall with
+// (measured slower, in the kernel and in a micro-benchmark of the loop alone).
+constexpr int kWaves = 8;
 constexpr int kAttnThreads = 64 * kWaves;
 constexpr int kKT = 64;        // keys per tile
 constexpr int kHD = 128;       // head dim of the MFMA path
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr int kAttnStages = 3;
+constexpr int kAttnStages = 4;  // a power of two: the stage of tile i is i & 3
 constexpr int kKRowBytes = 272;                  // K tile row in LDS: 256 B + 16 B pad (17 chunks)
 constexpr int kVRowBytes = 288;                  // V tile row in LDS: 256 B + 32 B pad (18 chunks)
 constexpr int kKTileBytes = kKT * kKRowBytes;    // 17408 = 17 DMA blocks of 1 KB
@@ -102,7 +102,7 @@ AttnPlan attn_plan(int batch, int T, int Hq, int Hkv, int D, long long sum_L, in
     // units with shorter key ranges.  Taken when everything fits one round and the model says so.
     const int full = nblk / 8, rem = nblk % 8;
     if (full >= 1 && rem >= 1 && rem <= 4 && tiles >= 1) {
-        const double c_tail = 0.5;
+        const double c_tail = 0.6;  // a key tile of the small tail tile against one of a whole tile (measured)
         best_cost *= 0.97;  // (with key ranges the uneven form goes through partials: it has to pay for them)
         const long long base_m = (long long)batch * Hkv * full, base_t = (long long)batch * Hkv;
         for (int Sm = 1; Sm <= 32; ++Sm) {
@@ -202,12 +202,13 @@ __device__ __forceinline__ void static_for(F &&f)
 // asm reads the waits are placed by hand: s_waitcnt vmcnt(0) + barrier once per tile for the
 // DMA, lds_wait_*() below for the reads (LDS reads return in order, so "at most N outstanding"
 // identifies exactly which of them have landed).
+// The destination of a read is tied to its previous value ("+v"): the read lands in the register
+// of the operand it replaces and cannot be scheduled above the matrix instruction that still
+// reads that operand.
 template <int OFF>
-__device__ __forceinline__ u32x4 lds_rd128(uint32_t addr)
+__device__ __forceinline__ void lds_rd128(u32x4 &v, uint32_t addr)
 {
-    u32x4 v;
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
-    return v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "+v"(v) : "v"(addr), "n"(OFF) : "memory");
 }
 // LDS transpose read (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane 4*j + r points
 // at four consecutive 16-bit elements; afterwards lane i of the group holds, for j = 0..3, element
@@ -215,36 +216,35 @@ __device__ __forceinline__ u32x4 lds_rd128(uint32_t addr)
 // lane i receives V[key_0..3][d0 + i]: a column of the row-major V tile, which is what the A
 // operand (V^T) of the second product needs.
 template <int OFF>
-__device__ __forceinline__ u32x2 lds_rdtr(uint32_t addr)
+__device__ __forceinline__ void lds_rdtr(u32x2 &v, uint32_t addr)
 {
-    u32x2 v;
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
-    return v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "+v"(v) : "v"(addr), "n"(OFF) : "memory");
 }
-// Wait until at most N LDS reads are outstanding; the operands tie the wait to the registers it
+// Wait for every outstanding LDS read of the wave; the operands tie the wait to the registers it
 // protects so that their uses cannot be scheduled above it.
-template <int N>
-__device__ __forceinline__ void lds_wait_k(u32x4 (&k)[8])
+__device__ __forceinline__ void lds_wait_all(u32x4 (&k)[8], u32x2 (&v)[2][4][2])
 {
-    asm volatile("s_waitcnt lgkmcnt(%8)"
-                 : "+v"(k[0]), "+v"(k[1]), "+v"(k[2]), "+v"(k[3]), "+v"(k[4]), "+v"(k[5]), "+v"(k[6]),
-                   "+v"(k[7])
-                 : "n"(N)
-                 : "memory");
-}
-template <int N>
-__device__ __forceinline__ void lds_wait_v(u32x2 (&v)[2][4][2])
-{
-    asm volatile("s_waitcnt lgkmcnt(%16)"
-                 : "+v"(v[0][0][0]), "+v"(v[0][0][1]), "+v"(v[0][1][0]), "+v"(v[0][1][1]),
-                   "+v"(v[0][2][0]), "+v"(v[0][2][1]), "+v"(v[0][3][0]), "+v"(v[0][3][1]),
-                   "+v"(v[1][0][0]), "+v"(v[1][0][1]), "+v"(v[1][1][0]), "+v"(v[1][1][1]),
-                   "+v"(v[1][2][0]), "+v"(v[1][2][1]), "+v"(v[1][3][0]), "+v"(v[1][3][1])
-                 : "n"(N)
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(k[0]), "+v"(k[1]), "+v"(k[2]), "+v"(k[3]), "+v"(k[4]), "+v"(k[5]), "+v"(k[6]), "+v"(k[7]),
+                   "+v"(v[0][0][0]), "+v"(v[0][0][1]), "+v"(v[0][1][0]), "+v"(v[0][1][1]), "+v"(v[0][2][0]),
+                   "+v"(v[0][2][1]), "+v"(v[0][3][0]), "+v"(v[0][3][1]), "+v"(v[1][0][0]), "+v"(v[1][0][1]),
+                   "+v"(v[1][1][0]), "+v"(v[1][1][1]), "+v"(v[1][2][0]), "+v"(v[1][2][1]), "+v"(v[1][3][0]),
+                   "+v"(v[1][3][1])
+                 :
                  : "memory");
 }
 
-constexpr float kRefSlack = 64.0f;  // log2 units a row's scores may exceed its softmax reference
+// Largest row sum (in units of 2^reference) a key range may end with: every single probability is
+// then at most 2^72, far inside what bf16 operands and fp32 accumulators carry exactly as well as
+// small ones.  A larger (or non-finite) sum means some score outgrew the row's reference by more
+// than that and the workgroup redoes its key range with the true row maxima as references.
+constexpr float kSumLimit = 0x1p72f;
+
+template <int N>
+__device__ __forceinline__ void vm_wait()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
 __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_cache,
@@ -291,7 +291,7 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     const int M = T * G;
     const int L0 = args.kv_start[seq];
     const int L = args.kv_len[seq];
-    // this tile's blocks of 32 rows: wave w owns blocks kCB*w .. kCB*w + kCB - 1 of the tile
+    // this tile's blocks of 32 rows: wave w owns block w of the tile
     const int first_blk = tail_splits > 0 ? mt * 8 : mt * blk_base + min(mt, blk_extra);
     const int n_blk = tail_splits > 0 ? (tail ? blk_extra : 8) : blk_base + (mt < blk_extra ? 1 : 0);
     const int m0 = first_blk * 32;
@@ -305,127 +305,121 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     // (nt < 2^25 key tiles and at most 32 key ranges: 32-bit arithmetic is exact)
     const int t_begin = (int)(((unsigned)nt * (unsigned)split + (unsigned)splits - 1u) / (unsigned)splits);
     const int t_end = (int)(((unsigned)nt * (unsigned)(split + 1) + (unsigned)splits - 1u) / (unsigned)splits);
-    const bool wave_active = m0 + wave * 32 * kCB < m_end;
+    const bool wave_active = m0 + wave * 32 < m_end;
 
-    // this lane's two query rows (cb = 0, 1)
-    int node_[kCB], rowg_[kCB];
-    bool rvalid[kCB];
-#pragma unroll
-    for (int cb = 0; cb < kCB; ++cb) {
-        const int r = m0 + wave * 32 * kCB + cb * 32 + l32;
-        rvalid[cb] = r < m_end;
-        const int node = rvalid[cb] ? r / G : 0;
-        const int g = rvalid[cb] ? r - node * G : 0;
-        node_[cb] = node;
-        rowg_[cb] = (seq * T + node) * Hq + hk * G + g;
-    }
+    // this lane's query row
+    const int row_m = m0 + wave * 32 + l32;
+    const bool rvalid = row_m < m_end;
+    const int node_ = rvalid ? row_m / G : 0;
+    const int rowg_ = (seq * T + node_) * Hq + hk * G + (rvalid ? row_m - node_ * G : 0);
     // Q^T operand: lane holds Q[row][16*ks + 8*half .. +8]
-    bf16x8 qreg[kCB][8];
-    bool real_[kCB];  // the row's node is a real tree node (it sees itself)
+    bf16x8 qreg[8];
 #pragma unroll
-    for (int cb = 0; cb < kCB; ++cb) {
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (rvalid[cb])
-                v = *reinterpret_cast<const uint4 *>(q + (size_t)rowg_[cb] * kHD + ks * 16 + half * 8);
-            qreg[cb][ks] = __builtin_bit_cast(bf16x8, v);
-        }
-        const int node = node_[cb];
-        real_[cb] = rvalid[cb] && ((mask[((size_t)seq * T + node) * W + (node >> 6)] >> (node & 63)) & 1ull);
+    for (int ks = 0; ks < 8; ++ks) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (rvalid) v = *reinterpret_cast<const uint4 *>(q + (size_t)rowg_ * kHD + ks * 16 + half * 8);
+        qreg[ks] = __builtin_bit_cast(bf16x8, v);
     }
+    const uint64_t *mask_row = mask + ((size_t)seq * T + node_) * W;
+    // the row's node is a real tree node (it sees itself); padding rows produce zeros
+    const bool real_ = rvalid && ((mask_row[node_ >> 6] >> (node_ & 63)) & 1ull);
 
-    floatx16 o[4][kCB];
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int cb = 0; cb < kCB; ++cb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[db][cb][v] = 0.0f;
-    float m_run[kCB];   // softmax reference of the row (log2 units)
-    float m_seen[kCB];  // true running maximum of the row
-    float l_run[kCB];
-#pragma unroll
-    for (int cb = 0; cb < kCB; ++cb) {
-        m_run[cb] = -INFINITY;
-        m_seen[cb] = -INFINITY;
-        l_run[cb] = 0.0f;
-    }
-    bool overflow = false;
-
-    // ---- tile loads: DMA block b (1 KB of LDS) is issued by wave b % kWaves; lane l of the block fills
+    // ---- tile loads: a K tile is 17 and a V tile 18 DMA blocks of 1 KB of LDS; lane l of block b fills
     //      16-byte slot u = 64*b + l, i.e. row u / chunks_per_row, chunk u % chunks_per_row.
-    //      The per-lane source offsets (bytes from the tile's first key) are computed once. ----
+    //      The blocks are dealt round-robin to the n_dma loading waves: all eight, or, in a workgroup
+    //      where at most two waves have query rows (the small tail tile), the six or seven waves
+    //      without any, so that the waves that compute issue no loads at all.  A loading wave
+    //      issues 2 K + 2 V blocks per tile plus at most one more of each: 4, 5 or 6 loads, the
+    //      same for whole and ragged tiles (see tiles_in_flight).  The per-lane source offsets
+    //      (bytes from the tile's first key) are computed once. ----
     const uint32_t row_bytes = (uint32_t)Hkv * kHD * 2;  // bytes between consecutive keys in global memory
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    constexpr int kFull = 16 / kWaves;
-    uint32_t k_src[kFull + 1], v_src[kFull + 1];   // block kWaves*i + wave
+    const int n_active = min(kWaves, (m_end - m0 + 31) >> 5);  // waves 0 .. n_active-1 have query rows
+    const bool offload = n_active <= 2;
+    const int n_dma = offload ? kWaves - n_active : kWaves;
+    const int dma_rank = offload ? wave_u - n_active : wave_u;  // negative: this wave loads nothing
+    const bool k_third = dma_rank >= 0 && 2 * n_dma + dma_rank < 17;
+    const bool v_third = dma_rank >= 0 && 2 * n_dma + dma_rank < 18;
+    const int dma_loads = dma_rank < 0 ? 0 : 4 + (k_third ? 1 : 0) + (v_third ? 1 : 0);
+    uint32_t k_src[3], v_src[3];   // of block n_dma*i + dma_rank
 #pragma unroll
-    for (int i = 0; i < kFull + 1; ++i) {
-        const int u = (kWaves * i + wave) * 64 + lane;
+    for (int i = 0; i < 3; ++i) {
+        const int u = (n_dma * i + max(dma_rank, 0)) * 64 + lane;
         const int rk = (u * 241) >> 12;   // u / 17 for u < 2048
         const int ck = u - rk * 17;
-        k_src[i] = (uint32_t)rk * row_bytes + (ck == 16 ? 0 : ck) * 16;  // padding slot: any chunk
+        k_src[i] = (uint32_t)min(rk, kKT - 1) * row_bytes + (ck == 16 ? 0 : ck) * 16;  // padding slot: any chunk
         const int rv = (u * 3641) >> 16;  // u / 18 for u < 2048
         const int cv = u - rv * 18;
-        v_src[i] = (uint32_t)rv * row_bytes + (cv >= 16 ? 0 : cv) * 16;
+        v_src[i] = (uint32_t)min(rv, kKT - 1) * row_bytes + (cv >= 16 ? 0 : cv) * 16;
     }
+    // first cache row and first tree row of this (sequence, kv head), as byte addresses; a tile is
+    // kKT consecutive keys, tile_bytes apart (the cache bases are formed but never used when the
+    // sequence has no cache rows)
+    const unsigned char *const kc0 = reinterpret_cast<const unsigned char *>(k_cache) + ((size_t)L0 * Hkv + hk) * (kHD * 2);
+    const unsigned char *const vc0 = reinterpret_cast<const unsigned char *>(v_cache) + ((size_t)L0 * Hkv + hk) * (kHD * 2);
+    const unsigned char *const kt0 = reinterpret_cast<const unsigned char *>(k_tree) + ((size_t)seq * T * Hkv + hk) * (kHD * 2);
+    const unsigned char *const vt0 = reinterpret_cast<const unsigned char *>(v_tree) + ((size_t)seq * T * Hkv + hk) * (kHD * 2);
+    const uint32_t tile_bytes = (uint32_t)kKT * row_bytes;
     auto issue_tile = [&](int tt, int stage) __attribute__((always_inline)) {
         const bool cache = tt < n_cache_tiles;
         const int tl = cache ? tt : tt - n_cache_tiles;
-        const size_t row0 = (cache ? (size_t)L0 : (size_t)seq * T) + (size_t)tl * kKT;
-        const unsigned char *kp =
-            reinterpret_cast<const unsigned char *>((cache ? k_cache : k_tree) + (row0 * Hkv + hk) * kHD);
-        const unsigned char *vp =
-            reinterpret_cast<const unsigned char *>((cache ? v_cache : v_tree) + (row0 * Hkv + hk) * kHD);
+        const uint64_t toff = (uint64_t)(uint32_t)tl * tile_bytes;
+        const unsigned char *kp = (cache ? kc0 : kt0) + toff;
+        const unsigned char *vp = (cache ? vc0 : vt0) + toff;
         const int valid_ = min(kKT, (cache ? L : T) - tl * kKT);
         unsigned char *st = smem + stage * kStageBytes;
+        // Every load is written as (uniform 64-bit base) + (32-bit lane offset), the form that
+        // takes the base in scalar registers; the offsets pass through an empty asm so that their
+        // widening to 64 bits stays next to the load instead of being kept, widened, in a pair of
+        // vector registers each for the whole kernel.
+        auto dma = [&](const unsigned char *base, uint32_t off, unsigned char *dst) __attribute__((always_inline)) {
+            asm volatile("" : "+v"(off));
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(base + off),
+                                             (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+        };
+        if (dma_rank < 0) return;
         if (valid_ == kKT) {
 #pragma unroll
-            for (int i = 0; i < kFull; ++i) {
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kp + k_src[i]),
-                                                 (__attribute__((address_space(3))) void *)(st + (kWaves * i + wave_u) * 1024),
-                                                 16, 0, 0);
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)(vp + v_src[i]),
-                    (__attribute__((address_space(3))) void *)(st + kKTileBytes + (kWaves * i + wave_u) * 1024), 16, 0, 0);
+            for (int i = 0; i < 2; ++i) {
+                dma(kp, k_src[i], st + (n_dma * i + dma_rank) * 1024);
+                dma(vp, v_src[i], st + kKTileBytes + (n_dma * i + dma_rank) * 1024);
             }
-            if (wave_u < 1)  // K: 17 blocks
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kp + k_src[kFull]),
-                                                 (__attribute__((address_space(3))) void *)(st + 16 * 1024), 16, 0, 0);
-            if (wave_u < 2)  // V: 18 blocks
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)(vp + v_src[kFull]),
-                    (__attribute__((address_space(3))) void *)(st + kKTileBytes + (16 + wave_u) * 1024), 16, 0, 0);
+            if (k_third) dma(kp, k_src[2], st + (2 * n_dma + dma_rank) * 1024);
+            if (v_third) dma(vp, v_src[2], st + kKTileBytes + (2 * n_dma + dma_rank) * 1024);
         } else {
             // ragged tile (at most two per key range): rows past the end re-read the last valid
             // row, so that the LDS tile holds finite data everywhere
 #pragma unroll 1
-            for (int i = 0; i < kFull + 1; ++i) {
-                const int blk = kWaves * i + wave_u;
+            for (int i = 0; i < 3; ++i) {
+                const int blk = n_dma * i + dma_rank;
                 const int u = blk * 64 + lane;
                 if (blk < 17) {
                     const int r = (u * 241) >> 12, c = u - r * 17;
-                    const uint32_t off = (uint32_t)min(r, valid_ - 1) * row_bytes + (c == 16 ? 0 : c) * 16;
-                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kp + off),
-                                                     (__attribute__((address_space(3))) void *)(st + blk * 1024), 16, 0, 0);
+                    dma(kp, (uint32_t)min(r, valid_ - 1) * row_bytes + (c == 16 ? 0 : c) * 16, st + blk * 1024);
                 }
                 if (blk < 18) {
                     const int r = (u * 3641) >> 16, c = u - r * 18;
-                    const uint32_t off = (uint32_t)min(r, valid_ - 1) * row_bytes + (c >= 16 ? 0 : c) * 16;
-                    __builtin_amdgcn_global_load_lds(
-                        (const __attribute__((address_space(1))) void *)(vp + off),
-                        (__attribute__((address_space(3))) void *)(st + kKTileBytes + blk * 1024), 16, 0, 0);
+                    dma(vp, (uint32_t)min(r, valid_ - 1) * row_bytes + (c >= 16 ? 0 : c) * 16,
+                        st + kKTileBytes + blk * 1024);
                 }
             }
         }
+    };
+    // Wait until at most the `n` most recently requested tiles of this wave may still be in
+    // flight (vector memory operations complete in order, and a tile is dma_loads of them for
+    // this wave): everything requested before them has landed.
+    auto tiles_in_flight = [&](int n) __attribute__((always_inline)) {
+        if (n <= 0 || dma_loads == 0) vm_wait<0>();
+        else if (dma_loads == 6) { if (n == 1) vm_wait<6>(); else vm_wait<12>(); }
+        else if (dma_loads == 5) { if (n == 1) vm_wait<5>(); else vm_wait<10>(); }
+        else { if (n == 1) vm_wait<4>(); else vm_wait<8>(); }
     };
 
     // per-lane LDS read bases (bytes, relative to the tile); everything else is an immediate
     const int k_base = l32 * kKRowBytes + half * 16;  // K: row l32 (+32*kb), column 2*ks + half
     const int lm = lane & 15, dim16 = (lane >> 4) & 1;
     // V: row 4*half + lm/4 (+16*kstep, +8), dims 32*db + 16*dim16 + 4*(lm%4)
-    const int v_base = (4 * half + (lm >> 2)) * kVRowBytes + 32 * dim16 + 8 * (lm & 3);
+    const int v_base = kKTileBytes + (4 * half + (lm >> 2)) * kVRowBytes + 32 * dim16 + 8 * (lm & 3);
 
     const uint32_t lds_base =
         (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
@@ -435,208 +429,213 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     // V columns of one sub-tile (2 k-steps x 4 dim blocks x 2 transposing reads).
     u32x4 kbuf[8];
     u32x2 vbuf[2][4][2];
-    floatx16 sc[kCB];     // scores of the sub-tile in flight, per query block cb
-    bf16x8 pb[2][kCB][2];  // P^T operands, double buffered by sub-tile parity: [parity][cb][k-step]
+#pragma unroll
+    for (int i = 0; i < 8; ++i) kbuf[i] = (u32x4){0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) vbuf[a][b][0] = vbuf[a][b][1] = (u32x2){0u, 0u};
+    floatx16 o[4];      // O^T accumulators, one per block of 32 output dims
+    floatx16 s_a, s_b;  // scores of two consecutive sub-tiles (one being turned into P, one being formed)
+    uint32_t p_a[8], p_b[8];  // P^T operands of two consecutive sub-tiles, bf16 pairs
+    float m_ref = -INFINITY;   // softmax reference of the row (log2 units): fixed by its first visible keys
+    float m_seen = -INFINITY;  // true running maximum, tracked only by the first pass of a retry
+    // Row sums of P, taken by the matrix cores from the very bf16 values that multiply V: one
+    // v_mfma_f32_16x16x32_bf16 per k-step whose B operand is the P^T operand as it stands and whose
+    // A operand selects, for output row 0, the lanes that hold query rows 0-15 (lanes 0-15 and 32-47
+    // of the P^T registers: k-groups 0 and 2 of the smaller shape) and, for output row 1, those that
+    // hold query rows 16-31 (k-groups 1 and 3).  Lane j < 16 then holds the sum of query row j in
+    // register 0 and that of row 16 + j in register 1.
+    floatx4 l_acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    const uint32_t sel_bits = (lane == 0 || lane == 32 || lane == 17 || lane == 49) ? 0x3f803f80u : 0u;
+    const bf16x8 sel = __builtin_bit_cast(bf16x8, (u32x4){sel_bits, sel_bits, sel_bits, sel_bits});
+    auto row_sum = [&]() __attribute__((always_inline)) {
+        const float lo = __shfl(l_acc[0], l32 & 15, 64), hi = __shfl(l_acc[1], l32 & 15, 64);
+        return l32 < 16 ? lo : hi;
+    };
 
-    // K operand reads of sub-tile kb of the tile at LDS address tile_addr
-    auto issue_k = [&](uint32_t tile_addr, auto KB) __attribute__((always_inline)) {
-        static_for<0, 8>([&](auto KS) {
-            kbuf[KS.value] = lds_rd128<decltype(KB)::value * 32 * kKRowBytes + KS.value * 32>(tile_addr);
-        });
-    };
-    // V operand reads of sub-tile kb: key rows 32*kb + 16*t2 + 4*half + vj (+8)
-    auto issue_v = [&](uint32_t tile_addr, auto KB) __attribute__((always_inline)) {
-        static_for<0, 2>([&](auto T2) {
-            static_for<0, 4>([&](auto DB) {
-                constexpr int off = (2 * decltype(KB)::value + T2.value) * 16 * kVRowBytes + DB.value * 64;
-                vbuf[T2.value][DB.value][0] = lds_rdtr<off>(tile_addr);
-                vbuf[T2.value][DB.value][1] = lds_rdtr<off + 8 * kVRowBytes>(tile_addr);
-            });
-        });
-    };
-    // S^T sub-tile = K Q^T from the staged K operands
-    auto qk = [&](floatx16 (&sd)[kCB]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int cb = 0; cb < kCB; ++cb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) sd[cb][v] = 0.0f;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 a = __builtin_bit_cast(bf16x8, kbuf[ks]);
-#pragma unroll
-            for (int cb = 0; cb < kCB; ++cb)
-                sd[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[cb][ks], sd[cb], 0, 0, 0);
-        }
-    };
-    // Mask (apply_mask: tree tiles and ragged ends only; kb selects the half of the tile's 64-bit
-    // mask word) and softmax of one sub-tile (32 keys): sd -> P^T operands, updating m_run /
-    // l_run and flagging rows that outgrow their reference.
-    auto apply_mask = [&](floatx16 (&sd)[kCB], int t, int kb) __attribute__((always_inline)) {
-        const bool is_tree = t >= n_cache_tiles;
-        const int tb = t - n_cache_tiles;
-        const int valid = is_tree ? min(kKT, T - tb * kKT) : min(kKT, L - t * kKT);
-        if (is_tree || valid < kKT) {  // tree tiles and a ragged last cache tile only
-#pragma unroll
-            for (int cb = 0; cb < kCB; ++cb) {
+    // One step of the software pipeline, sub-tile j (32 keys) of tile t:
+    //   matrix cores   S(j+1) = K Q^T  (8 instructions)  and  O += V^T P(j-1)  (8 instructions), alternating
+    //   vector ALUs    P(j) = 2^(S(j) * scale - reference), its row sum, bf16 pairs
+    //   LDS            operands K(j+2) and V(j), each requested right behind the matrix instruction
+    //                  that consumed the register it lands in
+    // so that every matrix instruction has its share of the softmax (fma, exp, add, half a
+    // conversion) issued in its shadow.  Slow steps (tiles with masked keys, the first tile of a key
+    // range, retries) first apply the mask and fix the reference of rows that see their first key.
+    auto step = [&](bool slow, floatx16 &cur, floatx16 &nxt, uint32_t (&pin)[8], uint32_t (&pout)[8],
+                    uint32_t k_addr, uint32_t v_addr, int t, int kb, bool track, auto &&early) __attribute__((always_inline)) {
+        lds_wait_all(kbuf, vbuf);
+        if (slow) {
+            const bool is_tree = t >= n_cache_tiles;
+            const int tb = t - n_cache_tiles;
+            const int valid = is_tree ? min(kKT, T - tb * kKT) : min(kKT, L - t * kKT);
+            if (is_tree || valid < kKT) {  // tree tiles and a ragged last cache tile
                 uint64_t word = ~0ull;
-                if (is_tree) word = rvalid[cb] ? mask[((size_t)seq * T + node_[cb]) * W + tb] : 0ull;
+                if (is_tree) word = rvalid ? mask_row[tb] : 0ull;
                 if (valid < kKT) word &= (1ull << valid) - 1ull;
-                const uint32_t w32 = (uint32_t)(word >> (32 * kb));
+                // this lane's keys of the sub-tile: 8 * (v / 4) + 4 * half + v % 4
+                const uint32_t w32 = (uint32_t)(word >> (32 * kb)) >> (4 * half);
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int key = (v >> 2) * 8 + half * 4 + (v & 3);
-                    if (!((w32 >> key) & 1u)) sd[cb][v] = -INFINITY;
-                }
+                for (int v = 0; v < 16; ++v)
+                    if (!((w32 >> ((v >> 2) * 8 + (v & 3))) & 1u)) cur[v] = -INFINITY;
             }
-        }
-    };
-    auto softmax = [&](floatx16 (&sd)[kCB], bf16x8 (&pout)[kCB][2]) __attribute__((always_inline)) {
+            float tmax = cur[0];
 #pragma unroll
-        for (int cb = 0; cb < kCB; ++cb) {
-            float tmax = sd[cb][0];
-#pragma unroll
-            for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, sd[cb][v]);
+            for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, cur[v]);
             // the other half-wave holds the other 16 keys of this row
             const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax),
                                                              false, false);
-            tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-            // The softmax reference of a row is fixed by its first visible key and never moved, so
-            // the accumulators are never rescaled: exp2 arguments may become positive, which
-            // fp32 and bf16 carry exactly as well as negative ones.  Only a row whose scores
-            // outgrow the reference by more than kRefSlack makes the workgroup redo its key
-            // range once, with the true maxima as references (see the retry loop).
-            m_seen[cb] = fmaxf(m_seen[cb], tmax * scale_log2e);
-            m_run[cb] = m_run[cb] == -INFINITY ? m_seen[cb] : m_run[cb];
-            overflow |= m_seen[cb] > m_run[cb] + kRefSlack;
-            const float m_use = m_run[cb] == -INFINITY ? 0.0f : m_run[cb];
-            // p = 2^(s*scale - reference), rounded to bf16 in pairs; the row sum is taken over
-            // the rounded values (the same ones that multiply V) with one dot2 per pair
-            float psum = 0.0f;
-            uint32_t pk[8];
-#pragma unroll
-            for (int v2 = 0; v2 < 8; ++v2) {
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(sd[cb][2 * v2], scale_log2e, -m_use));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(sd[cb][2 * v2 + 1], scale_log2e, -m_use));
-                pk[v2] = f2bf_pair(p0, p1);
-                psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk[v2]),
-                                                       __builtin_bit_cast(bf16x2, 0x3f803f80u), psum, false);
-            }
-            l_run[cb] += psum;
-#pragma unroll
-            for (int t2 = 0; t2 < 2; ++t2)
-                pout[cb][t2] = __builtin_bit_cast(
-                    bf16x8, (u32x4){pk[4 * t2], pk[4 * t2 + 1], pk[4 * t2 + 2], pk[4 * t2 + 3]});
+            tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1])) * scale_log2e;
+            if (track) m_seen = fmaxf(m_seen, tmax);
+            m_ref = m_ref == -INFINITY ? tmax : m_ref;
         }
-    };
-    // O^T += V^T P^T for one sub-tile.  Element j of the P^T operand of k-step t2 is key
-    // 16*t2 + 8*(j/4) + 4*half + j%4 of the sub-tile; the two transposing reads fetched those keys.
-    auto pv = [&](bf16x8 (&pin)[kCB][2]) __attribute__((always_inline)) {
+        // The reference is never moved, so the accumulators are never rescaled: exp2 arguments may
+        // become positive, which fp32 and bf16 carry exactly as well as negative ones.
+        const float m_use = m_ref == -INFINITY ? 0.0f : m_ref;
+        static_for<0, 8>([&](auto I) {
+            constexpr int i = decltype(I)::value;
+            {
+                const bf16x8 a = __builtin_bit_cast(bf16x8, kbuf[i]);
+                if constexpr (i == 0) {
+                    floatx16 z;
 #pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-            for (int db = 0; db < 4; ++db) {
+                    for (int v = 0; v < 16; ++v) z[v] = 0.0f;
+                    nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[i], z, 0, 0, 0);
+                } else {
+                    nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[i], nxt, 0, 0, 0);
+                }
+                lds_rd128<i * 32>(kbuf[i], k_addr);
+            }
+            float e0 = __builtin_amdgcn_exp2f(fmaf(cur[2 * i], scale_log2e, -m_use));
+            // (the empty asm statements pin the softmax arithmetic to its slot: without them the
+            // optimiser sinks it past the slot boundaries towards its first use in the next step)
+            asm volatile("" : "+v"(e0));
+            __builtin_amdgcn_sched_barrier(0);
+            {
+                // element j of the P^T operand of k-step t2 is key 16*t2 + 8*(j/4) + 4*half + j%4 of the
+                // sub-tile; the two transposing reads fetched those keys
+                constexpr int t2 = i / 4, db = i % 4;
                 const bf16x8 a = __builtin_bit_cast(
                     bf16x8, (u32x4){vbuf[t2][db][0].x, vbuf[t2][db][0].y, vbuf[t2][db][1].x, vbuf[t2][db][1].y});
-#pragma unroll
-                for (int cb = 0; cb < kCB; ++cb)
-                    o[db][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pin[cb][t2], o[db][cb], 0, 0, 0);
+                const bf16x8 b = __builtin_bit_cast(
+                    bf16x8, (u32x4){pin[4 * t2], pin[4 * t2 + 1], pin[4 * t2 + 2], pin[4 * t2 + 3]});
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, o[db], 0, 0, 0);
+                if constexpr (db == 3) l_acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sel, b, l_acc, 0, 0, 0);
+                lds_rdtr<t2 * 16 * kVRowBytes + db * 64>(vbuf[t2][db][0], v_addr);
+                lds_rdtr<(t2 * 16 + 8) * kVRowBytes + db * 64>(vbuf[t2][db][1], v_addr);
             }
+            const float e1 = __builtin_amdgcn_exp2f(fmaf(cur[2 * i + 1], scale_log2e, -m_use));
+            pout[i] = f2bf_pair(e0, e1);
+            asm volatile("" : "+v"(pout[i]));
+            __builtin_amdgcn_sched_barrier(0);
+            // work that only has to happen some time during the step (the next tile request: scalar
+            // address arithmetic and a handful of loads) goes behind the first slots, where the
+            // other wave of the SIMD keeps the matrix cores busy meanwhile
+            if constexpr (i == 1) {
+                early();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        });
     };
 
-    // Scheduling request for the phases that pair a P V product with a softmax: one matrix
-    // instruction, then half a dozen vector instructions, once per matrix instruction, so that the vector work runs
-    // in the shadow of the matrix pipeline instead of after it.
-    auto interleave_mfma_valu = [&]() __attribute__((always_inline)) {
+    // ---- the key range, up to three times: once normally; if some row's sum shows that its
+    //      scores outgrew the reference, once more to find the true row maxima and a last time with
+    //      those as references (rare) ----
+    for (int pass = 0;; ++pass) {
+        const bool all_slow = pass > 0, track = pass == 1;
 #pragma unroll
-        for (int i = 0; i < 8 * kCB; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);   // VALU  // VALU
-        }
-    };
-    // ---- software pipeline over 32-key sub-tiles j = (tile, half), three LDS stages ----
-    // The matrix cores alternate between the scores of sub-tile j and the P V product of sub-tile
-    // j-1; the vector ALUs do the softmax of sub-tile j while that P V product runs:
-    //   A: S = K Q^T of (t, 0)
-    //   B: O += P V of (t-1, 1)   ||  softmax of (t, 0)
-    //   -- tile t+1 has landed (vmcnt + barrier); tile t+2 is requested into the stage that
-    //      (t-1) occupied, whose last reader was phase B
-    //   C: S = K Q^T of (t, 1)
-    //   D: O += P V of (t, 0)     ||  softmax of (t, 1)
-    // LDS operands are requested one phase before the product that consumes them.
-    for (;;) {
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[db][v] = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) p_b[i] = 0u;
+        l_acc = (floatx4){0.0f, 0.0f, 0.0f, 0.0f};
+        // Ring of four stages: while the keys of tile `it` are worked on, tile it+1 is resident
+        // (its K operands are requested one sub-tile ahead), tile it+2 is in flight and tile it+3
+        // is requested into the stage that tile it-1 has just left.
         if (n_tiles > 0) issue_tile(t_begin, 0);
         if (n_tiles > 1) issue_tile(t_begin + 1, 1);
-        __builtin_amdgcn_s_waitcnt(0);
+        if (n_tiles > 2) issue_tile(t_begin + 2, 2);
+        tiles_in_flight(n_tiles > 2 ? 1 : 0);  // tiles 0 and 1 have landed
         __syncthreads();
-        if (wave_active && n_tiles > 0) issue_k(lds_base + k_base, IC<0>{});
+        if (wave_active && n_tiles > 0) {
+            // S(0) on its own, then the operands the first step expects: K(1), and V(0) standing in
+            // for the V(-1) that does not exist (P(-1) is zero)
+            static_for<0, 8>([&](auto I) { lds_rd128<decltype(I)::value * 32>(kbuf[decltype(I)::value], lds_base + k_base); });
+            lds_wait_all(kbuf, vbuf);
+            static_for<0, 8>([&](auto I) {
+                constexpr int i = decltype(I)::value;
+                const bf16x8 a = __builtin_bit_cast(bf16x8, kbuf[i]);
+                if constexpr (i == 0) {
+                    floatx16 z;
 #pragma unroll
-        for (int cb = 0; cb < kCB; ++cb)
-#pragma unroll
-            for (int t2 = 0; t2 < 2; ++t2) pb[1][cb][t2] = __builtin_bit_cast(bf16x8, (u32x4){0u, 0u, 0u, 0u});
-        int st = 0;  // LDS stage of tile `it` (it % kAttnStages, kept without a division)
+                    for (int v = 0; v < 16; ++v) z[v] = 0.0f;
+                    s_a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[i], z, 0, 0, 0);
+                } else {
+                    s_a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[i], s_a, 0, 0, 0);
+                }
+                lds_rd128<i * 32>(kbuf[i], lds_base + k_base + 32 * kKRowBytes);
+            });
+            static_for<0, 8>([&](auto I) {
+                constexpr int t2 = decltype(I)::value / 4, db = decltype(I)::value % 4;
+                lds_rdtr<t2 * 16 * kVRowBytes + db * 64>(vbuf[t2][db][0], lds_base + v_base);
+                lds_rdtr<(t2 * 16 + 8) * kVRowBytes + db * 64>(vbuf[t2][db][1], lds_base + v_base);
+            });
+        }
         for (int it = 0; it < n_tiles; ++it) {
             const int t = t_begin + it;
-            const int st_prev = st == 0 ? kAttnStages - 1 : st - 1;
-            const int st_next = st == kAttnStages - 1 ? 0 : st + 1;
-            const uint32_t stage_addr = lds_base + st * kStageBytes;
-            const uint32_t prev_addr = lds_base + st_prev * kStageBytes;
+            const uint32_t stage_addr = lds_base + (it & (kAttnStages - 1)) * kStageBytes;
             // when there is no next tile the K operands are re-read from this one and never used:
             // the control flow stays the same for the last tile
-            const uint32_t next_addr = it + 1 < n_tiles ? lds_base + st_next * kStageBytes : stage_addr;
-            if (wave_active) {
-                // ---- A ----
-                lds_wait_k<0>(kbuf);
-                // the first tile has no predecessor: its P operands are zero and the V operands
-                // are read from the tile itself, so that 0 * V is a plain zero
-                issue_v((it > 0 ? prev_addr : stage_addr) + kKTileBytes + v_base, IC<1>{});
-                qk(sc);
-                apply_mask(sc, t, 0);
-                // ---- B ----
-                lds_wait_v<0>(vbuf);
-                issue_k(stage_addr + k_base, IC<1>{});
-                pv(pb[1]);
-                softmax(sc, pb[0]);
-                interleave_mfma_valu();
+            const uint32_t next_addr = it + 1 < n_tiles ? lds_base + ((it + 1) & (kAttnStages - 1)) * kStageBytes : stage_addr;
+            if (it > 0) {
+                // Tile it+1 has landed (this wave's share; the barrier makes it everyone's) and
+                // nobody reads tile it-1 any more: its stage takes tile it+3.
+                if (wave_active) lds_wait_all(kbuf, vbuf);
+                tiles_in_flight(it + 2 < n_tiles ? 1 : 0);
+                __syncthreads();
             }
-            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile t+1 is in LDS
-            __syncthreads();
-            if (it + 2 < n_tiles) issue_tile(t + 2, st_prev);  // (it + 2) % 3 == (it - 1) % 3
+            auto request = [&]() __attribute__((always_inline)) {
+                if (it + 3 < n_tiles) issue_tile(t + 3, (it + 3) & (kAttnStages - 1));
+            };
+            if (!wave_active) request();
             if (wave_active) {
-                // ---- C ----
-                lds_wait_k<0>(kbuf);
-                issue_v(stage_addr + kKTileBytes + v_base, IC<0>{});
-                qk(sc);
-                apply_mask(sc, t, 1);
-                // ---- D ----
-                lds_wait_v<0>(vbuf);
-                issue_k(next_addr + k_base, IC<0>{});
-                pv(pb[0]);
-                softmax(sc, pb[1]);
-                interleave_mfma_valu();
+                const bool slow = all_slow || it == 0 || t >= n_cache_tiles || (t == n_cache_tiles - 1 && (L & (kKT - 1)) != 0);
+                // sub-tile (t, 0): forms S(t, 1), multiplies P(t-1, 1); requests K(t+1, 0) and V(t, 0)
+                // sub-tile (t, 1): forms S(t+1, 0), multiplies P(t, 0); requests K(t+1, 1) and V(t, 1)
+                step(slow, s_a, s_b, p_b, p_a, next_addr + k_base, stage_addr + v_base, t, 0, track, request);
+                step(slow, s_b, s_a, p_a, p_b, next_addr + k_base + 32 * kKRowBytes,
+                     stage_addr + v_base + 32 * kVRowBytes, t, 1, track, []() {});
             }
-            st = st_next;
         }
         if (wave_active && n_tiles > 0) {
             // drain: P V of the last sub-tile
-            lds_wait_k<0>(kbuf);
-            const uint32_t last_addr = lds_base + (st == 0 ? kAttnStages - 1 : st - 1) * kStageBytes;
-            issue_v(last_addr + kKTileBytes + v_base, IC<1>{});
-            lds_wait_v<0>(vbuf);
-            pv(pb[1]);
+            lds_wait_all(kbuf, vbuf);
+#pragma unroll
+            for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+                for (int db = 0; db < 4; ++db) {
+                    const bf16x8 a = __builtin_bit_cast(
+                        bf16x8, (u32x4){vbuf[t2][db][0].x, vbuf[t2][db][0].y, vbuf[t2][db][1].x, vbuf[t2][db][1].y});
+                    const bf16x8 b = __builtin_bit_cast(
+                        bf16x8, (u32x4){p_b[4 * t2], p_b[4 * t2 + 1], p_b[4 * t2 + 2], p_b[4 * t2 + 3]});
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, o[db], 0, 0, 0);
+                    if (db == 3) l_acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sel, b, l_acc, 0, 0, 0);
+                }
         }
-        // Retry (rare): some row outgrew its reference.  All tiles have been seen, so m_seen holds
-        // the true row maxima; with those as references the second pass cannot outgrow anything.
-        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): no LDS read of this wave is still in flight
-        if (!__syncthreads_or(overflow ? 1 : 0)) break;
-        overflow = false;
-#pragma unroll
-        for (int cb = 0; cb < kCB; ++cb) {
-            m_run[cb] = m_seen[cb];
-            l_run[cb] = 0.0f;
-#pragma unroll
-            for (int db = 0; db < 4; ++db)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) o[db][cb][v] = 0.0f;
+        // no DMA and no LDS read of this wave is still in flight; behind the barrier that holds for
+        // the workgroup, and the ring may be filled again (or reused by the epilogue)
+        __builtin_amdgcn_s_waitcnt(0);
+        if (pass == 0) {
+            const float l_tot = row_sum();
+            const bool outgrown = wave_active && !(l_tot <= kSumLimit);  // also true for inf and NaN
+            if (!__syncthreads_or(outgrown ? 1 : 0)) break;
+            m_ref = -INFINITY;
+            m_seen = -INFINITY;
+        } else {
+            __syncthreads();
+            if (pass == 2) break;
+            m_ref = m_seen;  // the true row maxima: nothing can outgrow them
         }
     }
 
@@ -646,30 +645,29 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     // there a row would leave in 32 pieces.  The block is staged row-major in this wave's share
     // of the ring (idle now: every wave has passed the barrier above with its tiles consumed, and
     // no DMA is in flight) and leaves in whole rows, 16 bytes per lane and four rows per store.
-    static_assert(kCB == 1, "the staged epilogue handles one block per wave");
     constexpr int kEpiRow = kHD * 2 + 16;  // bytes per staged row: 16-byte aligned, rows 4 banks apart
     static_assert(kWaves * 32 * kEpiRow <= kAttnLdsBytes, "staging fits the ring");
     unsigned char *stg = smem + wave * (32 * kEpiRow);
     const size_t n_rows = (size_t)batch_n * T * Hq;
     {
-        const float l_tot = l_run[0] + __shfl_xor(l_run[0], 32, 64);
-        const float inv = (rvalid[0] && real_[0] && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
+        const float l_tot = row_sum();
+        const float inv = (rvalid && real_ && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
                 const int dim = db * 32 + g4 * 8 + half * 4;
-                const float a0 = o[db][0][4 * g4 + 0] * inv, a1 = o[db][0][4 * g4 + 1] * inv;
-                const float a2 = o[db][0][4 * g4 + 2] * inv, a3 = o[db][0][4 * g4 + 3] * inv;
+                const float a0 = o[db][4 * g4 + 0] * inv, a1 = o[db][4 * g4 + 1] * inv;
+                const float a2 = o[db][4 * g4 + 2] * inv, a3 = o[db][4 * g4 + 3] * inv;
                 uint2 val;  // bf16 for the output itself, fp16 for the partial of a key range
                 val.x = part_splits == 0 ? f2bf_pair(a0, a1) : f2h_pair(a0, a1);
                 val.y = part_splits == 0 ? f2bf_pair(a2, a3) : f2h_pair(a2, a3);
                 *reinterpret_cast<uint2 *>(stg + l32 * kEpiRow + dim * 2) = val;
             }
-        if (part_splits != 0 && rvalid[0] && half == 0) {
+        if (part_splits != 0 && rvalid && half == 0) {
             // log2-sum-exp of this key range, indexed by global row
-            const size_t ridx = (size_t)rowg_[0];
-            lse[(size_t)split * n_rows + ridx] = inv > 0.0f ? m_run[0] + __builtin_amdgcn_logf(l_tot) : -INFINITY;
+            const size_t ridx = (size_t)rowg_;
+            lse[(size_t)split * n_rows + ridx] = inv > 0.0f ? m_ref + __builtin_amdgcn_logf(l_tot) : -INFINITY;
             // key ranges this tile does not have (the other kind of tile has more): empty
             if (split == 0)
                 for (int sx = splits; sx < part_splits; ++sx) lse[(size_t)sx * n_rows + ridx] = -INFINITY;
