@@ -142,7 +142,9 @@ int ddtree_build(const int32_t *topk_tok, const float *topk_lp, int batch, int B
  *                                               zero but is still multiplied (0 * NaN = NaN)
  *   ancestor_mask    [device] uint64 [batch, T, W]
  *   kv_offset        [host]   int32 [batch+1], non-decreasing, kv_offset[0] >= 0
- *   dtype      DDTREE_DTYPE_BF16 (bf16 in/out, fp32 accumulation and softmax) or
+ *   dtype      DDTREE_DTYPE_BF16 (bf16 in/out, fp32 accumulation and softmax; any finite bf16
+ *              values: partial results of split key ranges are kept relative to their row's
+ *              magnitude, so large value rows do not overflow on the way) or
  *              DDTREE_DTYPE_FP32 (fp32 throughout)
  *   out        [device] [batch*T, Hq, D], same dtype as q
  * Requires Hq % Hkv == 0, D a multiple of 8 and <= 256, T <= DDTREE_MAX_N + 1,

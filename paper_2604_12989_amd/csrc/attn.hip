@@ -131,7 +131,7 @@ AttnPlan attn_plan(int batch, int T, int Hq, int Hkv, int D, long long sum_L, in
         p.part_off = off;
         off = align_up(off + (size_t)p.part_splits * rows * D * 2, 256);  // fp16 partials
         p.lse_off = off;
-        off = align_up(off + (size_t)p.part_splits * rows * 4, 256);
+        off = align_up(off + (size_t)p.part_splits * rows * 8, 256);      // (log2-sum-exp, scale) per row
     }
     p.bytes = off;
     return p;
@@ -158,7 +158,7 @@ size_t attn_ws_upper(int batch, int T, int Hq, int Hkv, int D)
     if (cap <= 1 && !uneven_possible) return p.bytes;
     const size_t rows = (size_t)batch * T * Hq;
     size_t off = align_up((size_t)cap * rows * D * 2, 256);
-    off = align_up(off + (size_t)cap * rows * 4, 256);
+    off = align_up(off + (size_t)cap * rows * 8, 256);
     return off > p.bytes ? off : p.bytes;
 }
 
@@ -253,7 +253,7 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                       AttnArgs args, int batch_n, int T, int Hq, int Hkv, float scale_log2e, int n_tiles_m,
                       int blk_base, int blk_extra, int main_splits, int tail_splits, int part_splits,
                       uint16_t *__restrict__ out,
-                      uint16_t *__restrict__ part, float *__restrict__ lse)
+                      uint16_t *__restrict__ part, float2 *__restrict__ lse)
 {
     // LDS: kAttnStages stages of {K tile, V tile}, filled by direct global->LDS loads.  One wave
     // instruction writes 64 x 16 B contiguously, but every lane may fetch any 16-byte chunk, so
@@ -652,25 +652,40 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     {
         const float l_tot = row_sum();
         const float inv = (rvalid && real_ && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
+        // The partial of a key range is stored as fp16 relative to the largest magnitude of its
+        // row (so that it fits whatever the values are: bf16 inputs reach 3e38, fp16 65504), with
+        // that magnitude kept beside the log2-sum-exp.
+        float rs = 1.0f;
+        if (part_splits != 0) {
+            float amax = 0.0f;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) amax = fmaxf(amax, fabsf(o[db][v]));
+            amax = fmaxf(amax, __shfl_xor(amax, 32, 64)) * inv;  // the other half-wave holds the row's other dims
+            rs = (amax > 0.0f && amax < INFINITY) ? amax : 1.0f;
+        }
+        const float mul = part_splits == 0 ? inv : inv / rs;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
                 const int dim = db * 32 + g4 * 8 + half * 4;
-                const float a0 = o[db][4 * g4 + 0] * inv, a1 = o[db][4 * g4 + 1] * inv;
-                const float a2 = o[db][4 * g4 + 2] * inv, a3 = o[db][4 * g4 + 3] * inv;
+                const float a0 = o[db][4 * g4 + 0] * mul, a1 = o[db][4 * g4 + 1] * mul;
+                const float a2 = o[db][4 * g4 + 2] * mul, a3 = o[db][4 * g4 + 3] * mul;
                 uint2 val;  // bf16 for the output itself, fp16 for the partial of a key range
                 val.x = part_splits == 0 ? f2bf_pair(a0, a1) : f2h_pair(a0, a1);
                 val.y = part_splits == 0 ? f2bf_pair(a2, a3) : f2h_pair(a2, a3);
                 *reinterpret_cast<uint2 *>(stg + l32 * kEpiRow + dim * 2) = val;
             }
         if (part_splits != 0 && rvalid && half == 0) {
-            // log2-sum-exp of this key range, indexed by global row
+            // log2-sum-exp and scale of this key range, indexed by global row
             const size_t ridx = (size_t)rowg_;
-            lse[(size_t)split * n_rows + ridx] = inv > 0.0f ? m_ref + __builtin_amdgcn_logf(l_tot) : -INFINITY;
+            lse[(size_t)split * n_rows + ridx] =
+                make_float2(inv > 0.0f ? m_ref + __builtin_amdgcn_logf(l_tot) : -INFINITY, rs);
             // key ranges this tile does not have (the other kind of tile has more): empty
             if (split == 0)
-                for (int sx = splits; sx < part_splits; ++sx) lse[(size_t)sx * n_rows + ridx] = -INFINITY;
+                for (int sx = splits; sx < part_splits; ++sx) lse[(size_t)sx * n_rows + ridx] = make_float2(-INFINITY, 1.0f);
         }
     }
     uint16_t *dst_base = part_splits == 0 ? out : part + (size_t)split * n_rows * kHD;
@@ -694,15 +709,15 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 }
 
 // Merge of the split-KV partials: out = sum_s 2^(lse_s - max) O_s / sum_s 2^(lse_s - max).
-// Partials are normalised per split and stored as fp16 (outputs are averages of V entries, far
-// inside the fp16 range for any KV cache a bf16 model produces; eps 2^-11 is below the bf16
-// rounding of the result).  One thread per (row, 8 dims); the loads of kMergeBatch splits are in
-// flight together: 8 for up to 8 key ranges, 16 beyond (small budgets on long caches).
+// Partials are normalised per split and stored as fp16 relative to the largest magnitude of the
+// row, which travels beside the row's log2-sum-exp (eps 2^-11 is below the bf16 rounding of the
+// result).  One thread per (row, 8 dims); the loads of kMergeBatch splits are in flight
+// together: 8 for up to 8 key ranges, 16 beyond (small budgets on long caches).
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 template <int kMergeBatch>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const uint16_t *__restrict__ part_all,
-                                                         const float *__restrict__ lse_all, size_t n_rows,
+                                                         const float2 *__restrict__ lse_all, size_t n_rows,
                                                          int splits, uint16_t *__restrict__ out)
 {
     const size_t gid = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -710,7 +725,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const uint16_t *__restr
     const int dg = (int)(gid & 15);
     if (row >= n_rows) return;
     const uint16_t *part = part_all + row * kHD + dg * 8;
-    const float *lse = lse_all + row;
+    const float2 *lse = lse_all + row;
     const size_t pstride = n_rows * kHD;
 
     // one pass: the weights are taken against the largest lse seen so far and what has been
@@ -720,11 +735,13 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const uint16_t *__restr
     float wsum = 0.0f;
     for (int s0 = 0; s0 < splits; s0 += kMergeBatch) {
         f16x8 v[kMergeBatch];
-        float l[kMergeBatch];
+        float l[kMergeBatch], sc[kMergeBatch];
 #pragma unroll
         for (int j = 0; j < kMergeBatch; ++j) {
             const bool on = s0 + j < splits;
-            l[j] = on ? lse[(size_t)(s0 + j) * n_rows] : -INFINITY;
+            const float2 ls = on ? lse[(size_t)(s0 + j) * n_rows] : make_float2(-INFINITY, 1.0f);
+            l[j] = ls.x;
+            sc[j] = ls.y;
             v[j] = on ? *reinterpret_cast<const f16x8 *>(part + (size_t)(s0 + j) * pstride) : f16x8(0);
         }
         float bm = l[0];
@@ -744,7 +761,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const uint16_t *__restr
             const bool live = l[j] > -INFINITY;
             const float w = live ? __builtin_amdgcn_exp2f(l[j] - mx) : 0.0f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] += live ? w * (float)v[j][e] : 0.0f;
+            for (int e = 0; e < 8; ++e) acc[e] += live ? (w * sc[j]) * (float)v[j][e] : 0.0f;
             wsum += w;
         }
     }
@@ -942,7 +959,7 @@ static int verify_attn_impl(const void *q, const void *k_cache, const void *v_ca
         if (!ws_ok(workspace, workspace_bytes, p.bytes)) return DDTREE_ERR_WORKSPACE;
         char *wsb = static_cast<char *>(workspace);
         uint16_t *part = reinterpret_cast<uint16_t *>(wsb + p.part_off);
-        float *lse = reinterpret_cast<float *>(wsb + p.lse_off);
+        float2 *lse = reinterpret_cast<float2 *>(wsb + p.lse_off);
         static std::atomic<bool> lds_allowed{false};
         if (!allow_dynamic_lds(reinterpret_cast<const void *>(attn_mfma_kernel), kAttnLdsBytes, lds_allowed))
             return DDTREE_ERR_HIP;

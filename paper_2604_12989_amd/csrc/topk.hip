@@ -202,7 +202,7 @@ struct BucketScratch {
 };
 
 // Exact descending ranks, for ranks < want, of the workgroup's elements whose value lies in
-// [lo, hi].  Each thread brings NS values in registers (NaN = empty slot; values below lo are
+// [lo, hi].  Each thread brings NS values in registers (-inf = empty slot; values below lo are
 // ignored) and comp(i), the composite of slot i, evaluated only for the few elements that are
 // placed.  Bit i of `active` (uniform over the wave) tells whether slot i can be non-empty
 // anywhere in the wave, so that a wave skips the code of slots it does not use.

@@ -499,6 +499,24 @@ def test_attn_mask_leak_adversarial(dtype):
     assert np.abs(moved[0] - ref[i, 0]).max() > 50.0
 
 
+def test_attn_large_values_through_split_partials():
+    """Value rows of magnitude 1e5 (beyond the fp16 range of 65504) on a shape whose key range is
+    split: the partial results are stored relative to their row's magnitude, so nothing overflows."""
+    import paper_2604_12989_amd as dd
+    T, L, Hq, Hkv, D = 257, 4100, 8, 2, 128
+    assert dd.verify_attn_workspace_bytes(1, T, Hq, Hkv, D, dd.DTYPE_BF16, L) > 0   # split: partials in scratch
+    q, kc, vc, kt, vt, mask = _attn_case(31, T, L, Hq, Hkv, D, "bf16")
+    vc = di.round_to_bf16((1.0e5 * (1.0 + 0.1 * vc)).astype(np.float32))
+    vt = di.round_to_bf16((1.0e5 * (1.0 + 0.1 * vt)).astype(np.float32))
+    ref = oracle.verify_attn(q, kc, vc, kt, vt, mask)
+    got = gu.gpu_attn(q, kc, vc, kt, vt, mask[None], [0, L], 1, T, "bf16")[0]
+    assert np.isfinite(got).all()
+    assert np.abs(ref).min() > 5.0e4          # every element is compared relative to its size
+    err = attn_err(got, ref)
+    print(f"values of 1e5: max relative err {err:.2e}")
+    assert err < 1e-2
+
+
 def test_attn_chain_tree_and_no_cache():
     T, Hq, Hkv, D = 130, 4, 2, 128
     q, kc, vc, kt, vt = di.attn_tensors(5, T, 0, Hq, Hkv, D, "bf16")
