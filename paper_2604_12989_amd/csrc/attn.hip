@@ -61,7 +61,7 @@ struct AttnArgs {
     int32_t kv_len[DDTREE_MAX_BATCH];    // its number of cache rows
     // matrix-core kernel only: the sequences longest cache first, and the first work item of
     // each of the 8 XCDs' runs (run x = work items xcd_start[x] .. xcd_start[x + 1] - 1)
-    uint8_t order[DDTREE_MAX_BATCH];
+    int32_t order[DDTREE_MAX_BATCH];     // (32-bit entries: read with scalar loads)
     int32_t xcd_start[9];
 };
 
@@ -320,9 +320,13 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         if (rvalid) v = *reinterpret_cast<const uint4 *>(q + (size_t)rowg_ * kHD + ks * 16 + half * 8);
         qreg[ks] = __builtin_bit_cast(bf16x8, v);
     }
-    const uint64_t *mask_row = mask + ((size_t)seq * T + node_) * W;
-    // the row's node is a real tree node (it sees itself); padding rows produce zeros
-    const bool real_ = rvalid && ((mask_row[node_ >> 6] >> (node_ & 63)) & 1ull);
+    // (the row's mask words are addressed from node_ where they are needed: a pointer kept in
+    // registers through the loop would cost a spill)
+    auto mask_row = [&]() __attribute__((always_inline)) { return mask + ((size_t)seq * T + node_) * W; };
+    // the mask word that holds the row's own bit (a real tree node sees itself; padding rows produce
+    // zeros) is requested during the last key tile and looked at in the epilogue: asked for here it
+    // would hold a register through the whole loop, or be waited for and spilled before the loop
+    uint32_t own_word = 0u;
 
     // ---- tile loads: a K tile is 17 and a V tile 18 DMA blocks of 1 KB of LDS; lane l of block b fills
     //      16-byte slot u = 64*b + l, i.e. row u / chunks_per_row, chunk u % chunks_per_row.
@@ -471,7 +475,7 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             const int valid = is_tree ? min(kKT, T - tb * kKT) : min(kKT, L - t * kKT);
             if (is_tree || valid < kKT) {  // tree tiles and a ragged last cache tile
                 uint64_t word = ~0ull;
-                if (is_tree) word = rvalid ? mask_row[tb] : 0ull;
+                if (is_tree) word = rvalid ? mask_row()[tb] : 0ull;
                 if (valid < kKT) word &= (1ull << valid) - 1ull;
                 // this lane's keys of the sub-tile: 8 * (v / 4) + 4 * half + v % 4
                 const uint32_t w32 = (uint32_t)(word >> (32 * kb)) >> (4 * half);
@@ -600,6 +604,7 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             };
             if (!wave_active) request();
             if (wave_active) {
+                if (it == n_tiles - 1 && rvalid) own_word = reinterpret_cast<const uint32_t *>(mask_row())[node_ >> 5];
                 const bool slow = all_slow || it == 0 || t >= n_cache_tiles || (t == n_cache_tiles - 1 && (L & (kKT - 1)) != 0);
                 // sub-tile (t, 0): forms S(t, 1), multiplies P(t-1, 1); requests K(t+1, 0) and V(t, 0)
                 // sub-tile (t, 1): forms S(t+1, 0), multiplies P(t, 0); requests K(t+1, 1) and V(t, 1)
@@ -651,6 +656,7 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     const size_t n_rows = (size_t)batch_n * T * Hq;
     {
         const float l_tot = row_sum();
+        const bool real_ = (own_word >> (node_ & 31)) & 1u;
         const float inv = (rvalid && real_ && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
         // The partial of a key range is stored as fp16 relative to the largest magnitude of its
         // row (so that it fits whatever the values are: bf16 inputs reach 3e38, fp16 65504), with
@@ -680,7 +686,7 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             }
         if (part_splits != 0 && rvalid && half == 0) {
             // log2-sum-exp and scale of this key range, indexed by global row
-            const size_t ridx = (size_t)rowg_;
+            const size_t ridx = (size_t)((seq * T + node_) * Hq + hk * G + (row_m - node_ * G));
             lse[(size_t)split * n_rows + ridx] =
                 make_float2(inv > 0.0f ? m_ref + __builtin_amdgcn_logf(l_tot) : -INFINITY, rs);
             // key ranges this tile does not have (the other kind of tile has more): empty
@@ -970,8 +976,8 @@ static int verify_attn_impl(const void *q, const void *k_cache, const void *v_ca
         const long long per_seq = (long long)Hkv * (main_tiles * p.splits + p.tail_splits);
         const long long total = per_seq * batch;
         if (total > (1ll << 28)) return DDTREE_ERR_ARG;
-        for (int i = 0; i < batch; ++i) args.order[i] = (uint8_t)i;
-        std::stable_sort(args.order, args.order + batch, [&](uint8_t a, uint8_t b) {
+        for (int i = 0; i < batch; ++i) args.order[i] = i;
+        std::stable_sort(args.order, args.order + batch, [&](int32_t a, int32_t b) {
             return kv_len[a] > kv_len[b];
         });
         long long work_total = 0;
