@@ -1,0 +1,158 @@
+// The attention kernel's inner loop on its own (gfx950): per 32-key step and wave 16 matrix
+// instructions (8 for the next scores, 8 for P V), the softmax of 16 scores and the LDS operand
+// reads, without tile loads, masks or epilogue.  CB = blocks of 32 query rows per wave (1: eight
+// waves, two per SIMD; 2: four waves, one per SIMD, every operand read feeds two matrix
+// instructions).  Not part of the library; build and run by hand:
+//   hipcc --offload-arch=gfx950 -O3 -std=c++17 -Xclang -target-feature -Xclang -packed-fp32-ops \
+//       paper_2604_12989_amd/microbench/attn_loop.hip -o /tmp/attn_loop && /tmp/attn_loop
+#include <hip/hip_runtime.h>
+#include <cstdio>
+#include <cstdint>
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+template <int OFF>
+__device__ __forceinline__ void lds_rd128(u32x4 &v, uint32_t addr)
+{
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "+v"(v) : "v"(addr), "n"(OFF) : "memory");
+}
+template <int OFF>
+__device__ __forceinline__ void lds_rdtr(u32x2 &v, uint32_t addr)
+{
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "+v"(v) : "v"(addr), "n"(OFF) : "memory");
+}
+__device__ __forceinline__ uint32_t f2bf_pair(float lo, float hi)
+{
+    const floatx2 f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+}
+template <int N> struct IC { static constexpr int value = N; };
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (B < E) { f(IC<B>{}); static_for<B + 1, E>(f); }
+}
+
+template <int CB, int WAVES, bool BAR>
+__global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(WAVES / 4, WAVES / 4))) void k(float *out, int iters, float scale, uint64_t *cyc)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    for (int i = threadIdx.x; i < 36 * 1024 / 4; i += 64 * WAVES) ((unsigned *)smem)[i] = 0x3c003c00u + (i & 7);
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const unsigned base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    const unsigned ka = base + (lane & 31) * 272 + (lane >> 5) * 16;
+    const unsigned va = base + 17408 + (4 * (lane >> 5) + ((lane & 15) >> 2)) * 288 + 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
+    floatx16 o[CB][4], sa[CB], sb[CB];
+    for (int c = 0; c < CB; ++c) {
+        for (int i = 0; i < 4; ++i) for (int v = 0; v < 16; ++v) o[c][i][v] = 0.f;
+        for (int v = 0; v < 16; ++v) { sa[c][v] = 0.01f * v; sb[c][v] = 0.02f * v; }
+    }
+    bf16x8 q[CB][8];
+    for (int c = 0; c < CB; ++c)
+        for (int ks = 0; ks < 8; ++ks) for (int j = 0; j < 8; ++j) q[c][ks][j] = (__bf16)(0.01f * (threadIdx.x + j + ks + c));
+    u32x4 kbuf[8];
+    u32x2 vbuf[2][4][2];
+    for (int i = 0; i < 8; ++i) kbuf[i] = (u32x4){0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
+    for (int a = 0; a < 2; ++a) for (int b = 0; b < 4; ++b) for (int c = 0; c < 2; ++c) vbuf[a][b][c] = (u32x2){0x3c003c00u, 0x3c003c00u};
+    uint32_t pa[CB][8], pb[CB][8];
+    for (int c = 0; c < CB; ++c) for (int i = 0; i < 8; ++i) pa[c][i] = pb[c][i] = 0x3c003c00u;
+    float lsum[CB];
+    for (int c = 0; c < CB; ++c) lsum[c] = 0.f;
+    const float mref = 1.0f;
+    uint64_t t0;
+    asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t0)::"memory");
+
+    auto step = [&](floatx16 (&cur)[CB], floatx16 (&nxt)[CB], uint32_t (&pin)[CB][8], uint32_t (&pout)[CB][8]) __attribute__((always_inline)) {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        static_for<0, 8>([&](auto I) {
+            constexpr int i = decltype(I)::value;
+            const bf16x8 a = __builtin_bit_cast(bf16x8, kbuf[i]);
+            float e0[CB], e1[CB];
+#pragma unroll
+            for (int c = 0; c < CB; ++c) {
+                if (i == 0) {
+                    floatx16 z;
+                    for (int v = 0; v < 16; ++v) z[v] = 0.f;
+                    nxt[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, q[c][i], z, 0, 0, 0);
+                } else {
+                    nxt[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, q[c][i], nxt[c], 0, 0, 0);
+                }
+                if (c == CB - 1) lds_rd128<i * 32>(kbuf[i], ka);
+                e0[c] = __builtin_amdgcn_exp2f(fmaf(cur[c][2 * i], scale, -mref));
+                lsum[c] += e0[c];
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            constexpr int t2 = i / 4, db = i % 4;
+            const bf16x8 va_ = __builtin_bit_cast(bf16x8, (u32x4){vbuf[t2][db][0].x, vbuf[t2][db][0].y, vbuf[t2][db][1].x, vbuf[t2][db][1].y});
+#pragma unroll
+            for (int c = 0; c < CB; ++c) {
+                const bf16x8 pp = __builtin_bit_cast(bf16x8, (u32x4){pin[c][4 * t2], pin[c][4 * t2 + 1], pin[c][4 * t2 + 2], pin[c][4 * t2 + 3]});
+                o[c][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va_, pp, o[c][db], 0, 0, 0);
+                if (c == CB - 1) {
+                    lds_rdtr<(t2 * 16) * 288 + db * 64>(vbuf[t2][db][0], va);
+                    lds_rdtr<(t2 * 16 + 8) * 288 + db * 64>(vbuf[t2][db][1], va);
+                }
+                e1[c] = __builtin_amdgcn_exp2f(fmaf(cur[c][2 * i + 1], scale, -mref));
+                lsum[c] += e1[c];
+                pout[c][i] = f2bf_pair(e0[c], e1[c]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        });
+    };
+    for (int it = 0; it < iters; ++it) {
+        step(sa, sb, pa, pb);
+        step(sb, sa, pb, pa);
+        if (BAR) __syncthreads();
+    }
+    uint64_t t1;
+    asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t1)::"memory");
+    float s = 0.f;
+    for (int c = 0; c < CB; ++c) {
+        s += lsum[c];
+        for (int i = 0; i < 4; ++i) for (int v = 0; v < 16; ++v) s += o[c][i][v];
+        for (int v = 0; v < 16; ++v) s += sa[c][v] + sb[c][v];
+    }
+    out[blockIdx.x * 512 + threadIdx.x] = s;
+    if ((threadIdx.x & 63) == 0) cyc[blockIdx.x * 8 + (threadIdx.x >> 6)] = t1 - t0;
+}
+
+template <int CB, int WAVES, bool BAR>
+void run(const char *what, int grid)
+{
+    float *out; uint64_t *cyc;
+    (void)hipMalloc(&out, (size_t)256 * 512 * 4); (void)hipMalloc(&cyc, 256 * 8 * 8);
+    (void)hipMemset(cyc, 0, 256 * 8 * 8);
+    (void)hipFuncSetAttribute((const void *)k<CB, WAVES, BAR>, hipFuncAttributeMaxDynamicSharedMemorySize, 40 * 1024);
+    const int iters = 1000;
+    k<CB, WAVES, BAR><<<grid, 64 * WAVES, 40 * 1024>>>(out, 10, 0.125f, cyc);
+    (void)hipDeviceSynchronize();
+    hipEvent_t e0, e1; (void)hipEventCreate(&e0); (void)hipEventCreate(&e1);
+    (void)hipEventRecord(e0);
+    k<CB, WAVES, BAR><<<grid, 64 * WAVES, 40 * 1024>>>(out, iters, 0.125f, cyc);
+    (void)hipEventRecord(e1);
+    (void)hipDeviceSynchronize();
+    float ms; (void)hipEventElapsedTime(&ms, e0, e1);
+    uint64_t h[8];
+    (void)hipMemcpy(h, cyc, sizeof(h), hipMemcpyDeviceToHost);
+    uint64_t mx = 0; for (int i = 0; i < WAVES; ++i) mx = h[i] > mx ? h[i] : mx;
+    const double mfma_per_simd = 2.0 * 16 * CB * (WAVES / 4);  // per iteration
+    printf("%-40s grid %3d: %7.1f clk/iter = %5.1f clk per MFMA of a SIMD; %.3f ms -> %4.0f TFLOP/s at %.0f MHz\n", what, grid,
+           (double)mx / iters, (double)mx / iters / mfma_per_simd, ms, (double)iters * mfma_per_simd * 4 * grid * 32768.0 / ms / 1e9,
+           (double)mx / (ms * 1e3));
+    (void)hipFree(out); (void)hipFree(cyc);
+}
+int main()
+{
+    for (int grid : {1, 256}) {
+        run<1, 8, true>("CB=1, 8 waves, barrier per tile", grid);
+        run<1, 8, false>("CB=1, 8 waves, no barrier", grid);
+        run<1, 4, true>("CB=1, 4 waves, barrier per tile", grid);
+        run<2, 4, true>("CB=2, 4 waves, barrier per tile", grid);
+        run<2, 4, false>("CB=2, 4 waves, no barrier", grid);
+    }
+    return 0;
+}
