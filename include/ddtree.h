@@ -119,10 +119,9 @@ int ddtree_topk(const float *logits, int batch, int B, int V, int K, int32_t *to
  * Rows past n_nodes hold tokens = parent = depth = rank = -1, score 0 and a zero mask row.
  * A prefix of score -inf (it contains a token of probability zero; the paper assumes
  * probabilities in (0,1)) never becomes a node: n_nodes counts prefixes of finite score only.
- * Requires 1 <= N <= DDTREE_MAX_N, 1 <= K <= DDTREE_MAX_N, 1 <= B <= DDTREE_MAX_B, and that the
- * log-probability table and the node records fit the workgroup's LDS:
- * 4 B (K + 3) + 8 (N + 1) + 512 (B + 1) <= 153600 bytes, which only B = 32 with K = N = 1024
- * exceeds.  That shape returns DDTREE_ERR_ARG.
+ * Requires 1 <= N <= DDTREE_MAX_N, 1 <= K <= DDTREE_MAX_N, 1 <= B <= DDTREE_MAX_B (the
+ * log-probability table and the node records, 4 B (K + 3) + 8 (N + 1) bytes, then fit the
+ * workgroup's LDS); anything else returns DDTREE_ERR_ARG.
  */
 int ddtree_build(const int32_t *topk_tok, const float *topk_lp, int batch, int B, int K, int N,
                  const int32_t *root_token, int32_t *tokens, int32_t *parent, int32_t *depth,

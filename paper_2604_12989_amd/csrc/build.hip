@@ -70,10 +70,12 @@ __device__ bool tuple_before(const uint32_t *s_node, int pa, int ra, int pb, int
 // dependent pops, all 256 threads work depth by depth:
 //   * "alive" is a score bucket cut: the score range [lp[0][N-1], lp[0][0]] is divided into 256
 //     equal buckets (bucket 0 the best; one more bucket takes everything below the range), a
-//     histogram of every prefix found so far is kept, and the cut b* is the first bucket at which
+//     histogram of every prefix known so far is kept, and the cut b* is the first bucket at which
 //     the cumulative count reaches N.  At least N prefixes lie at or above the cut, so a prefix
 //     below it is not in the tree, nor is any descendant (scores only fall along a path).  b* only
-//     moves up.
+//     moves up.  "Known" is more than "found": a prefix found with rank >= 1 brings its top-1
+//     continuation with it (see count_continuation), which on peaked rows, where most nodes are
+//     rank-0 children, puts the cut near its final place after the first level.
 //   * level d: every alive depth-(d-1) member finds, by bisection over its (sorted) row, how
 //     many of its children lie at or above the cut; the children are written out, bucketed, the
 //     cut is updated, and the children above the new cut join the members.
@@ -85,6 +87,8 @@ __device__ bool tuple_before(const uint32_t *s_node, int pa, int ra, int pb, int
 //     survived, the construction gives up.
 //   * the end: the members above the cut are ranked exactly (bucket position plus an all-pairs
 //     count inside the bucket, ties by rank tuple) and the first N become nodes 1..N.
+//   * levels with at most 64 parents (with the early cut: nearly all levels of a deep tree) are
+//     run by one wave without barriers (see wave_levels).
 // Giving up (a cut that cannot be proven, or a capacity that heavy ties exceed) returns -1 and
 // the caller runs the sequential pops instead.
 // ------------------------------------------------------------------------------------------
@@ -93,6 +97,7 @@ __device__ unsigned int g_level_giveups;  // sequences the level construction ha
 constexpr int kLvBuckets = 256;
 constexpr float kLvNeg = -3.0e38f;   // scores at or below count as -inf: never part of a tree
 constexpr int kLvSmall = 8;          // parents with at most this many children write them alone
+constexpr int kLvSeedRanks = 16;     // ranks 1 .. 16 off the top-1 chain are entered before the first level
 constexpr int kLvBigCap = 256;
 
 __device__ __forceinline__ uint32_t pack_member(int parent, int rank, int depth)
@@ -200,12 +205,14 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
                            uint32_t *s_node, float *s_score)
 {
     static_assert(kBuildThreads == kLvBuckets, "one bucket per thread");
-    __shared__ int s_hist[kLvBuckets + 1];    // every prefix found so far, by bucket
-    __shared__ int s_histc[kLvBuckets + 1];   // the candidates of the level; at the end: cursors
-    __shared__ int s_pref[kLvBuckets + 1];    // exclusive prefix of s_histc, later of s_hist
+    __shared__ __align__(16) int s_hist[kLvBuckets + 4];    // every prefix known so far, by bucket
+    __shared__ __align__(16) int s_histc[kLvBuckets + 4];   // the candidates of the level; at the end: cursors
+    __shared__ __align__(16) int s_histv[kLvBuckets + 4];   // the prefixes the level makes known
+    __shared__ __align__(16) int s_pref[kLvBuckets + 4];    // exclusive prefix of s_histc, later of s_hist
+    __shared__ int s_state[8];                // what the single-wave levels hand back to the workgroup
     __shared__ int s_w[kBuildThreads / 64];
     __shared__ int s_w2[2][kBuildThreads / 64];
-    __shared__ int s_M, s_fail, s_nbig, s_bstar;
+    __shared__ int s_M, s_fail, s_nbig, s_bstar, s_chain;
     __shared__ uint16_t s_big[kLvBigCap];
     constexpr int NT = kBuildThreads;
     const int tid = threadIdx.x;
@@ -231,138 +238,578 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
     const float inv = ((float)kLvBuckets - 0.5f) / fmaxf(hi - lo, 1e-30f);
     auto bucket_of = [&](float sc) { return (int)fminf((hi - sc) * inv, (float)kLvBuckets); };
     __syncthreads();
+    // Known prefixes.  A prefix found with rank >= 1 makes its whole top-1 continuation known (the
+    // same prefix followed by rank 0 at every further depth: real, distinct prefixes whose scores
+    // are the running sums the construction itself will form), so the histogram takes those at
+    // once and the cut settles levels earlier than the candidates alone would move it; a rank-0
+    // child is then already counted when it turns up.  Continuations below the cut of the
+    // moment are of no interest (the cut only tightens) and end the walk.  The increments are
+    // fetched eight at a time: the running sum is the only dependency from step to step.
+    auto count_continuation = [&](int *hist, float sc, int depth, int cutb) {
+        float v = sc;
+        bool live = true;
+        for (int t0 = depth; t0 < B && live; t0 += 8) {
+            float inc[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) inc[k] = s_lp[min(t0 + k, B - 1) * Kp];
+            // (the empty statements keep the eight fetches together, ahead of the steps: sunk
+            // into the steps each would wait for its own round trip and for the update before it)
+#pragma unroll
+            for (int k = 0; k < 8; ++k) asm volatile("" : "+v"(inc[k]));
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                v += inc[k];
+                const int b = bucket_of(v);
+                live = live && t0 + k < B && v > kLvNeg && b <= cutb;
+                // (a finished walk adds zero, to a word of its own: no branch, no shared address)
+                atomicAdd(&hist[live ? b : (int)(threadIdx.x & 63)], live ? 1 : 0);
+            }
+        }
+    };
+    // Before the first level: the top-1 chain (the root's continuation) and, off every node of
+    // that chain, the children of ranks 1 .. kLvSeedRanks with their continuations: thread
+    // (16 i + r - 1) takes rank r of row i.  On peaked rows these are most of the tree, and the
+    // first level already starts from a cut near the final one.  When they turn up as candidates
+    // they are not counted again (the children of the chain's member, chain_m below, up to that
+    // rank).  With K >= N the final cut lies inside the bucket range (the N children of the
+    // root do), so whatever falls below the range is left out, here and in every later walk (all
+    // of it would land in the one overflow bucket, lane after lane); otherwise everything is counted.
+    const int cutb0 = (K >= N && lo_raw > kLvNeg) ? kLvBuckets - 1 : kLvBuckets;
+    {
+        // score of the chain node at depth i, summed in path order, for this thread's rows i0 and
+        // i0 + 16 (the row maxima are fetched eight at a time, as in the walk above)
+        const int i0 = tid >> 4;
+        float cc = 0.0f, cc_a = 0.0f, cc_b = 0.0f;
+        for (int u0 = 0; u0 < B; u0 += 8) {
+            float inc[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) inc[k] = s_lp[min(u0 + k, B - 1) * Kp];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) asm volatile("" : "+v"(inc[k]));
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int u = u0 + k;
+                if (u == i0) cc_a = cc;
+                if (u == i0 + 16) cc_b = cc;
+                cc += u < B ? inc[k] : 0.0f;
+            }
+        }
+        static_assert(DDTREE_MAX_B <= 32, "two rows per thread cover every depth");
+        const int r = 1 + (tid & 15);
+        // the chain itself: its node at depth i by the thread that takes rank 1 of row i (the
+        // scores fall along the chain, so the tests below are those of a walk that stops), its
+        // last node, at depth B, by thread 0
+        auto count_chain_node = [&](float sc) {
+            const int b = bucket_of(sc);
+            if (sc > kLvNeg && b <= cutb0) atomicAdd(&s_hist[b], 1);
+        };
+        if (tid == 0) count_chain_node(cc);
+        if (r == 1) {
+            if (i0 >= 1 && i0 < B) count_chain_node(cc_a);
+            if (i0 + 16 < B) count_chain_node(cc_b);
+        }
+        if (r < K) {
+#pragma unroll 1
+            for (int h = 0; h < 2; ++h) {
+                const int i = i0 + 16 * h;
+                if (i >= B) break;
+                const float head = (h == 0 ? cc_a : cc_b) + s_lp[i * Kp + r];
+                const int b = bucket_of(head);
+                if (head > kLvNeg && b <= cutb0) {
+                    atomicAdd(&s_hist[b], 1);
+                    count_continuation(s_hist, head, i + 1, cutb0);
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // Children of a parent with score S that lie at or above the cut: a prefix of the sorted row,
+    // at most cap long.  The first four ranks are probed in one round (most parents of a deep tree
+    // have a few children at most); then eight probes at doubling distances bracket the count,
+    // and a 9-ary search (eight independent probes per round) closes the bracket.
+    // (four_only: stop after the first round, a result of 4 with cap > 4 then means "at least 4";
+    // past_four: the first round is known to have passed)
+    auto count_children = [&](const float *row, float S, int cap, int cutb, bool four_only = false,
+                              bool past_four = false) {
+        auto child_ok = [&](int r) {
+            const float sc = S + row[r];
+            return sc > kLvNeg && bucket_of(sc) <= cutb;
+        };
+        // first failing probe of eight increasing ones (the answers are monotone): the count lies
+        // in [q[f-1] + 1, q[f]], with q[-1] + 1 = a and q[8] = b
+        auto narrow8 = [&](const int (&q)[8], int &a, int &b) {
+            bool ok[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) ok[k] = child_ok(q[k]);
+            int f = 8;
+#pragma unroll
+            for (int k = 7; k >= 0; --k) f = ok[k] ? f : k;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                if (k < f) a = q[k] + 1;
+                if (k == f) b = q[k];
+            }
+        };
+        if (!past_four) {
+            bool lead[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) lead[k] = child_ok(min(k, cap - 1));
+            const int n_lead = !lead[0] ? 0 : !lead[1] ? 1 : !lead[2] ? 2 : !lead[3] ? 3 : 4;
+            if (n_lead < 4 || cap <= 4 || four_only) return min(n_lead, cap);
+        }
+        int a = 4, b = cap;  // the count lies in [a, b]
+        {
+            int q[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) q[k] = min(4 + (1 << k), cap - 1);  // ranks 5, 6, 8, 12, 20, 36, 68, 132
+            narrow8(q, a, b);
+        }
+        while (a < b) {
+            const int len = b - a;
+            const int step = len <= 8 ? 1 : (len + 8) / 9;
+            int q[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) q[k] = min(a + (k + 1) * step - 1, b - 1);
+            narrow8(q, a, b);
+        }
+        return a;
+    };
 
     int bstar = kLvBuckets;  // alive <=> bucket <= bstar
     int M = 1, ls = 0, le = 1;   // members so far; the previous level's members are [ls, le)
-    for (int d = 1; d <= B; ++d) {
-        const float *row = s_lp + (d - 1) * Kp;
-        const int n_par = le - ls;
-        if (n_par > L.capp) return -1;
-        if (tid == 0) {
-            s_nbig = 0;
-            s_bstar = bstar;
-        }
-        s_histc[tid] = 0;
-        if (tid == 0) s_histc[kLvBuckets] = 0;
-        // 1. children at or above the cut, per parent (a prefix of the sorted row, found by a
-        //    5-ary search: four independent probes per round), and where they go; small families
-        //    are written on the spot by their parent's thread, large ones are queued
-        auto child_ok = [&](float S, int r) {
-            const float sc = S + row[r];
-            return sc > kLvNeg && bucket_of(sc) <= bstar;
+    int d = 1;
+    int chain_m = 0;    // the member that is the top-1 chain's node of the previous level, -1 once it is dead
+    int C_resume = -1;  // >= 0: level d was taken through its cut check by the single wave below
+                        // and the workgroup continues with its C_resume candidates
+
+    // a candidate that makes itself and its continuation known: rank >= 1 and not entered up front
+    auto newly_known = [&](int parent_m, int r) { return r > 0 && !(parent_m == chain_m && r <= kLvSeedRanks); };
+
+    // Levels with at most 64 parents are run by wave 0 alone, as many in a row as there are: no
+    // barriers, prefix sums and the compaction of survivors by cross-lane operations, the level's
+    // histogram filled while the candidates are written.  LDS operations of one wave execute in
+    // program order, so a lane reads what another lane of the wave wrote by an earlier
+    // instruction; the wavefront-scope fences keep the compiler from reordering them.  Hands back
+    // 0: level d has more than 64 parents; 1: no level is left; 2: level d needs members squeezed
+    // out before its survivors fit (state[6] = its candidate count); -1: give up.
+    auto wave_levels = [&]() {
+        const int lane = tid;
+        int status = 1, C_out = 0;
+        bool calm = false;    // the last level that moved the cut left it where it was
+        int fresh_total = 0;  // prefixes made known since
+        // the cut: lane l adds what the level made known in buckets 4l .. 4l+3 to the running
+        // histogram, takes the prefix sums and finds the bucket of the N-th best known prefix
+        auto move_cut = [&]() {
+            const int4 hc = *reinterpret_cast<const int4 *>(&s_histc[4 * lane]);
+            const int4 hv = *reinterpret_cast<const int4 *>(&s_histv[4 * lane]);
+            int4 ha = *reinterpret_cast<const int4 *>(&s_hist[4 * lane]);
+            ha.x += hv.x;
+            ha.y += hv.y;
+            ha.z += hv.z;
+            ha.w += hv.w;
+            const int ta = ha.x + ha.y + ha.z + ha.w, tc = hc.x + hc.y + hc.z + hc.w;
+            const int ia = wave_scan_inclusive_i32(ta), ic = wave_scan_inclusive_i32(tc);
+            const int a0 = ia - ta, a1 = a0 + ha.x, a2 = a1 + ha.y, a3 = a2 + ha.z;
+            const int c0 = ic - tc;
+            *reinterpret_cast<int4 *>(&s_hist[4 * lane]) = ha;
+            *reinterpret_cast<int4 *>(&s_pref[4 * lane]) = make_int4(c0, c0 + hc.x, c0 + hc.x + hc.y, c0 + hc.x + hc.y + hc.z);
+            if (lane == 63) {
+                s_pref[kLvBuckets] = ic;
+                s_hist[kLvBuckets] += s_histv[kLvBuckets];
+            }
+            // (at most one bucket qualifies)
+            uint32_t bn = (uint32_t)kLvBuckets;
+            if (a0 < N && a0 + ha.x >= N) bn = 4 * lane;
+            if (a1 < N && a1 + ha.y >= N) bn = 4 * lane + 1;
+            if (a2 < N && a2 + ha.z >= N) bn = 4 * lane + 2;
+            if (a3 < N && a3 + ha.w >= N) bn = 4 * lane + 3;
+            bstar = min(bstar, (int)wave_min_u32(bn));
         };
-        int C = 0;
-        for (int i0 = 0; i0 < n_par; i0 += NT) {
-            const int i = i0 + tid;
-            const int m = ls + i;
-            int c = 0;
-            bool cut = false;
+        auto clear_level = [&]() {
+            const int4 z = make_int4(0, 0, 0, 0);
+            *reinterpret_cast<int4 *>(&s_histc[4 * lane]) = z;
+            *reinterpret_cast<int4 *>(&s_histv[4 * lane]) = z;
+            if (lane == 0) s_histc[kLvBuckets] = s_histv[kLvBuckets] = 0;
+        };
+        if (d == 1) {  // the cut that the prefixes entered up front give
+            clear_level();
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            move_cut();
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        }
+        for (; d <= B; ++d) {
+            const int n_par = le - ls;
+            // (a first level without a cut takes every rank of row 0 and walks the continuation
+            // of most: work for the whole workgroup)
+            if (n_par > kWave || (d == 1 && bstar == kLvBuckets && min(K, N) > kWave)) {
+                status = 0;
+                break;
+            }
+            const float *row = s_lp + (d - 1) * Kp;
+            clear_level();
+            const int m = ls + lane;
+            int c = 0, cap = 0;
+            bool cut = false, open = false;
             float S = 0.0f;
-            if (i < n_par) {
+            if (lane < n_par) {
                 S = L.m_score[m];
                 if (m == 0 || bucket_of(S) <= bstar) {
-                    const int cap = min(K, max(1, N / ((int)L.m_jlo[m] + 1)));
-                    int a = 0, b = cap;  // the count lies in [a, b]
-                    while (a < b) {
-                        const int len = b - a;
-                        const int step = len <= 4 ? 1 : (len + 4) / 5;
-                        int q[4];
-                        bool ok[4];
-#pragma unroll
-                        for (int k = 0; k < 4; ++k) q[k] = min(a + (k + 1) * step - 1, b - 1);
-#pragma unroll
-                        for (int k = 0; k < 4; ++k) ok[k] = child_ok(S, q[k]);
-                        // first failing probe (the probes are increasing, the answers monotone)
-                        if (!ok[0]) {
-                            b = q[0];
-                        } else if (!ok[1]) {
-                            a = q[0] + 1;
-                            b = q[1];
-                        } else if (!ok[2]) {
-                            a = q[1] + 1;
-                            b = q[2];
-                        } else if (!ok[3]) {
-                            a = q[2] + 1;
-                            b = q[3];
-                        } else {
-                            a = q[3] + 1;
+                    const int jlo = L.m_jlo[m];
+                    cap = N;
+                    if (jlo != 0) cap = max(1, N / (jlo + 1));  // (members of settled levels carry 0)
+                    cap = min(K, cap);
+                    c = count_children(row, S, cap, bstar, true);
+                    open = c == 4 && cap > 4;
+                }
+            }
+            // Parents with more than four children: a few of them (a deep tree has the chain's
+            // node and little else) are finished one after the other by the whole wave, lane j
+            // probing rank 4 + j, which takes one round per 64 ranks; many of them each finish
+            // their own search.
+            {
+                unsigned long long om = __ballot(open);
+                if (__popcll(om) > 8) {
+                    if (open) c = count_children(row, S, cap, bstar, false, true);
+                } else {
+                    while (om) {
+                        const int src = __ffsll((long long)om) - 1;
+                        om &= om - 1;
+                        const float pS = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(S), src));
+                        const int pcap = __builtin_amdgcn_readlane(cap, src);
+                        int cnt = pcap;
+                        for (int base = 4; base < pcap; base += kWave) {
+                            const int r = base + lane;
+                            bool ok = false;
+                            if (r < pcap) {
+                                const float sc = pS + row[r];
+                                ok = sc > kLvNeg && bucket_of(sc) <= bstar;
+                            }
+                            const unsigned long long okm = __ballot(ok);
+                            if (~okm != 0ull) {
+                                cnt = min(pcap, base + __ffsll((long long)~okm) - 1);
+                                break;
+                            }
+                        }
+                        if (lane == src) c = cnt;
+                    }
+                }
+            }
+            cut = cap > 0 && c == cap && cap < K;
+            const int incl = wave_scan_inclusive_i32(c);
+            const int C = __builtin_amdgcn_readlane(incl, 63);
+            const int off = incl - c;
+            if (C == 0) break;
+            if (C > L.capc) {
+                status = -1;
+                break;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            // The cut has settled (on a deep tree: from the first level or two on): the level
+            // leaves the cut alone, its candidates are alive as they stand and become members
+            // directly.  What it makes known still enters the histogram, and once that adds up
+            // the next level moves the cut again.  A rank cut that the cut as it is cannot
+            // justify sends the level the long way (moving the cut may justify it).
+            bool settled = calm && M + C <= L.capm;
+            if (settled) {
+                bool bad = false;
+                if (cut) {
+                    const float sc = S + row[c];
+                    bad = sc > kLvNeg && bucket_of(sc) <= bstar;
+                }
+                settled = __ballot(bad) == 0ull;
+            }
+            if (settled) {
+                int fresh = 0;
+                // small families rank by rank, as many ranks as the largest of them has (on a
+                // deep tree one or two: a wave runs its instructions one after the other, so a
+                // step that no lane needs is best not issued at all)
+                const int csmall = c <= kLvSmall ? c : 0;
+#pragma unroll 1
+                for (int r = 0; __ballot(r < csmall) != 0ull; ++r)
+                    if (r < csmall) {
+                        const float sc = S + row[r];
+                        L.m_score[M + off + r] = sc;
+                        L.m_info[M + off + r] = pack_member(m, r, d);
+                        L.m_jlo[M + off + r] = 0;
+                        if (newly_known(m, r)) {
+                            atomicAdd(&s_hist[bucket_of(sc)], 1);
+                            count_continuation(s_hist, sc, d, min(bstar, cutb0));
+                            ++fresh;
                         }
                     }
-                    c = a;
-                    cut = c == cap && cap < K;
-                }
-            }
-            int total;
-            const int off = C + build_block_scan(c, s_w, &total);
-            if (i < n_par) {
-                L.p_c[i] = (uint16_t)(c | (cut ? 0x8000 : 0));
-                L.p_off[i] = (uint16_t)min(off, 0xFFFF);
-                if (c > kLvSmall) {
-                    const int slot = atomicAdd(&s_nbig, 1);
-                    if (slot < kLvBigCap) s_big[slot] = (uint16_t)i; else s_fail = 1;
-                } else if (c > 0 && off + c <= L.capc) {  // (too many candidates: given up below)
-                    float v[kLvSmall];
-#pragma unroll
-                    for (int r = 0; r < kLvSmall; ++r) v[r] = row[min(r, K - 1)];
-#pragma unroll
-                    for (int r = 0; r < kLvSmall; ++r)
-                        if (r < c) {
-                            L.c_score[off + r] = S + v[r];
-                            L.c_info[off + r] = pack_member(m, r, d);
+                unsigned long long bigf = __ballot(c > kLvSmall);
+                while (bigf) {
+                    const int src = __ffsll((long long)bigf) - 1;
+                    bigf &= bigf - 1;
+                    const int bc = __builtin_amdgcn_readlane(c, src), boff = __builtin_amdgcn_readlane(off, src);
+                    const float bS = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(S), src));
+                    for (int r = lane; r < bc; r += kWave) {
+                        const float sc = bS + row[r];
+                        L.m_score[M + boff + r] = sc;
+                        L.m_info[M + boff + r] = pack_member(ls + src, r, d);
+                        L.m_jlo[M + boff + r] = 0;
+                        if (newly_known(ls + src, r)) {
+                            atomicAdd(&s_hist[bucket_of(sc)], 1);
+                            count_continuation(s_hist, sc, d, min(bstar, cutb0));
+                            ++fresh;
                         }
+                    }
+                }
+                fresh_total += __popcll(__ballot(fresh > 0));  // (lanes, not prefixes: a rough gauge is enough)
+                if (16 * fresh_total > N) {
+                    calm = false;
+                    fresh_total = 0;
+                }
+                // the chain's next member: the rank-0 child of the chain's member, if it has one
+                const unsigned long long chm = __ballot(lane < n_par && m == chain_m && c > 0);
+                chain_m = chm != 0ull ? M + __builtin_amdgcn_readlane(off, __ffsll((long long)chm) - 1) : -1;
+                ls = M;
+                M += C;
+                le = M;
+                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+                continue;
+            }
+            const int bstar_before = bstar;
+            // candidates: small families by their parent's lane, large ones by the whole wave
+            if (c <= kLvSmall) {
+                float v[kLvSmall];
+#pragma unroll
+                for (int r = 0; r < kLvSmall; ++r) v[r] = row[min(r, K - 1)];
+#pragma unroll
+                for (int r = 0; r < kLvSmall; ++r)
+                    if (r < c) {
+                        const float sc = S + v[r];
+                        L.c_score[off + r] = sc;
+                        L.c_info[off + r] = pack_member(m, r, d);
+                        const int bk = bucket_of(sc);
+                        atomicAdd(&s_histc[bk], 1);
+                        if (newly_known(m, r)) {
+                            atomicAdd(&s_histv[bk], 1);
+                            count_continuation(s_histv, sc, d, min(bstar, cutb0));
+                        }
+                    }
+            }
+            unsigned long long bigm = __ballot(c > kLvSmall);
+            while (bigm) {
+                const int src = __ffsll((long long)bigm) - 1;
+                bigm &= bigm - 1;
+                const int bc = __builtin_amdgcn_readlane(c, src), boff = __builtin_amdgcn_readlane(off, src);
+                const float bS = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(S), src));
+                for (int r = lane; r < bc; r += kWave) {
+                    const float sc = bS + row[r];
+                    L.c_score[boff + r] = sc;
+                    L.c_info[boff + r] = pack_member(ls + src, r, d);
+                    const int bk = bucket_of(sc);
+                    atomicAdd(&s_histc[bk], 1);
+                    if (newly_known(ls + src, r)) {
+                        atomicAdd(&s_histv[bk], 1);
+                        count_continuation(s_histv, sc, d, min(bstar, cutb0));
+                    }
                 }
             }
-            C += total;
-        }
-        if (C == 0) break;
-        if (C > L.capc) return -1;
-        __syncthreads();
-        if (s_fail) return -1;
-        // 2. the large families, each written by all threads
-        const int nbig = s_nbig;
-        for (int q = 0; q < nbig; ++q) {
-            const int i = s_big[q];
-            const int m = ls + i, off = L.p_off[i], c = L.p_c[i] & 0x7FFF;
-            const float S = L.m_score[m];
-            for (int r = tid; r < c; r += NT) {
-                L.c_score[off + r] = S + row[r];
-                L.c_info[off + r] = pack_member(m, r, d);
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            move_cut();
+            // every rank cut must have left out only children below the new cut
+            {
+                bool bad = false;
+                if (cut) {
+                    const float sc = S + row[c];
+                    bad = sc > kLvNeg && bucket_of(sc) <= bstar;
+                }
+                if (__ballot(bad) != 0ull) {
+                    status = -1;
+                    break;
+                }
             }
-        }
-        __syncthreads();
-        // 3. bucket the candidates, move the cut
-        for (int t = tid; t < C; t += NT) atomicAdd(&s_histc[bucket_of(L.c_score[t])], 1);
-        __syncthreads();
-        const int hc = s_histc[tid];
-        const int ha = s_hist[tid] + hc;
-        int total_a, total_c;
-        int ex_a = ha, ex_c = hc;
-        build_block_scan2(&ex_a, &ex_c, s_w2, &total_a, &total_c);
-        s_pref[tid] = ex_c;
-        s_hist[tid] = ha;
-        if (tid == 0) {
-            s_pref[kLvBuckets] = total_c;
-            s_hist[kLvBuckets] += s_histc[kLvBuckets];
-        }
-        if (ex_a < N && ex_a + ha >= N) s_bstar = tid;  // the bucket that holds the N-th best
-        __syncthreads();
-        bstar = min(bstar, s_bstar);
-        // 4. every rank cut must have left out only children below the new cut
-        for (int i = tid; i < n_par; i += NT) {
-            const int pc = L.p_c[i];
-            if (pc & 0x8000) {
-                const float sc = L.m_score[ls + i] + row[pc & 0x7FFF];
-                if (sc > kLvNeg && bucket_of(sc) <= bstar) s_fail = 1;
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            const int n_surv = s_pref[bstar] + s_histc[bstar];
+            if (M + n_surv > L.capm) {
+                status = 2;
+                C_out = C;
+                break;
             }
+            // candidates at or above the cut become members, in candidate order
+            int base = M, chain_next = -1;
+            for (int t0 = 0; t0 < C; t0 += kWave) {
+                const int t = t0 + lane;
+                float sc = 0.0f;
+                int bk = 0;
+                bool keep = false;
+                if (t < C) {
+                    sc = L.c_score[t];
+                    bk = bucket_of(sc);
+                    keep = bk <= bstar;
+                }
+                const unsigned long long km = __ballot(keep);
+                const int pos = base + __popcll(km & ((1ull << lane) - 1ull));
+                bool on_chain = false;
+                if (keep) {
+                    const uint32_t info = L.c_info[t];
+                    L.m_score[pos] = sc;
+                    L.m_info[pos] = info;
+                    L.m_jlo[pos] = (uint16_t)min(s_pref[bk], 0xFFFF);
+                    on_chain = member_parent(info) == chain_m && member_rank(info) == 0;
+                }
+                const unsigned long long cm = __ballot(on_chain);
+                if (cm != 0ull) chain_next = __builtin_amdgcn_readlane(pos, __ffsll((long long)cm) - 1);
+                base += __popcll(km);
+            }
+            chain_m = chain_next;
+            calm = bstar == bstar_before;
+            fresh_total = 0;
+            ls = M;
+            M = base;
+            le = M;
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            if (ls == le) break;
         }
-        __syncthreads();
-        if (s_fail) return -1;
+        if (lane == 0) {
+            s_state[0] = status;
+            s_state[1] = d;
+            s_state[2] = M;
+            s_state[3] = ls;
+            s_state[4] = le;
+            s_state[5] = bstar;
+            s_state[6] = C_out;
+            s_state[7] = chain_m;
+            s_M = M;
+            s_chain = -1;
+        }
+    };
+
+    bool by_workgroup = false;  // the single wave has handed this level over
+    while (d <= B) {
+        if (le - ls <= kWave && C_resume < 0 && !by_workgroup) {
+            if (tid < kWave) wave_levels();
+            __syncthreads();
+            const int status = s_state[0];
+            d = s_state[1];
+            M = s_state[2];
+            ls = s_state[3];
+            le = s_state[4];
+            bstar = s_state[5];
+            chain_m = s_state[7];
+            if (status < 0) return -1;
+            if (status == 1) break;
+            if (status == 2) C_resume = s_state[6];
+            by_workgroup = true;
+            continue;  // level d goes on below: it has more than 64 parents, or its survivors need room
+        }
+        const float *row = s_lp + (d - 1) * Kp;
+        const int n_par = le - ls;
+        int C = 0;
+        if (C_resume >= 0) {
+            C = C_resume;
+            C_resume = -1;
+        } else {
+            if (n_par > L.capp) return -1;
+            if (tid == 0) {
+                s_nbig = 0;
+                s_bstar = bstar;
+                s_chain = -1;
+            }
+            s_histc[tid] = 0;
+            s_histv[tid] = 0;
+            if (tid == 0) s_histc[kLvBuckets] = s_histv[kLvBuckets] = 0;
+            // 1. children at or above the cut, per parent, and where they go; small families
+            //    are written on the spot by their parent's thread, large ones are queued
+            for (int i0 = 0; i0 < n_par; i0 += NT) {
+                const int i = i0 + tid;
+                const int m = ls + i;
+                int c = 0;
+                bool cut = false;
+                float S = 0.0f;
+                if (i < n_par) {
+                    S = L.m_score[m];
+                    if (m == 0 || bucket_of(S) <= bstar) {
+                        const int cap = min(K, max(1, N / ((int)L.m_jlo[m] + 1)));
+                        c = count_children(row, S, cap, bstar);
+                        cut = c == cap && cap < K;
+                    }
+                }
+                int total;
+                const int off = C + build_block_scan(c, s_w, &total);
+                if (i < n_par) {
+                    L.p_c[i] = (uint16_t)(c | (cut ? 0x8000 : 0));
+                    L.p_off[i] = (uint16_t)min(off, 0xFFFF);
+                    if (c > kLvSmall) {
+                        const int slot = atomicAdd(&s_nbig, 1);
+                        if (slot < kLvBigCap) s_big[slot] = (uint16_t)i; else s_fail = 1;
+                    } else if (c > 0 && off + c <= L.capc) {  // (too many candidates: given up below)
+                        float v[kLvSmall];
+#pragma unroll
+                        for (int r = 0; r < kLvSmall; ++r) v[r] = row[min(r, K - 1)];
+#pragma unroll
+                        for (int r = 0; r < kLvSmall; ++r)
+                            if (r < c) {
+                                L.c_score[off + r] = S + v[r];
+                                L.c_info[off + r] = pack_member(m, r, d);
+                            }
+                    }
+                }
+                C += total;
+            }
+            if (C == 0) break;
+            if (C > L.capc) return -1;
+            __syncthreads();
+            if (s_fail) return -1;
+            // 2. the large families, each written by all threads
+            const int nbig = s_nbig;
+            for (int q = 0; q < nbig; ++q) {
+                const int i = s_big[q];
+                const int m = ls + i, off = L.p_off[i], c = L.p_c[i] & 0x7FFF;
+                const float S = L.m_score[m];
+                for (int r = tid; r < c; r += NT) {
+                    L.c_score[off + r] = S + row[r];
+                    L.c_info[off + r] = pack_member(m, r, d);
+                }
+            }
+            __syncthreads();
+            // 3. bucket the candidates, move the cut
+            for (int t = tid; t < C; t += NT) {
+                const float sc = L.c_score[t];
+                const int bk = bucket_of(sc);
+                atomicAdd(&s_histc[bk], 1);
+                const uint32_t info = L.c_info[t];
+                if (newly_known(member_parent(info), member_rank(info))) {
+                    atomicAdd(&s_histv[bk], 1);
+                    count_continuation(s_histv, sc, d, min(bstar, cutb0));
+                }
+            }
+            __syncthreads();
+            const int hc = s_histc[tid];
+            const int ha = s_hist[tid] + s_histv[tid];
+            int total_a, total_c;
+            int ex_a = ha, ex_c = hc;
+            build_block_scan2(&ex_a, &ex_c, s_w2, &total_a, &total_c);
+            s_pref[tid] = ex_c;
+            s_hist[tid] = ha;
+            if (tid == 0) {
+                s_pref[kLvBuckets] = total_c;
+                s_hist[kLvBuckets] += s_histv[kLvBuckets];
+            }
+            if (ex_a < N && ex_a + ha >= N) s_bstar = tid;  // the bucket that holds the N-th best
+            __syncthreads();
+            bstar = min(bstar, s_bstar);
+            // 4. every rank cut must have left out only children below the new cut
+            for (int i = tid; i < n_par; i += NT) {
+                const int pc = L.p_c[i];
+                if (pc & 0x8000) {
+                    const float sc = L.m_score[ls + i] + row[pc & 0x7FFF];
+                    if (sc > kLvNeg && bucket_of(sc) <= bstar) s_fail = 1;
+                }
+            }
+            __syncthreads();
+            if (s_fail) return -1;
+        }
         // 5. room for the survivors: when the member arrays would overflow, the members that
         //    have fallen below the cut are squeezed out (the order is kept, so the previous
         //    level stays a contiguous range; parent references are renumbered)
         const int n_surv = s_pref[bstar] + s_histc[bstar];
         if (M + n_surv > L.capm) {
             uint16_t *remap = L.p_c;  // p_c and p_off (contiguous, 2 * capp >= capm) are free now
+            const bool chain_kept = chain_m >= 0 && bucket_of(L.m_score[chain_m]) <= bstar;
             int base = 1;
             if (tid == 0) remap[0] = 0;
             for (int m0 = 1; m0 < M; m0 += NT) {
@@ -388,6 +835,7 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
                 base += tot;
             }
             __syncthreads();
+            chain_m = chain_kept ? (int)remap[chain_m] : -1;
             const int M2 = base;
             for (int m = 1 + tid; m < M2; m += NT) {
                 const uint32_t info = L.m_info[m];
@@ -411,9 +859,11 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
             if (bk <= bstar) {
                 const int slot = atomicAdd(&s_M, 1);
                 if (slot < L.capm) {
+                    const uint32_t info = L.c_info[t];
                     L.m_score[slot] = sc;
-                    L.m_info[slot] = L.c_info[t];
+                    L.m_info[slot] = info;
                     L.m_jlo[slot] = (uint16_t)min(s_pref[bk], 0xFFFF);
+                    if (member_parent(info) == chain_m && member_rank(info) == 0) s_chain = slot;
                 } else {
                     s_fail = 1;
                 }
@@ -424,22 +874,32 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
         ls = M;
         M = s_M;
         le = M;
+        chain_m = s_chain;
         if (ls == le) break;
-        __syncthreads();  // s_M, s_nbig and s_histc are rewritten by the next level
+        __syncthreads();  // s_M, s_nbig, s_chain and the level's histograms are rewritten by the next level
+        by_workgroup = false;
+        ++d;
     }
     __syncthreads();
 
     // ---- exact order of the members at or above the cut ----
-    const int hb = tid <= bstar ? s_hist[tid] : 0;
+    // (the members are counted per bucket afresh: the running histogram also holds prefixes that
+    // were entered ahead of being found)
+    s_histv[tid] = 0;
+    s_histc[tid] = 0;
+    if (tid == 0) s_histv[kLvBuckets] = s_histc[kLvBuckets] = 0;
+    __syncthreads();
+    for (int m = 1 + tid; m < M; m += NT) {
+        const int bk = bucket_of(L.m_score[m]);
+        if (bk <= bstar) atomicAdd(&s_histv[bk], 1);
+    }
+    __syncthreads();
+    const int hb = tid <= bstar ? s_histv[tid] : 0;
     int total_alive;
     const int start = build_block_scan(hb, s_w, &total_alive);
     s_pref[tid] = start;
-    s_histc[tid] = 0;
-    if (tid == 0) {
-        s_pref[kLvBuckets] = total_alive;
-        s_histc[kLvBuckets] = 0;
-    }
-    if (bstar == kLvBuckets) total_alive += s_hist[kLvBuckets];
+    if (tid == 0) s_pref[kLvBuckets] = total_alive;
+    if (bstar == kLvBuckets) total_alive += s_histv[kLvBuckets];
     uint16_t *sorted = reinterpret_cast<uint16_t *>(L.c_info);
     uint16_t *node_id = reinterpret_cast<uint16_t *>(L.c_score);
     __syncthreads();
@@ -451,7 +911,7 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
     for (int e = tid; e < total_alive; e += NT) {
         const int m = sorted[e];
         const int bk = bucket_of(L.m_score[m]);
-        const int bs = s_pref[bk], nb = s_hist[bk];
+        const int bs = s_pref[bk], nb = s_histv[bk];
         int g = 0;
         for (int j = 0; j < nb; ++j) {
             const int o = sorted[bs + j];
@@ -488,8 +948,7 @@ __global__ __launch_bounds__(kBuildThreads) void build_kernel(
     float *s_lp = reinterpret_cast<float *>(smem);                     // [B][Kp], -inf padded
     uint32_t *s_node = reinterpret_cast<uint32_t *>(s_lp + B * Kp);     // [T]
     float *s_score = reinterpret_cast<float *>(s_node + T);             // [T]
-    uint16_t *s_chain = reinterpret_cast<uint16_t *>(s_score + T);      // [B+1][kBuildThreads]
-    // the level-synchronous construction's arrays share the space of s_chain (used afterwards)
+    // the level-synchronous construction's arrays follow
     LevelMem lv;
     lv.capm = capm;
     lv.capp = capp;
@@ -751,38 +1210,40 @@ __global__ __launch_bounds__(kBuildThreads) void build_kernel(
         }
         const uint32_t nd = s_node[i];
         // (depth and rank are clamped to the table: whatever the records hold, every read below
-        // stays inside topk_tok and the chain scratch)
+        // stays inside topk_tok and the workgroup's LDS)
         const int d = min(max(node_depth(nd), 1), B);
         tokens[o] = tk[(d - 1) * K + min(node_rank(nd), K - 1)];
         parent[o] = node_parent(nd);
         depth[o] = d;
         if (rank) rank[o] = node_rank(nd);
         if (node_score) node_score[o] = s_score[i];
-        // ancestors of i (itself first, the root last): d + 1 ids, kept in this thread's
-        // column of s_chain, then folded into the W mask words
+        // ancestors of i (itself first, the root last), folded into the W <= NSLOT mask words as the
+        // chain is walked: the words stay in registers (compile-time indices), so the only
+        // dependent LDS reads are the d parent look-ups
+        uint64_t word[NSLOT];
+#pragma unroll
+        for (int w = 0; w < NSLOT; ++w) word[w] = 0ull;
         int j = i;
         for (int t = 0; t <= d; ++t) {
-            s_chain[t * kBuildThreads + tid] = (uint16_t)j;
+            const uint64_t bit = 1ull << (j & 63);
+            const int wj = j >> 6;
+#pragma unroll
+            for (int w = 0; w < NSLOT; ++w) word[w] |= wj == w ? bit : 0ull;
             j = node_parent(s_node[j]);
         }
-        for (int w = 0; w < W; ++w) {
-            uint64_t word = 0ull;
-            for (int t = 0; t <= d; ++t) {
-                const int a = s_chain[t * kBuildThreads + tid];
-                if ((a >> 6) == w) word |= 1ull << (a & 63);
-            }
-            mrow[w] = word;
-        }
+#pragma unroll
+        for (int w = 0; w < NSLOT; ++w)
+            if (w < W) mrow[w] = word[w];
     }
 }
 
 static size_t build_lds_bytes(int B, int K, int N)
 {
-    return (size_t)B * (K + 3) * 4 + (size_t)(N + 1) * 8 + (size_t)(B + 1) * kBuildThreads * 2;
+    return (size_t)B * (K + 3) * 4 + (size_t)(N + 1) * 8;
 }
 
 // Dynamic LDS of the kernel and the capacities of the level-synchronous construction (members,
-// candidates per level), which shares the space of the ancestor-chain scratch.  capm = 0: no room,
+// candidates per level).  capm = 0: no room,
 // sequential pops only.
 struct BuildLds {
     size_t bytes;
@@ -791,8 +1252,7 @@ struct BuildLds {
 static BuildLds build_lds_plan(int B, int K, int N, bool level)
 {
     const size_t base = (size_t)B * (K + 3) * 4 + (size_t)(N + 1) * 8;
-    const size_t chain = (size_t)(B + 1) * kBuildThreads * 2;
-    BuildLds r{base + chain, 0, 0, 0};
+    BuildLds r{base, 0, 0, 0};
     if (!level) return r;
     const size_t limit = 150 * 1024;
     if (base >= limit) return r;
@@ -814,7 +1274,7 @@ static BuildLds build_lds_plan(int B, int K, int N, bool level)
     r.capp = capp;
     r.capc = capc;
     const size_t lv = 10 * capm + fixed;
-    r.bytes = base + (lv > chain ? lv : chain);
+    r.bytes = base + lv;
     return r;
 }
 
