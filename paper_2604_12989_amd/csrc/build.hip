@@ -275,7 +275,12 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
     // root do), so whatever falls below the range is left out, here and in every later walk (all
     // of it would land in the one overflow bucket, lane after lane); otherwise everything is counted.
     const int cutb0 = (K >= N && lo_raw > kLvNeg) ? kLvBuckets - 1 : kLvBuckets;
-    {
+    // None of this pays when the top-1 chain leaves the bucket range within three steps (flat
+    // rows: continuations are out of range almost at once): then nothing is entered ahead, every
+    // candidate counts when it is found, rank 0 included, and no continuation is walked.
+    const float chain3 = B >= 3 ? (s_lp[0] + s_lp[Kp]) + s_lp[2 * Kp] : -INFINITY;
+    const bool walks = chain3 > kLvNeg && bucket_of(chain3) < kLvBuckets;
+    if (walks) {
         // score of the chain node at depth i, summed in path order, for this thread's rows i0 and
         // i0 + 16 (the row maxima are fetched eight at a time, as in the walk above)
         const int i0 = tid >> 4;
@@ -384,7 +389,9 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
                         // and the workgroup continues with its C_resume candidates
 
     // a candidate that makes itself and its continuation known: rank >= 1 and not entered up front
-    auto newly_known = [&](int parent_m, int r) { return r > 0 && !(parent_m == chain_m && r <= kLvSeedRanks); };
+    auto newly_known = [&](int parent_m, int r) {
+        return !walks || (r > 0 && !(parent_m == chain_m && r <= kLvSeedRanks));
+    };
 
     // Levels with at most 64 parents are run by wave 0 alone, as many in a row as there are: no
     // barriers, prefix sums and the compaction of survivors by cross-lane operations, the level's
@@ -534,7 +541,7 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
                         L.m_jlo[M + off + r] = 0;
                         if (newly_known(m, r)) {
                             atomicAdd(&s_hist[bucket_of(sc)], 1);
-                            count_continuation(s_hist, sc, d, min(bstar, cutb0));
+                            if (walks) count_continuation(s_hist, sc, d, min(bstar, cutb0));
                             ++fresh;
                         }
                     }
@@ -551,7 +558,7 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
                         L.m_jlo[M + boff + r] = 0;
                         if (newly_known(ls + src, r)) {
                             atomicAdd(&s_hist[bucket_of(sc)], 1);
-                            count_continuation(s_hist, sc, d, min(bstar, cutb0));
+                            if (walks) count_continuation(s_hist, sc, d, min(bstar, cutb0));
                             ++fresh;
                         }
                     }
@@ -586,7 +593,7 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
                         atomicAdd(&s_histc[bk], 1);
                         if (newly_known(m, r)) {
                             atomicAdd(&s_histv[bk], 1);
-                            count_continuation(s_histv, sc, d, min(bstar, cutb0));
+                            if (walks) count_continuation(s_histv, sc, d, min(bstar, cutb0));
                         }
                     }
             }
@@ -604,7 +611,7 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
                     atomicAdd(&s_histc[bk], 1);
                     if (newly_known(ls + src, r)) {
                         atomicAdd(&s_histv[bk], 1);
-                        count_continuation(s_histv, sc, d, min(bstar, cutb0));
+                        if (walks) count_continuation(s_histv, sc, d, min(bstar, cutb0));
                     }
                 }
             }
@@ -774,7 +781,7 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
                 const uint32_t info = L.c_info[t];
                 if (newly_known(member_parent(info), member_rank(info))) {
                     atomicAdd(&s_histv[bk], 1);
-                    count_continuation(s_histv, sc, d, min(bstar, cutb0));
+                    if (walks) count_continuation(s_histv, sc, d, min(bstar, cutb0));
                 }
             }
             __syncthreads();
