@@ -263,6 +263,16 @@ def test_build_large_budget_on_peaked_rows(spike, N, build_algo):
     assert dd.build_giveups() == before
 
 
+@pytest.mark.parametrize("B,spike,N,K", [(24, 13.0, 256, 256), (32, 12.0, 300, 200), (32, 14.0, 512, 512), (17, 13.0, 128, 64)])
+def test_build_more_than_sixteen_positions(B, spike, N, K, build_algo):
+    # block sizes beyond 16: deep chains that run past row 16 (the level construction enters the
+    # low ranks off the top-1 chain two rows per thread there) and fewer ranks than budget
+    x = _peaked_logits(29, B, 4096, spike)
+    tok, lp = oracle.topk(x, K)
+    o = _check_build(tok, lp, N)
+    assert o["depth"].max() > 16
+
+
 def test_build_rows_with_minus_infinity(build_algo):
     # masked vocabulary: rows end in -inf log-probabilities, which never become nodes
     rng = np.random.default_rng(9)
