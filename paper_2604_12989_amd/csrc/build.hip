@@ -507,8 +507,8 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
             const int C = __builtin_amdgcn_readlane(incl, 63);
             const int off = incl - c;
             if (C == 0) break;
-            if (C > L.capc) {
-                status = -1;
+            if (C > L.capc) {  // too many to hold: the workgroup's path knows what to do
+                status = 0;
                 break;
             }
             __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
@@ -711,54 +711,86 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
             C_resume = -1;
         } else {
             if (n_par > L.capp) return -1;
-            if (tid == 0) {
-                s_nbig = 0;
-                s_bstar = bstar;
-                s_chain = -1;
-            }
-            s_histc[tid] = 0;
-            s_histv[tid] = 0;
-            if (tid == 0) s_histc[kLvBuckets] = s_histv[kLvBuckets] = 0;
-            // 1. children at or above the cut, per parent, and where they go; small families
-            //    are written on the spot by their parent's thread, large ones are queued
-            for (int i0 = 0; i0 < n_par; i0 += NT) {
-                const int i = i0 + tid;
-                const int m = ls + i;
-                int c = 0;
-                bool cut = false;
-                float S = 0.0f;
-                if (i < n_par) {
-                    S = L.m_score[m];
-                    if (m == 0 || bucket_of(S) <= bstar) {
-                        const int cap = min(K, max(1, N / ((int)L.m_jlo[m] + 1)));
-                        c = count_children(row, S, cap, bstar);
-                        cut = c == cap && cap < K;
+            // (a level whose candidates do not fit is counted by bucket without being written, the
+            // cut moves, and the children are counted once more against the new cut)
+            for (int attempt = 0;; ++attempt) {
+                C = 0;
+                if (tid == 0) {
+                    s_nbig = 0;
+                    s_bstar = bstar;
+                    s_chain = -1;
+                }
+                s_histc[tid] = 0;
+                s_histv[tid] = 0;
+                if (tid == 0) s_histc[kLvBuckets] = s_histv[kLvBuckets] = 0;
+                // 1. children at or above the cut, per parent, and where they go; small families
+                //    are written on the spot by their parent's thread, large ones are queued
+                for (int i0 = 0; i0 < n_par; i0 += NT) {
+                    const int i = i0 + tid;
+                    const int m = ls + i;
+                    int c = 0;
+                    bool cut = false;
+                    float S = 0.0f;
+                    if (i < n_par) {
+                        S = L.m_score[m];
+                        if (m == 0 || bucket_of(S) <= bstar) {
+                            const int cap = min(K, max(1, N / ((int)L.m_jlo[m] + 1)));
+                            c = count_children(row, S, cap, bstar);
+                            cut = c == cap && cap < K;
+                        }
+                    }
+                    int total;
+                    const int off = C + build_block_scan(c, s_w, &total);
+                    if (i < n_par) {
+                        L.p_c[i] = (uint16_t)(c | (cut ? 0x8000 : 0));
+                        L.p_off[i] = (uint16_t)min(off, 0xFFFF);
+                        if (c > kLvSmall) {
+                            const int slot = atomicAdd(&s_nbig, 1);
+                            if (slot < kLvBigCap) s_big[slot] = (uint16_t)i; else s_fail = 1;
+                        } else if (c > 0 && off + c <= L.capc) {  // (too many candidates: given up below)
+                            float v[kLvSmall];
+#pragma unroll
+                            for (int r = 0; r < kLvSmall; ++r) v[r] = row[min(r, K - 1)];
+#pragma unroll
+                            for (int r = 0; r < kLvSmall; ++r)
+                                if (r < c) {
+                                    L.c_score[off + r] = S + v[r];
+                                    L.c_info[off + r] = pack_member(m, r, d);
+                                }
+                        }
+                    }
+                    C += total;
+                }
+                if (C <= L.capc) break;
+                if (attempt == 1) return -1;
+                __syncthreads();
+                if (s_fail) return -1;
+                for (int i = tid; i < n_par; i += NT) {
+                    const int pc = L.p_c[i] & 0x7FFF;
+                    if (pc > 0 && pc <= kLvSmall) {
+                        const float S = L.m_score[ls + i];
+                        for (int r = 0; r < pc; ++r)
+                            if (newly_known(ls + i, r)) atomicAdd(&s_histv[bucket_of(S + row[r])], 1);
                     }
                 }
-                int total;
-                const int off = C + build_block_scan(c, s_w, &total);
-                if (i < n_par) {
-                    L.p_c[i] = (uint16_t)(c | (cut ? 0x8000 : 0));
-                    L.p_off[i] = (uint16_t)min(off, 0xFFFF);
-                    if (c > kLvSmall) {
-                        const int slot = atomicAdd(&s_nbig, 1);
-                        if (slot < kLvBigCap) s_big[slot] = (uint16_t)i; else s_fail = 1;
-                    } else if (c > 0 && off + c <= L.capc) {  // (too many candidates: given up below)
-                        float v[kLvSmall];
-#pragma unroll
-                        for (int r = 0; r < kLvSmall; ++r) v[r] = row[min(r, K - 1)];
-#pragma unroll
-                        for (int r = 0; r < kLvSmall; ++r)
-                            if (r < c) {
-                                L.c_score[off + r] = S + v[r];
-                                L.c_info[off + r] = pack_member(m, r, d);
-                            }
-                    }
+                const int nbig0 = s_nbig;
+                for (int q = 0; q < nbig0; ++q) {
+                    const int i = s_big[q];
+                    const int c = L.p_c[i] & 0x7FFF;
+                    const float S = L.m_score[ls + i];
+                    for (int r = tid; r < c; r += NT)
+                        if (newly_known(ls + i, r)) atomicAdd(&s_histv[bucket_of(S + row[r])], 1);
                 }
-                C += total;
+                __syncthreads();
+                const int ha0 = s_hist[tid] + s_histv[tid];
+                int total0;
+                const int ex0 = build_block_scan(ha0, s_w, &total0);
+                if (ex0 < N && ex0 + ha0 >= N) s_bstar = tid;
+                __syncthreads();
+                bstar = min(bstar, s_bstar);
+                __syncthreads();
             }
             if (C == 0) break;
-            if (C > L.capc) return -1;
             __syncthreads();
             if (s_fail) return -1;
             // 2. the large families, each written by all threads
