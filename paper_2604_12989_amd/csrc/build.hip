@@ -335,8 +335,8 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
     // and a 9-ary search (eight independent probes per round) closes the bracket.
     // (four_only: stop after the first round, a result of 4 with cap > 4 then means "at least 4";
     // past_four: the first round is known to have passed)
-    auto count_children = [&](const float *row, float S, int cap, int cutb, bool four_only = false,
-                              bool past_four = false) {
+    auto count_children = [&](const float *row, float S, int cap, int cutb, bool past_four = false,
+                              bool four_only = false) {
         auto child_ok = [&](int r) {
             const float sc = S + row[r];
             return sc > kLvNeg && bucket_of(sc) <= cutb;
@@ -466,7 +466,7 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
                     cap = N;
                     if (jlo != 0) cap = max(1, N / (jlo + 1));  // (members of settled levels carry 0)
                     cap = min(K, cap);
-                    c = count_children(row, S, cap, bstar, true);
+                    c = count_children(row, S, cap, bstar, false, true);
                     open = c == 4 && cap > 4;
                 }
             }
@@ -477,7 +477,7 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
             {
                 unsigned long long om = __ballot(open);
                 if (__popcll(om) > 8) {
-                    if (open) c = count_children(row, S, cap, bstar, false, true);
+                    if (open) c = count_children(row, S, cap, bstar, true);
                 } else {
                     while (om) {
                         const int src = __ffsll((long long)om) - 1;
@@ -951,10 +951,28 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
         const int m = sorted[e];
         const int bk = bucket_of(L.m_score[m]);
         const int bs = s_pref[bk], nb = s_histv[bk];
+        const float sm = L.m_score[m];
         int g = 0;
-        for (int j = 0; j < nb; ++j) {
-            const int o = sorted[bs + j];
-            g += (o != m && member_before(L.m_score, L.m_info, o, m)) ? 1 : 0;
+        // the bucket's members eight at a time: ids and scores are fetched together (the empty
+        // statements keep the fetches ahead of the comparisons), and only equal scores, which
+        // the rank tuples decide, take the full comparison
+        for (int j0 = 0; j0 < nb; j0 += 8) {
+            int o[8];
+            float so[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) o[k] = sorted[bs + min(j0 + k, nb - 1)];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) asm volatile("" : "+v"(o[k]));
+#pragma unroll
+            for (int k = 0; k < 8; ++k) so[k] = L.m_score[o[k]];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) asm volatile("" : "+v"(so[k]));
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                if (j0 + k >= nb || o[k] == m) continue;
+                if (so[k] != sm) g += so[k] > sm ? 1 : 0;
+                else g += member_before(L.m_score, L.m_info, o[k], m) ? 1 : 0;
+            }
         }
         const int pos = bs + g;
         node_id[m] = (uint16_t)(pos < N ? pos + 1 : 0);
@@ -1007,22 +1025,37 @@ __global__ __launch_bounds__(kBuildThreads) void build_kernel(
     const int32_t *tk = topk_tok + (size_t)seq * B * K;
 
     // log-probabilities into LDS, rows padded with -inf.  The [B][K] table is contiguous: thread
-    // t takes elements t, t + 256, ..., sixteen loads in flight at a time (one round trip to
-    // memory at B = 16, K = 256), and keeps (row, column) of its element by stepping both.
+    // t takes the 16-byte pieces t, t + 256, ..., sixteen loads in flight at a time (one round trip
+    // to memory up to B K = 16384), and keeps (row, column) of its first element by stepping both.
     {
         const int n_el = B * K;
-        const int dq = kBuildThreads / K, dr = kBuildThreads % K;  // one step of 256 elements
-        int d = tid / K, k = tid % K;
-        for (int e0 = tid; e0 < n_el; e0 += 16 * kBuildThreads) {
-            float v[16];
+        // whole pieces of four, if this sequence's table starts on a 16-byte boundary (else, and
+        // for the last one to three elements, the plain loop below)
+        const int n_q = (reinterpret_cast<uintptr_t>(lp) & 15) == 0 ? n_el >> 2 : 0;
+        const int dq = (4 * kBuildThreads) / K, dr = (4 * kBuildThreads) % K;  // one step of 1024 elements
+        int d = (4 * tid) / K, k = (4 * tid) % K;
+        const float4 *lp4 = reinterpret_cast<const float4 *>(lp);
+        for (int q0 = tid; q0 < n_q; q0 += 16 * kBuildThreads) {
+            float4 v[16];
 #pragma unroll
             for (int u = 0; u < 16; ++u) {
-                const int e = e0 + u * kBuildThreads;
-                v[u] = e < n_el ? lp[e] : 0.0f;
+                const int q = q0 + u * kBuildThreads;
+                v[u] = q < n_q ? lp4[q] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
             }
 #pragma unroll
             for (int u = 0; u < 16; ++u) {
-                if (e0 + u * kBuildThreads < n_el) s_lp[d * Kp + k] = v[u];
+                if (q0 + u * kBuildThreads < n_q) {
+                    const float x[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+                    int dd = d, kk = k;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        s_lp[dd * Kp + kk] = x[c];
+                        if (++kk == K) {
+                            kk = 0;
+                            ++dd;
+                        }
+                    }
+                }
                 d += dq;
                 k += dr;
                 if (k >= K) {
@@ -1031,6 +1064,7 @@ __global__ __launch_bounds__(kBuildThreads) void build_kernel(
                 }
             }
         }
+        for (int e = 4 * n_q + tid; e < n_el; e += kBuildThreads) s_lp[(e / K) * Kp + e % K] = lp[e];
         for (int i = tid; i < 3 * B; i += kBuildThreads) s_lp[(i / 3) * Kp + K + i % 3] = -INFINITY;
     }
     if (tid == 0) {
@@ -1256,23 +1290,44 @@ __global__ __launch_bounds__(kBuildThreads) void build_kernel(
         depth[o] = d;
         if (rank) rank[o] = node_rank(nd);
         if (node_score) node_score[o] = s_score[i];
-        // ancestors of i (itself first, the root last), folded into the W <= NSLOT mask words as the
-        // chain is walked: the words stay in registers (compile-time indices), so the only
-        // dependent LDS reads are the d parent look-ups
-        uint64_t word[NSLOT];
+        if constexpr (NSLOT <= 5) {
+            // ancestors of i (itself first, the root last), folded into the W <= NSLOT mask words as
+            // the chain is walked: the words stay in registers (compile-time indices), so the only
+            // dependent LDS reads are the d parent look-ups
+            uint64_t word[NSLOT];
 #pragma unroll
-        for (int w = 0; w < NSLOT; ++w) word[w] = 0ull;
-        int j = i;
-        for (int t = 0; t <= d; ++t) {
-            const uint64_t bit = 1ull << (j & 63);
-            const int wj = j >> 6;
+            for (int w = 0; w < NSLOT; ++w) word[w] = 0ull;
+            int j = i;
+            for (int t = 0; t <= d; ++t) {
+                const uint64_t bit = 1ull << (j & 63);
+                const int wj = j >> 6;
 #pragma unroll
-            for (int w = 0; w < NSLOT; ++w) word[w] |= wj == w ? bit : 0ull;
-            j = node_parent(s_node[j]);
+                for (int w = 0; w < NSLOT; ++w) word[w] |= wj == w ? bit : 0ull;
+                j = node_parent(s_node[j]);
+            }
+#pragma unroll
+            for (int w = 0; w < NSLOT; ++w)
+                if (w < W) mrow[w] = word[w];
+        } else {
+            // many words, few ancestors: the row is cleared, then the chain is walked with one word
+            // in hand (a parent's id is below its child's, so the word index never rises) and
+            // every word that received bits is stored over its zero (stores of one thread to
+            // one address keep their order)
+            for (int w = 0; w < W; ++w) mrow[w] = 0ull;
+            int j = i, cur_w = i >> 6;
+            uint64_t cur = 0ull;
+            for (int t = 0; t <= d; ++t) {
+                const int wj = min(j >> 6, W - 1);  // (clamped like every index taken from a record)
+                if (wj != cur_w) {
+                    mrow[cur_w] = cur;
+                    cur = 0ull;
+                    cur_w = wj;
+                }
+                cur |= 1ull << (j & 63);
+                j = node_parent(s_node[j]);
+            }
+            mrow[cur_w] = cur;
         }
-#pragma unroll
-        for (int w = 0; w < NSLOT; ++w)
-            if (w < W) mrow[w] = word[w];
     }
 }
 
