@@ -97,7 +97,7 @@ __device__ unsigned int g_level_giveups;  // sequences the level construction ha
 constexpr int kLvBuckets = 256;
 constexpr float kLvNeg = -3.0e38f;   // scores at or below count as -inf: never part of a tree
 constexpr int kLvSmall = 8;          // parents with at most this many children write them alone
-constexpr int kLvSeedRanks = 16;     // ranks 1 .. 16 off the top-1 chain are entered before the first level
+constexpr int kLvSeedRanksMax = 64;  // at most so many ranks off the top-1 chain are entered before the first level
 constexpr int kLvBigCap = 256;
 
 __device__ __forceinline__ uint32_t pack_member(int parent, int rank, int depth)
@@ -210,6 +210,7 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
     __shared__ __align__(16) int s_histv[kLvBuckets + 4];   // the prefixes the level makes known
     __shared__ __align__(16) int s_pref[kLvBuckets + 4];    // exclusive prefix of s_histc, later of s_hist
     __shared__ int s_state[8];                // what the single-wave levels hand back to the workgroup
+    __shared__ float s_cc[DDTREE_MAX_B + 1];  // scores of the top-1 chain's nodes
     __shared__ int s_w[kBuildThreads / 64];
     __shared__ int s_w2[2][kBuildThreads / 64];
     __shared__ int s_M, s_fail, s_nbig, s_bstar, s_chain;
@@ -267,8 +268,8 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
         }
     };
     // Before the first level: the top-1 chain (the root's continuation) and, off every node of
-    // that chain, the children of ranks 1 .. kLvSeedRanks with their continuations: thread
-    // (16 i + r - 1) takes rank r of row i.  On peaked rows these are most of the tree, and the
+    // that chain, the children of ranks 1 .. seed_ranks with their continuations, one (row,
+    // rank) per thread and pass.  On peaked rows these are most of the tree, and the
     // first level already starts from a cut near the final one.  When they turn up as candidates
     // they are not counted again (the children of the chain's member, chain_m below, up to that
     // rank).  With K >= N the final cut lies inside the bucket range (the N children of the
@@ -280,50 +281,45 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
     // candidate counts when it is found, rank 0 included, and no continuation is walked.
     const float chain3 = B >= 3 ? (s_lp[0] + s_lp[Kp]) + s_lp[2 * Kp] : -INFINITY;
     const bool walks = chain3 > kLvNeg && bucket_of(chain3) < kLvBuckets;
+    // ranks 1 .. seed_ranks off the chain are entered: 16 up to N = 256, N/16 beyond (at most 64)
+    const int seed_ranks = min(kLvSeedRanksMax, max(16, N >> 4));
     if (walks) {
-        // score of the chain node at depth i, summed in path order, for this thread's rows i0 and
-        // i0 + 16 (the row maxima are fetched eight at a time, as in the walk above)
-        const int i0 = tid >> 4;
-        float cc = 0.0f, cc_a = 0.0f, cc_b = 0.0f;
-        for (int u0 = 0; u0 < B; u0 += 8) {
-            float inc[8];
+        // scores of the chain's nodes, summed in path order by one thread (the row maxima fetched
+        // eight at a time, as in the walk above): s_cc[i] = node at depth i, s_cc[0] = 0
+        if (tid == 0) {
+            float cc = 0.0f;
+            s_cc[0] = 0.0f;
+            for (int u0 = 0; u0 < B; u0 += 8) {
+                float inc[8];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) inc[k] = s_lp[min(u0 + k, B - 1) * Kp];
+                for (int k = 0; k < 8; ++k) inc[k] = s_lp[min(u0 + k, B - 1) * Kp];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) asm volatile("" : "+v"(inc[k]));
+                for (int k = 0; k < 8; ++k) asm volatile("" : "+v"(inc[k]));
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int u = u0 + k;
-                if (u == i0) cc_a = cc;
-                if (u == i0 + 16) cc_b = cc;
-                cc += u < B ? inc[k] : 0.0f;
+                for (int k = 0; k < 8; ++k)
+                    if (u0 + k < B) {
+                        cc += inc[k];
+                        s_cc[u0 + k + 1] = cc;
+                    }
             }
         }
-        static_assert(DDTREE_MAX_B <= 32, "two rows per thread cover every depth");
-        const int r = 1 + (tid & 15);
-        // the chain itself: its node at depth i by the thread that takes rank 1 of row i (the
-        // scores fall along the chain, so the tests below are those of a walk that stops), its
-        // last node, at depth B, by thread 0
-        auto count_chain_node = [&](float sc) {
+        __syncthreads();
+        // the chain itself (the scores fall along it, so the test is that of a walk that stops)
+        if (tid >= 1 && tid <= B) {
+            const float sc = s_cc[tid];
             const int b = bucket_of(sc);
             if (sc > kLvNeg && b <= cutb0) atomicAdd(&s_hist[b], 1);
-        };
-        if (tid == 0) count_chain_node(cc);
-        if (r == 1) {
-            if (i0 >= 1 && i0 < B) count_chain_node(cc_a);
-            if (i0 + 16 < B) count_chain_node(cc_b);
         }
-        if (r < K) {
-#pragma unroll 1
-            for (int h = 0; h < 2; ++h) {
-                const int i = i0 + 16 * h;
-                if (i >= B) break;
-                const float head = (h == 0 ? cc_a : cc_b) + s_lp[i * Kp + r];
-                const int b = bucket_of(head);
-                if (head > kLvNeg && b <= cutb0) {
-                    atomicAdd(&s_hist[b], 1);
-                    count_continuation(s_hist, head, i + 1, cutb0);
-                }
+        // heads (row i, rank r): one per thread and pass
+        const int n_heads = B * seed_ranks;
+        for (int hx = tid; hx < n_heads; hx += NT) {
+            const int i = hx / seed_ranks, r = 1 + hx % seed_ranks;
+            if (r >= K) continue;
+            const float head = s_cc[i] + s_lp[i * Kp + r];
+            const int b = bucket_of(head);
+            if (head > kLvNeg && b <= cutb0) {
+                atomicAdd(&s_hist[b], 1);
+                count_continuation(s_hist, head, i + 1, cutb0);
             }
         }
     }
@@ -390,7 +386,153 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
 
     // a candidate that makes itself and its continuation known: rank >= 1 and not entered up front
     auto newly_known = [&](int parent_m, int r) {
-        return !walks || (r > 0 && !(parent_m == chain_m && r <= kLvSeedRanks));
+        return !walks || (r > 0 && !(parent_m == chain_m && r <= seed_ranks));
+    };
+
+    // (the two helpers below are for wave 0 alone: lane = thread)
+    const int lane = tid;
+    // the cut: lane l adds what the level made known in buckets 4l .. 4l+3 to the running
+    // histogram, takes the prefix sums and finds the bucket of the N-th best known prefix
+    auto move_cut = [&]() {
+        const int4 hc = *reinterpret_cast<const int4 *>(&s_histc[4 * lane]);
+        const int4 hv = *reinterpret_cast<const int4 *>(&s_histv[4 * lane]);
+        int4 ha = *reinterpret_cast<const int4 *>(&s_hist[4 * lane]);
+        ha.x += hv.x;
+        ha.y += hv.y;
+        ha.z += hv.z;
+        ha.w += hv.w;
+        const int ta = ha.x + ha.y + ha.z + ha.w, tc = hc.x + hc.y + hc.z + hc.w;
+        const int ia = wave_scan_inclusive_i32(ta), ic = wave_scan_inclusive_i32(tc);
+        const int a0 = ia - ta, a1 = a0 + ha.x, a2 = a1 + ha.y, a3 = a2 + ha.z;
+        const int c0 = ic - tc;
+        *reinterpret_cast<int4 *>(&s_hist[4 * lane]) = ha;
+        *reinterpret_cast<int4 *>(&s_pref[4 * lane]) = make_int4(c0, c0 + hc.x, c0 + hc.x + hc.y, c0 + hc.x + hc.y + hc.z);
+        if (lane == 63) {
+            s_pref[kLvBuckets] = ic;
+            s_hist[kLvBuckets] += s_histv[kLvBuckets];
+        }
+        // (at most one bucket qualifies)
+        uint32_t bn = (uint32_t)kLvBuckets;
+        if (a0 < N && a0 + ha.x >= N) bn = 4 * lane;
+        if (a1 < N && a1 + ha.y >= N) bn = 4 * lane + 1;
+        if (a2 < N && a2 + ha.z >= N) bn = 4 * lane + 2;
+        if (a3 < N && a3 + ha.w >= N) bn = 4 * lane + 3;
+        bstar = min(bstar, (int)wave_min_u32(bn));
+    };
+    auto clear_level = [&]() {
+        const int4 z = make_int4(0, 0, 0, 0);
+        *reinterpret_cast<int4 *>(&s_histc[4 * lane]) = z;
+        *reinterpret_cast<int4 *>(&s_histv[4 * lane]) = z;
+        if (lane == 0) s_histc[kLvBuckets] = s_histv[kLvBuckets] = 0;
+    };
+
+    // The cut that the prefixes entered up front give (wave 0; the others wait for it).
+    if (tid < kWave) {
+        clear_level();
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        move_cut();
+        if (tid == 0) s_state[5] = bstar;
+    }
+    __syncthreads();
+    bstar = s_state[5];
+
+    // By generations.  Where the up-front entries already give a cut (peaked rows), the members --
+    // every prefix at or above it -- are enumerated by the number of their non-zero ranks instead
+    // of by depth: generation g + 1 is found from generation g in one step of the whole workgroup,
+    // and there are at most log2(N + 1) + 1 generations (a prefix with g non-zero ranks has 2^g - 1
+    // better ones: itself with any subset of them set to rank 0), two or three on a tree from a
+    // confident drafter, against B levels.  One step: (A) every head of the generation (a member
+    // that ends in a non-zero rank; the root for generation 0) walks its top-1 continuation while
+    // it stays at or above the cut, and those nodes become members; (B) every head and every
+    // continuation node counts its children of rank >= 1 at or above the cut (a prefix of its
+    // sorted row): they are the heads of the next generation.  The cut is left where it is
+    // (allowed: see the settled levels below), so nothing is bucketed and no histogram is kept;
+    // if that lets in more members than a tight cut would (N + N/2 + 64), the construction starts
+    // over level by level.  Returns the number of members, or -1.
+    auto by_generations = [&]() -> int {
+        const int limit = min(L.capm, N + N / 2 + 64);
+        const int cap = min(K, N);
+        auto alive = [&](float v) { return v > kLvNeg && bucket_of(v) <= bstar; };
+        int hs = 0, he = 1, Mg = 1;
+        for (;;) {
+            // A. the continuations of the heads [hs, he)
+            const int n_heads = he - hs;
+            const int chain_base = Mg;
+            int Cn = 0;
+            for (int i0 = 0; i0 < n_heads; i0 += NT) {
+                const int i = i0 + tid, h = hs + i;
+                float S = 0.0f;
+                int dh = 0, len = 0;
+                if (i < n_heads) {
+                    S = L.m_score[h];
+                    dh = member_depth(L.m_info[h]);
+                    float v = S;
+                    bool live = true;
+                    for (int t0 = dh; t0 < B && live; t0 += 8) {
+                        float inc[8];
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) inc[k] = s_lp[min(t0 + k, B - 1) * Kp];
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) asm volatile("" : "+v"(inc[k]));
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) {
+                            v += inc[k];
+                            live = live && t0 + k < B && alive(v);
+                            len += live ? 1 : 0;
+                        }
+                    }
+                }
+                int total;
+                const int off = Cn + build_block_scan(len, s_w, &total);
+                if (len > 0 && chain_base + off + len <= L.capm) {
+                    float v = S;
+                    for (int j = 0; j < len; ++j) {
+                        v += s_lp[(dh + j) * Kp];
+                        const int id = chain_base + off + j;
+                        L.m_score[id] = v;
+                        L.m_info[id] = pack_member(j == 0 ? h : id - 1, 0, dh + 1 + j);
+                        L.m_jlo[id] = 0;
+                    }
+                }
+                Cn += total;
+            }
+            if (chain_base + Cn > limit) return -1;
+            Mg = chain_base + Cn;
+            __syncthreads();
+            // B. the children of rank >= 1 of the heads and of their continuation nodes
+            const int n_par = n_heads + Cn;
+            const int head_base = Mg;
+            int H = 0;
+            for (int p0 = 0; p0 < n_par; p0 += NT) {
+                const int p = p0 + tid;
+                const int pm = p < n_heads ? hs + p : chain_base + (p - n_heads);
+                float S = 0.0f;
+                int dp = 0, c = 0;
+                if (p < n_par) {
+                    S = L.m_score[pm];
+                    dp = member_depth(L.m_info[pm]);
+                    if (dp < B) c = max(0, count_children(s_lp + dp * Kp, S, cap, bstar) - 1);
+                }
+                int total;
+                const int off = H + build_block_scan(c, s_w, &total);
+                if (c > 0 && head_base + off + c <= L.capm) {
+                    const float *row = s_lp + dp * Kp;
+                    for (int r = 1; r <= c; ++r) {
+                        const int id = head_base + off + r - 1;
+                        L.m_score[id] = S + row[r];
+                        L.m_info[id] = pack_member(pm, r, dp + 1);
+                        L.m_jlo[id] = 0;
+                    }
+                }
+                H += total;
+            }
+            if (head_base + H > limit) return -1;
+            __syncthreads();
+            hs = head_base;
+            he = head_base + H;
+            Mg = he;
+            if (H == 0) return Mg;
+        }
     };
 
     // Levels with at most 64 parents are run by wave 0 alone, as many in a row as there are: no
@@ -401,50 +543,9 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
     // 0: level d has more than 64 parents; 1: no level is left; 2: level d needs members squeezed
     // out before its survivors fit (state[6] = its candidate count); -1: give up.
     auto wave_levels = [&]() {
-        const int lane = tid;
         int status = 1, C_out = 0;
         bool calm = false;    // the last level that moved the cut left it where it was
         int fresh_total = 0;  // prefixes made known since
-        // the cut: lane l adds what the level made known in buckets 4l .. 4l+3 to the running
-        // histogram, takes the prefix sums and finds the bucket of the N-th best known prefix
-        auto move_cut = [&]() {
-            const int4 hc = *reinterpret_cast<const int4 *>(&s_histc[4 * lane]);
-            const int4 hv = *reinterpret_cast<const int4 *>(&s_histv[4 * lane]);
-            int4 ha = *reinterpret_cast<const int4 *>(&s_hist[4 * lane]);
-            ha.x += hv.x;
-            ha.y += hv.y;
-            ha.z += hv.z;
-            ha.w += hv.w;
-            const int ta = ha.x + ha.y + ha.z + ha.w, tc = hc.x + hc.y + hc.z + hc.w;
-            const int ia = wave_scan_inclusive_i32(ta), ic = wave_scan_inclusive_i32(tc);
-            const int a0 = ia - ta, a1 = a0 + ha.x, a2 = a1 + ha.y, a3 = a2 + ha.z;
-            const int c0 = ic - tc;
-            *reinterpret_cast<int4 *>(&s_hist[4 * lane]) = ha;
-            *reinterpret_cast<int4 *>(&s_pref[4 * lane]) = make_int4(c0, c0 + hc.x, c0 + hc.x + hc.y, c0 + hc.x + hc.y + hc.z);
-            if (lane == 63) {
-                s_pref[kLvBuckets] = ic;
-                s_hist[kLvBuckets] += s_histv[kLvBuckets];
-            }
-            // (at most one bucket qualifies)
-            uint32_t bn = (uint32_t)kLvBuckets;
-            if (a0 < N && a0 + ha.x >= N) bn = 4 * lane;
-            if (a1 < N && a1 + ha.y >= N) bn = 4 * lane + 1;
-            if (a2 < N && a2 + ha.z >= N) bn = 4 * lane + 2;
-            if (a3 < N && a3 + ha.w >= N) bn = 4 * lane + 3;
-            bstar = min(bstar, (int)wave_min_u32(bn));
-        };
-        auto clear_level = [&]() {
-            const int4 z = make_int4(0, 0, 0, 0);
-            *reinterpret_cast<int4 *>(&s_histc[4 * lane]) = z;
-            *reinterpret_cast<int4 *>(&s_histv[4 * lane]) = z;
-            if (lane == 0) s_histc[kLvBuckets] = s_histv[kLvBuckets] = 0;
-        };
-        if (d == 1) {  // the cut that the prefixes entered up front give
-            clear_level();
-            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-            move_cut();
-            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-        }
         for (; d <= B; ++d) {
             const int n_par = le - ls;
             // (a first level without a cut takes every rank of row 0 and walks the continuation
@@ -686,6 +787,14 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
     };
 
     bool by_workgroup = false;  // the single wave has handed this level over
+    if (walks && bstar < kLvBuckets) {
+        const int Mgen = by_generations();
+        if (Mgen >= 0) {
+            M = Mgen;
+            d = B + 1;  // no level is left
+        }
+        __syncthreads();
+    }
     while (d <= B) {
         if (le - ls <= kWave && C_resume < 0 && !by_workgroup) {
             if (tid < kWave) wave_levels();
