@@ -63,6 +63,7 @@ struct AttnArgs {
     // each of the 8 XCDs' runs (run x = work items xcd_start[x] .. xcd_start[x + 1] - 1)
     int32_t order[DDTREE_MAX_BATCH];     // (32-bit entries: read with scalar loads)
     int32_t xcd_start[9];
+    uint32_t g_magic;                    // ceil(2^32 / G) for G = Hq / Hkv >= 2 (x / G = mulhi(x, g_magic) for x < 2^26), 0 for G = 1
 };
 
 AttnPlan attn_plan(int batch, int T, int Hq, int Hkv, int D, long long sum_L, int dtype)
@@ -320,9 +321,21 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         if (rvalid) v = *reinterpret_cast<const uint4 *>(q + (size_t)rowg_ * kHD + ks * 16 + half * 8);
         qreg[ks] = __builtin_bit_cast(bf16x8, v);
     }
-    // (the row's mask words are addressed from node_ where they are needed: a pointer kept in
-    // registers through the loop would cost a spill)
-    auto mask_row = [&]() __attribute__((always_inline)) { return mask + ((size_t)seq * T + node_) * W; };
+    // Past the query loads nothing derived from the lane's row is kept: the masked steps, the
+    // fetch of the row's own mask bit and the epilogue work the row out again from the thread
+    // index (a handful of instructions: the division by G is a multiplication by the host's
+    // reciprocal), read through an empty statement so that the compiler does not fall back on the
+    // copies above -- held through the key loop, those were spilled, and a spill's reload between
+    // the query loads and the first tile requests made the requests wait for the queries.
+    auto lane_row = [&](int &rm, bool &rv, int &nd) __attribute__((always_inline)) {
+        int t = (int)threadIdx.x;
+        asm volatile("" : "+v"(t));
+        rm = m0 + ((t >> 6) << 5) + (t & 31);
+        rv = rm < m_end;
+        const int dv = args.g_magic != 0u ? (int)__umulhi((uint32_t)rm, args.g_magic) : rm;
+        nd = rv ? dv : 0;
+    };
+    auto mask_row = [&](int nd) __attribute__((always_inline)) { return mask + ((size_t)seq * T + nd) * W; };
     // the mask word that holds the row's own bit (a real tree node sees itself; padding rows produce
     // zeros) is requested during the last key tile and looked at in the epilogue: asked for here it
     // would hold a register through the whole loop, or be waited for and spilled before the loop
@@ -475,7 +488,12 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             const int valid = is_tree ? min(kKT, T - tb * kKT) : min(kKT, L - t * kKT);
             if (is_tree || valid < kKT) {  // tree tiles and a ragged last cache tile
                 uint64_t word = ~0ull;
-                if (is_tree) word = rvalid ? mask_row()[tb] : 0ull;
+                if (is_tree) {
+                    int rm, nd;
+                    bool rv;
+                    lane_row(rm, rv, nd);
+                    word = rv ? mask_row(nd)[tb] : 0ull;
+                }
                 if (valid < kKT) word &= (1ull << valid) - 1ull;
                 // this lane's keys of the sub-tile: 8 * (v / 4) + 4 * half + v % 4
                 const uint32_t w32 = (uint32_t)(word >> (32 * kb)) >> (4 * half);
@@ -604,7 +622,12 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             };
             if (!wave_active) request();
             if (wave_active) {
-                if (it == n_tiles - 1 && rvalid) own_word = reinterpret_cast<const uint32_t *>(mask_row())[node_ >> 5];
+                if (it == n_tiles - 1) {
+                    int rm, nd;
+                    bool rv;
+                    lane_row(rm, rv, nd);
+                    if (rv) own_word = reinterpret_cast<const uint32_t *>(mask_row(nd))[nd >> 5];
+                }
                 const bool slow = all_slow || it == 0 || t >= n_cache_tiles || (t == n_cache_tiles - 1 && (L & (kKT - 1)) != 0);
                 // sub-tile (t, 0): forms S(t, 1), multiplies P(t-1, 1); requests K(t+1, 0) and V(t, 0)
                 // sub-tile (t, 1): forms S(t+1, 0), multiplies P(t, 0); requests K(t+1, 1) and V(t, 1)
@@ -655,9 +678,12 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     unsigned char *stg = smem + wave * (32 * kEpiRow);
     const size_t n_rows = (size_t)batch_n * T * Hq;
     {
+        int e_row, e_node;
+        bool e_valid;
+        lane_row(e_row, e_valid, e_node);
         const float l_tot = row_sum();
-        const bool real_ = (own_word >> (node_ & 31)) & 1u;
-        const float inv = (rvalid && real_ && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
+        const bool real_ = (own_word >> (e_node & 31)) & 1u;
+        const float inv = (e_valid && real_ && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
         // The partial of a key range is stored as fp16 relative to the largest magnitude of its
         // row (so that it fits whatever the values are: bf16 inputs reach 3e38, fp16 65504), with
         // that magnitude kept beside the log2-sum-exp.
@@ -684,9 +710,9 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                 val.y = part_splits == 0 ? f2bf_pair(a2, a3) : f2h_pair(a2, a3);
                 *reinterpret_cast<uint2 *>(stg + l32 * kEpiRow + dim * 2) = val;
             }
-        if (part_splits != 0 && rvalid && half == 0) {
+        if (part_splits != 0 && e_valid && half == 0) {
             // log2-sum-exp and scale of this key range, indexed by global row
-            const size_t ridx = (size_t)((seq * T + node_) * Hq + hk * G + (row_m - node_ * G));
+            const size_t ridx = (size_t)((seq * T + e_node) * Hq + hk * G + (e_row - e_node * G));
             lse[(size_t)split * n_rows + ridx] =
                 make_float2(inv > 0.0f ? m_ref + __builtin_amdgcn_logf(l_tot) : -INFINITY, rs);
             // key ranges this tile does not have (the other kind of tile has more): empty
@@ -949,6 +975,10 @@ static int verify_attn_impl(const void *q, const void *k_cache, const void *v_ca
     if (dtype != DDTREE_DTYPE_BF16 && dtype != DDTREE_DTYPE_FP32) return DDTREE_ERR_ARG;
     if (!(softmax_scale > 0.0f) || !(softmax_scale < 1e30f)) return DDTREE_ERR_ARG;
     AttnArgs args;
+    {
+        const uint32_t G = (uint32_t)(Hq / Hkv);
+        args.g_magic = G >= 2 ? (uint32_t)((0x100000000ull + G - 1) / G) : 0u;
+    }
     long long sum_L = 0;
     for (int s = 0; s < batch; ++s) {
         if (kv_start[s] < 0 || kv_len[s] < 0 || (long long)kv_start[s] + kv_len[s] > 0x7FFFFFFFll)
