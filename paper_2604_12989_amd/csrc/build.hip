@@ -454,6 +454,7 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
         const int cap = min(K, N);
         auto alive = [&](float v) { return v > kLvNeg && bucket_of(v) <= bstar; };
         int hs = 0, he = 1, Mg = 1;
+        if (tid == 0) s_nbig = 0;  // (the scan below has barriers before the first use)
         for (;;) {
             // A. the continuations of the heads [hs, he)
             const int n_heads = he - hs;
@@ -484,7 +485,8 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
                 }
                 int total;
                 const int off = Cn + build_block_scan(len, s_w, &total);
-                if (len > 0 && chain_base + off + len <= L.capm) {
+                if (chain_base + Cn + total > limit) return -1;  // (before anything of it is written)
+                if (len > 0) {
                     float v = S;
                     for (int j = 0; j < len; ++j) {
                         v += s_lp[(dh + j) * Kp];
@@ -496,7 +498,6 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
                 }
                 Cn += total;
             }
-            if (chain_base + Cn > limit) return -1;
             Mg = chain_base + Cn;
             __syncthreads();
             // B. the children of rank >= 1 of the heads and of their continuation nodes
@@ -515,7 +516,20 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
                 }
                 int total;
                 const int off = H + build_block_scan(c, s_w, &total);
-                if (c > 0 && head_base + off + c <= L.capm) {
+                if (head_base + H + total > limit) return -1;
+                // small families are written by their parent's thread, large ones are queued and
+                // written by the whole workgroup (s_nbig is 0 here: see the end of the round)
+                bool own = c > 0;
+                if (c > kLvSmall) {
+                    const int slot = atomicAdd(&s_nbig, 1);
+                    if (slot < kLvBigCap) {
+                        s_big[slot] = (uint16_t)pm;
+                        L.p_c[slot] = (uint16_t)c;
+                        L.p_off[slot] = (uint16_t)off;  // (below limit <= capm <= 8192)
+                        own = false;
+                    }
+                }
+                if (own) {
                     const float *row = s_lp + dp * Kp;
                     for (int r = 1; r <= c; ++r) {
                         const int id = head_base + off + r - 1;
@@ -524,9 +538,24 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
                         L.m_jlo[id] = 0;
                     }
                 }
+                __syncthreads();
+                const int nbig = min(s_nbig, kLvBigCap);
+                for (int qb = 0; qb < nbig; ++qb) {
+                    const int bpm = s_big[qb], bc = L.p_c[qb], boff = L.p_off[qb];
+                    const float bS = L.m_score[bpm];
+                    const int bdp = member_depth(L.m_info[bpm]);
+                    const float *row = s_lp + bdp * Kp;
+                    for (int r = 1 + tid; r <= bc; r += NT) {
+                        const int id = head_base + boff + r - 1;
+                        L.m_score[id] = bS + row[r];
+                        L.m_info[id] = pack_member(bpm, r, bdp + 1);
+                        L.m_jlo[id] = 0;
+                    }
+                }
+                __syncthreads();
+                if (tid == 0) s_nbig = 0;
                 H += total;
             }
-            if (head_base + H > limit) return -1;
             __syncthreads();
             hs = head_base;
             he = head_base + H;
@@ -1198,7 +1227,7 @@ __global__ __launch_bounds__(kBuildThreads) void build_kernel(
             deep += chain >= worst ? 1 : 0;
         }
         const bool bushy = B >= 2 && s_lp[0] + s_lp[Kp + min(3, K - 1)] >= worst;
-        use_levels = N > 256 || (N >= 96 && (deep >= 3 || bushy));
+        use_levels = N > 256 || (N >= 48 && (deep >= 3 || bushy));
     }
     int level_n = -1;
     if (use_levels) {
