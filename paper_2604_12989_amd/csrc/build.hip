@@ -67,7 +67,7 @@ __device__ bool tuple_before(const uint32_t *s_node, int pa, int ra, int pb, int
 //
 // The tree is the set of the N best prefixes (Proposition 2) under the total order "score
 // descending, then rank tuple", and the pop order of Algorithm 1 is that order.  Instead of N
-// dependent pops, all 256 threads work depth by depth:
+// dependent pops, the workgroup works depth by depth:
 //   * "alive" is a score bucket cut: the score range [lp[0][N-1], lp[0][0]] is divided into 256
 //     equal buckets (bucket 0 the best; one more bucket takes everything below the range), a
 //     histogram of every prefix known so far is kept, and the cut b* is the first bucket at which
@@ -87,8 +87,12 @@ __device__ bool tuple_before(const uint32_t *s_node, int pa, int ra, int pb, int
 //     survived, the construction gives up.
 //   * the end: the members above the cut are ranked exactly (bucket position plus an all-pairs
 //     count inside the bucket, ties by rank tuple) and the first N become nodes 1..N.
-//   * levels with at most 64 parents (with the early cut: nearly all levels of a deep tree) are
-//     run by one wave without barriers (see wave_levels).
+//   * levels with at most 64 parents are run by one wave without barriers (see wave_levels); a
+//     level whose candidates do not fit their arrays is counted by bucket first, the cut moves,
+//     and its children are counted again.
+//   * where the prefixes entered up front already give a cut (peaked rows), the members are not
+//     found depth by depth at all but by generations: by the number of their non-zero ranks, of
+//     which there are at most log2(N + 1) + 1 (see by_generations).
 // Giving up (a cut that cannot be proven, or a capacity that heavy ties exceed) returns -1 and
 // the caller runs the sequential pops instead.
 // ------------------------------------------------------------------------------------------
