@@ -273,6 +273,19 @@ def test_build_more_than_sixteen_positions(B, spike, N, K, build_algo):
     assert o["depth"].max() > 16
 
 
+@pytest.mark.parametrize("p_top,N", [(0.3, 256), (0.6, 256), (0.6, 512), (0.9, 256), (0.9, 512), (0.9, 1024), (0.97, 128)])
+def test_build_rows_peaked_at_a_given_probability(p_top, N, build_algo):
+    # every draft row with one token at probability p_top: at 0.9 the whole tree comes from the
+    # prefixes entered up front and is enumerated by generations; at 0.6 and N = 512 that attempt
+    # lets in too many members and the levels take over; at 0.3 no cut is known up front
+    import paper_2604_12989_amd as dd
+    x = di.peaked_draft_logits(31, 16, 30000, p_top)
+    tok, lp = oracle.topk(x, min(N, 30000))
+    before = dd.build_giveups()
+    _check_build(tok, lp, N)
+    assert dd.build_giveups() == before
+
+
 def test_build_rows_with_minus_infinity(build_algo):
     # masked vocabulary: rows end in -inf log-probabilities, which never become nodes
     rng = np.random.default_rng(9)
