@@ -286,7 +286,7 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
     const float chain3 = B >= 3 ? (s_lp[0] + s_lp[Kp]) + s_lp[2 * Kp] : -INFINITY;
     const bool walks = chain3 > kLvNeg && bucket_of(chain3) < kLvBuckets;
     // ranks 1 .. seed_ranks off the chain are entered: 16 up to N = 256, N/16 beyond (at most 64)
-    const int seed_ranks = min(kLvSeedRanksMax, max(16, N >> 4));
+    const int seed_ranks = min(kLvSeedRanksMax, max(32, N >> 3));
     if (walks) {
         // scores of the chain's nodes, summed in path order by one thread (the row maxima fetched
         // eight at a time, as in the walk above): s_cc[i] = node at depth i, s_cc[0] = 0
@@ -451,10 +451,11 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
     // continuation node counts its children of rank >= 1 at or above the cut (a prefix of its
     // sorted row): they are the heads of the next generation.  The cut is left where it is
     // (allowed: see the settled levels below), so nothing is bucketed and no histogram is kept;
-    // if that lets in more members than a tight cut would (N + N/2 + 64), the construction starts
-    // over level by level.  Returns the number of members, or -1.
+    // if that lets in far more members than a tight cut would (beyond 3.5 N + 64), the
+    // construction starts over level by level; a smaller surplus is shed when the members are
+    // ranked.  Returns the number of members, or -1.
     auto by_generations = [&]() -> int {
-        const int limit = min(L.capm, N + N / 2 + 64);
+        const int limit = min(L.capm, 3 * N + N / 2 + 64);
         const int cap = min(K, N);
         auto alive = [&](float v) { return v > kLvNeg && bucket_of(v) <= bstar; };
         int hs = 0, he = 1, Mg = 1;
@@ -1076,14 +1077,21 @@ __device__ int level_build(const float *s_lp, int Kp, int B, int K, int N, Level
     }
     __syncthreads();
     const int hb = tid <= bstar ? s_histv[tid] : 0;
+    if (tid == 0) s_bstar = bstar;
     int total_alive;
     const int start = build_block_scan(hb, s_w, &total_alive);
     s_pref[tid] = start;
     if (tid == 0) s_pref[kLvBuckets] = total_alive;
-    if (bstar == kLvBuckets) total_alive += s_histv[kLvBuckets];
+    // The members are every prefix at or above the cut, so the N best of them are the tree: the
+    // cut moves up to the bucket that holds the N-th best member, and whatever the construction
+    // let in beyond it (a cut left alone while members were enumerated) is not ranked at all.
+    if (start < N && start + hb >= N) s_bstar = tid;
     uint16_t *sorted = reinterpret_cast<uint16_t *>(L.c_info);
     uint16_t *node_id = reinterpret_cast<uint16_t *>(L.c_score);
     __syncthreads();
+    bstar = min(bstar, s_bstar);
+    if (bstar == kLvBuckets) total_alive += s_histv[kLvBuckets];
+    else total_alive = s_pref[bstar] + s_histv[bstar];
     for (int m = 1 + tid; m < M; m += NT) {
         const int bk = bucket_of(L.m_score[m]);
         if (bk <= bstar) sorted[s_pref[bk] + atomicAdd(&s_histc[bk], 1)] = (uint16_t)m;
