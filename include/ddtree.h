@@ -249,8 +249,9 @@ int ddtree_compact(const void *k_tree, const void *v_tree, const int32_t *path,
 /*
  * Construction used by ddtree_build (Algorithm 1 defines the result; both constructions produce
  * it bit for bit).  DDTREE_BUILD_POPS runs the best-first pops one after the other on one
- * wavefront; DDTREE_BUILD_LEVELS finds the same N best prefixes (Proposition 2) depth by depth
- * with the whole workgroup and falls back to the pops when heavy score ties defeat its bounds;
+ * wavefront; DDTREE_BUILD_LEVELS finds the same N best prefixes (Proposition 2) as a set, depth
+ * by depth or, on peaked rows, by the number of non-zero ranks in a prefix, orders them, and
+ * falls back to the pops when heavy score ties defeat its bounds;
  * DDTREE_BUILD_AUTO (the default) picks per sequence from the budget and the shape of the
  * log-probabilities.  Process-wide, takes effect at the next ddtree_build call; meant for
  * tests and tuning.  Returns DDTREE_ERR_ARG for any other value.
