@@ -216,6 +216,7 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(
     __shared__ int s_post[DDTREE_MAX_N + 1];
     __shared__ int s_tok[DDTREE_MAX_N + 1];
     __shared__ int s_par[DDTREE_MAX_N + 1];
+    __shared__ int s_dep[DDTREE_MAX_N + 1];
     __shared__ int s_path[DDTREE_MAX_B + 1];
     __shared__ int s_len;
     const int tid = threadIdx.x;
@@ -223,27 +224,35 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(
     const int n = n_nodes[seq];
     const size_t base = (size_t)seq * T;
     for (int i = tid; i < T; i += kWalkThreads) {
+        // Everything a row needs is requested before the node count is looked at, so that its
+        // arrival and theirs overlap: the first eight partial results of the row (padding rows
+        // have none written: what is read there is never used), its token, parent and depth.
+        const ArgPart *pp = part + (base + i) * splits;
+        ArgPart a[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a[u] = u < splits ? pp[u] : ArgPart{-INFINITY, -1};
+        const int tk = tokens[base + i], pr = parent[base + i], dp = depth[base + i];
+        const bool in_tree = i <= n;
         int post = -1;
-        if (i <= n) {
-            // the row's segments, eight partial results in flight at a time
-            const ArgPart *pp = part + (base + i) * splits;
-            float bv = -INFINITY;
-            for (int s0 = 0; s0 < splits; s0 += 8) {
-                ArgPart a[8];
+        float bv = -INFINITY;
+        for (int s0 = 0; s0 < splits; s0 += 8) {
+            if (s0 > 0) {
 #pragma unroll
                 for (int u = 0; u < 8; ++u) a[u] = s0 + u < splits ? pp[s0 + u] : ArgPart{-INFINITY, -1};
-#pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    if (s0 + u < splits && (post < 0 || a[u].val > bv)) {
-                        // later segments hold higher ids: strict > keeps the first maximum
-                        bv = a[u].val;
-                        post = a[u].idx;
-                    }
             }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (s0 + u < splits && (post < 0 || a[u].val > bv)) {
+                    // later segments hold higher ids: strict > keeps the first maximum
+                    bv = a[u].val;
+                    post = a[u].idx;
+                }
         }
+        if (!in_tree) post = -1;
         s_post[i] = post;
-        s_tok[i] = i <= n ? tokens[base + i] : -1;
-        s_par[i] = i <= n ? parent[base + i] : -1;
+        s_tok[i] = in_tree ? tk : -1;
+        s_par[i] = in_tree ? pr : -1;
+        s_dep[i] = dp;
         if (posterior) posterior[base + i] = post;
     }
     if (tid <= B) s_path[tid] = tid == 0 ? 0 : -1;
@@ -258,7 +267,7 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(
             j = pj;
         }
         if (ok) {
-            const int d = depth[base + i];
+            const int d = s_dep[i];
             if (d >= 1 && d <= B) {
                 s_path[d] = i;
                 atomicMax(&s_len, d);
