@@ -376,13 +376,17 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # ------------------------------------------------------------------ the step's distribution
+    # (the same uninstrumented step in blocks of eight; taken first, so that the timed loop below
+    # meets a chip that is already at its working clocks whatever --warmup says)
+    step_us = step_distribution(torch, wl)
+
     # ------------------------------------------------------------------ warm-up, then the timed loop
     elapsed = timed_loop(torch, wl, args.steps, args.warmup)
     ms_per_step = 1e3 * elapsed / args.steps
     steps_per_s = args.steps / elapsed
     n_acc = [int(v) for v in wl.acc["n_accepted"].cpu()]
     n_acc = n_acc[0] if batch == 1 else n_acc
-    step_us = step_distribution(torch, wl)
 
     # ------------------------------------------------------------------ roofline of the main kernel
     flops = wl.attn_flops()
