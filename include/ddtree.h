@@ -147,7 +147,7 @@ int ddtree_build(const int32_t *topk_tok, const float *topk_lp, int batch, int B
  *              DDTREE_DTYPE_FP32 (fp32 throughout)
  *   out        [device] [batch*T, Hq, D], same dtype as q
  * Requires Hq % Hkv == 0, D a multiple of 8 and <= 256, T <= DDTREE_MAX_N + 1,
- * batch <= DDTREE_MAX_BATCH.  bf16 with D = 128 runs on the matrix cores.
+ * batch <= DDTREE_MAX_BATCH.  bf16 with D = 128 (and Hkv <= 32768) runs on the matrix cores.
  */
 int ddtree_verify_attn(const void *q, const void *k_cache, const void *v_cache,
                        const void *k_tree, const void *v_tree, const uint64_t *ancestor_mask,

@@ -54,23 +54,52 @@ constexpr int kVRowBytes = 288;                  // V tile row in LDS: 256 B + 3
 constexpr int kKTileBytes = kKT * kKRowBytes;    // 17408 = 17 DMA blocks of 1 KB
 constexpr int kVTileBytes = kKT * kVRowBytes;    // 18432 = 18 DMA blocks of 1 KB
 constexpr int kStageBytes = kKTileBytes + kVTileBytes;
-constexpr int kAttnLdsBytes = kAttnStages * kStageBytes;
+constexpr int kRingBytes = kAttnStages * kStageBytes;
+// Behind the ring: the ancestor-mask words of the workgroup's rows for up to kMaskStages tree tiles
+// of its key range, one 64-bit word per (tree tile, row), staged once by the prologue so that the
+// masked steps read LDS and no global load sits in the key loop.
+constexpr int kMaskStages = 8;
+constexpr int kMaskStageBytes = kWaves * 32 * 8;
+constexpr int kAttnLdsBytes = kRingBytes + kMaskStages * kMaskStageBytes;
+static_assert(kAttnLdsBytes <= 160 * 1024, "fits the LDS of a compute unit");
 
 struct AttnArgs {
     int32_t kv_start[DDTREE_MAX_BATCH];  // first cache row of each sequence
     int32_t kv_len[DDTREE_MAX_BATCH];    // its number of cache rows
-    // matrix-core kernel only: the sequences longest cache first, and the first work item of
-    // each of the 8 XCDs' runs (run x = work items xcd_start[x] .. xcd_start[x + 1] - 1)
-    int32_t order[DDTREE_MAX_BATCH];     // (32-bit entries: read with scalar loads)
+    // matrix-core kernel only: the sequences longest cache first -- entry p = {sequence, its
+    // first cache row, its number of cache rows, 0}, one 16-byte scalar load -- and the first work
+    // item of each of the 8 XCDs' runs (run x = work items xcd_start[x] .. xcd_start[x + 1] - 1)
+    int32_t by_length[DDTREE_MAX_BATCH][4];
     int32_t xcd_start[9];
-    uint32_t g_magic;                    // ceil(2^32 / G) for G = Hq / Hkv >= 2 (x / G = mulhi(x, g_magic) for x < 2^26), 0 for G = 1
+    // Reciprocals for the divisions of the work-item decode, ceil(2^32 / d): x / d = mulhi(x, magic)
+    // whenever x * d < 2^32.  0 where d = 1 or where the host could not guarantee that bound (the
+    // kernel then divides).
+    int32_t group_size;                  // G = Hq / Hkv
+    uint32_t g_magic;                    // d = G, x = a row index
+    uint32_t per_grp_magic;              // d = work items per (sequence, kv head), x = a work item
+    uint32_t main_tiles_magic;           // d = whole row tiles, x = a work item within its group
+    uint32_t hkv_magic;                  // d = Hkv, x = a group
+    uint32_t splits_magic[2];            // d = key ranges of a whole / of the tail tile, x = key tiles * range + d - 1
 };
+
+__host__ __device__ __forceinline__ uint32_t magic_of(uint64_t d, uint64_t x_max)
+{
+    return (d >= 2 && x_max * d < 0x100000000ull) ? (uint32_t)((0x100000000ull + d - 1) / d) : 0u;
+}
+__device__ __forceinline__ int div_by(int x, int d, uint32_t magic)
+{
+    return magic != 0u ? (int)__umulhi((uint32_t)x, magic) : (d == 1 ? x : x / d);
+}
+
+// Shapes of the matrix-core kernel.  (The bound on the KV heads keeps the pitch between cache
+// rows below 2^24 bytes, which the kernel's 24-bit address multiplies rely on.)
+static bool mfma_shape(int dtype, int D, int Hkv) { return dtype == DDTREE_DTYPE_BF16 && D == kHD && Hkv <= 32768; }
 
 AttnPlan attn_plan(int batch, int T, int Hq, int Hkv, int D, long long sum_L, int dtype)
 {
     AttnPlan p{};
     p.splits = 1;
-    if (!(dtype == DDTREE_DTYPE_BF16 && D == kHD)) return p;  // generic path needs no scratch
+    if (!mfma_shape(dtype, D, Hkv)) return p;  // generic path needs no scratch
     const int G = Hq / Hkv;
     const long long M = (long long)T * G;
     const int nblk = (int)((M + 31) / 32);
@@ -279,61 +308,50 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     const int xcd = (int)blockIdx.x & 7;
     const int wid = args.xcd_start[xcd] + ((int)blockIdx.x >> 3);
     if (wid >= args.xcd_start[xcd + 1]) return;
-    const int grp = wid / per_grp;                        // (sequence, kv head) pair
+    // (the divisions of this decode are multiplications by the host's reciprocals: a division by a
+    // run-time value is some thirty instructions, and all of this sits before the first tile request)
+    const int grp = div_by(wid, per_grp, args.per_grp_magic);  // (sequence, kv head) pair
     const int wg = wid - grp * per_grp;
     const bool tail = wg >= main_tiles * main_splits;
-    const int mt = tail ? main_tiles : wg % main_tiles;
-    const int split = tail ? wg - main_tiles * main_splits : wg / main_tiles;
+    const int wg_split = div_by(wg, main_tiles, args.main_tiles_magic);
+    const int mt = tail ? main_tiles : wg - wg_split * main_tiles;
+    const int split = tail ? wg - main_tiles * main_splits : wg_split;
     const int splits = tail ? tail_splits : main_splits;  // key ranges of this tile
-    const int hk = grp % Hkv;
-    const int seq = args.order[grp / Hkv];
-    const int G = Hq / Hkv;
+    const int grp_seq = div_by(grp, Hkv, args.hkv_magic);
+    const int hk = grp - grp_seq * Hkv;
+    const int seq = args.by_length[grp_seq][0];
+    const int G = args.group_size;
     const int W = (T + 63) >> 6;
     const int M = T * G;
-    const int L0 = args.kv_start[seq];
-    const int L = args.kv_len[seq];
+    const int L0 = args.by_length[grp_seq][1];
+    const int L = args.by_length[grp_seq][2];
     // this tile's blocks of 32 rows: wave w owns block w of the tile
     const int first_blk = tail_splits > 0 ? mt * 8 : mt * blk_base + min(mt, blk_extra);
     const int n_blk = tail_splits > 0 ? (tail ? blk_extra : 8) : blk_base + (mt < blk_extra ? 1 : 0);
     const int m0 = first_blk * 32;
     const int m_end = min(M, (first_blk + n_blk) * 32);
-    const int last_node = min(T - 1, (m_end - 1) / G);
+    const int last_node = min(T - 1, div_by(m_end - 1, G, args.g_magic));
     const int n_cache_tiles = (L + kKT - 1) / kKT;
     const int n_tree_tiles = last_node / kKT + 1;
     const int nt = n_cache_tiles + n_tree_tiles;
     // key ranges rounded up, so that a surplus tile goes to the early ranges: the last range holds
     // the tree tiles, which carry the mask work on top
     // (nt < 2^25 key tiles and at most 32 key ranges: 32-bit arithmetic is exact)
-    const int t_begin = (int)(((unsigned)nt * (unsigned)split + (unsigned)splits - 1u) / (unsigned)splits);
-    const int t_end = (int)(((unsigned)nt * (unsigned)(split + 1) + (unsigned)splits - 1u) / (unsigned)splits);
+    const uint32_t s_magic = args.splits_magic[tail ? 1 : 0];
+    const int t_begin = div_by(nt * split + splits - 1, splits, s_magic);
+    const int t_end = div_by(nt * (split + 1) + splits - 1, splits, s_magic);
     const bool wave_active = m0 + wave * 32 < m_end;
 
-    // this lane's query row
-    const int row_m = m0 + wave * 32 + l32;
-    const bool rvalid = row_m < m_end;
-    const int node_ = rvalid ? row_m / G : 0;
-    const int rowg_ = (seq * T + node_) * Hq + hk * G + (rvalid ? row_m - node_ * G : 0);
-    // Q^T operand: lane holds Q[row][16*ks + 8*half .. +8]
-    bf16x8 qreg[8];
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (rvalid) v = *reinterpret_cast<const uint4 *>(q + (size_t)rowg_ * kHD + ks * 16 + half * 8);
-        qreg[ks] = __builtin_bit_cast(bf16x8, v);
-    }
-    // Past the query loads nothing derived from the lane's row is kept: the masked steps, the
+    // Nothing derived from the lane's row is kept through the key loop: the masked steps, the
     // fetch of the row's own mask bit and the epilogue work the row out again from the thread
-    // index (a handful of instructions: the division by G is a multiplication by the host's
-    // reciprocal), read through an empty statement so that the compiler does not fall back on the
-    // copies above -- held through the key loop, those were spilled, and a spill's reload between
-    // the query loads and the first tile requests made the requests wait for the queries.
+    // index (a handful of instructions), read through an empty statement so that the compiler does
+    // not fall back on one copy -- held through the key loop, such values were spilled.
     auto lane_row = [&](int &rm, bool &rv, int &nd) __attribute__((always_inline)) {
         int t = (int)threadIdx.x;
         asm volatile("" : "+v"(t));
         rm = m0 + ((t >> 6) << 5) + (t & 31);
         rv = rm < m_end;
-        const int dv = args.g_magic != 0u ? (int)__umulhi((uint32_t)rm, args.g_magic) : rm;
-        nd = rv ? dv : 0;
+        nd = rv ? div_by(rm, G, args.g_magic) : 0;
     };
     auto mask_row = [&](int nd) __attribute__((always_inline)) { return mask + ((size_t)seq * T + nd) * W; };
     // the mask word that holds the row's own bit (a real tree node sees itself; padding rows produce
@@ -341,6 +359,17 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     // would hold a register through the whole loop, or be waited for and spilled before the loop
     uint32_t own_word = 0u;
 
+    const uint32_t row_bytes = (uint32_t)Hkv * kHD * 2;  // bytes between consecutive keys in global memory
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    // first cache row and first tree row of this (sequence, kv head), as byte addresses; a tile is
+    // kKT consecutive keys, tile_bytes apart (the cache bases are formed but never used when the
+    // sequence has no cache rows)
+    const unsigned char *const kc0 = reinterpret_cast<const unsigned char *>(k_cache) + ((size_t)L0 * Hkv + hk) * (kHD * 2);
+    const unsigned char *const vc0 = reinterpret_cast<const unsigned char *>(v_cache) + ((size_t)L0 * Hkv + hk) * (kHD * 2);
+    const unsigned char *const kt0 = reinterpret_cast<const unsigned char *>(k_tree) + ((size_t)seq * T * Hkv + hk) * (kHD * 2);
+    const unsigned char *const vt0 = reinterpret_cast<const unsigned char *>(v_tree) + ((size_t)seq * T * Hkv + hk) * (kHD * 2);
+    const uint32_t tile_bytes = (uint32_t)kKT * row_bytes;
+    const int n_tiles = t_end - t_begin;
     // ---- tile loads: a K tile is 17 and a V tile 18 DMA blocks of 1 KB of LDS; lane l of block b fills
     //      16-byte slot u = 64*b + l, i.e. row u / chunks_per_row, chunk u % chunks_per_row.
     //      The blocks are dealt round-robin to the n_dma loading waves: all eight, or, in a workgroup
@@ -349,8 +378,6 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     //      issues 2 K + 2 V blocks per tile plus at most one more of each: 4, 5 or 6 loads, the
     //      same for whole and ragged tiles (see tiles_in_flight).  The per-lane source offsets
     //      (bytes from the tile's first key) are computed once. ----
-    const uint32_t row_bytes = (uint32_t)Hkv * kHD * 2;  // bytes between consecutive keys in global memory
-    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int n_active = min(kWaves, (m_end - m0 + 31) >> 5);  // waves 0 .. n_active-1 have query rows
     const bool offload = n_active <= 2;
     const int n_dma = offload ? kWaves - n_active : kWaves;
@@ -364,19 +391,13 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         const int u = (n_dma * i + max(dma_rank, 0)) * 64 + lane;
         const int rk = (u * 241) >> 12;   // u / 17 for u < 2048
         const int ck = u - rk * 17;
-        k_src[i] = (uint32_t)min(rk, kKT - 1) * row_bytes + (ck == 16 ? 0 : ck) * 16;  // padding slot: any chunk
+        // (24-bit multiplies: a row index below 64 times a row pitch below 2^24 -- the full multiply-add
+        // leaves its result in a register pair, and six such pairs were kept through the kernel)
+        k_src[i] = __umul24((uint32_t)min(rk, kKT - 1), row_bytes) + (ck == 16 ? 0 : ck) * 16;  // padding slot: any chunk
         const int rv = (u * 3641) >> 16;  // u / 18 for u < 2048
         const int cv = u - rv * 18;
-        v_src[i] = (uint32_t)min(rv, kKT - 1) * row_bytes + (cv >= 16 ? 0 : cv) * 16;
+        v_src[i] = __umul24((uint32_t)min(rv, kKT - 1), row_bytes) + (cv >= 16 ? 0 : cv) * 16;
     }
-    // first cache row and first tree row of this (sequence, kv head), as byte addresses; a tile is
-    // kKT consecutive keys, tile_bytes apart (the cache bases are formed but never used when the
-    // sequence has no cache rows)
-    const unsigned char *const kc0 = reinterpret_cast<const unsigned char *>(k_cache) + ((size_t)L0 * Hkv + hk) * (kHD * 2);
-    const unsigned char *const vc0 = reinterpret_cast<const unsigned char *>(v_cache) + ((size_t)L0 * Hkv + hk) * (kHD * 2);
-    const unsigned char *const kt0 = reinterpret_cast<const unsigned char *>(k_tree) + ((size_t)seq * T * Hkv + hk) * (kHD * 2);
-    const unsigned char *const vt0 = reinterpret_cast<const unsigned char *>(v_tree) + ((size_t)seq * T * Hkv + hk) * (kHD * 2);
-    const uint32_t tile_bytes = (uint32_t)kKT * row_bytes;
     auto issue_tile = [&](int tt, int stage) __attribute__((always_inline)) {
         const bool cache = tt < n_cache_tiles;
         const int tl = cache ? tt : tt - n_cache_tiles;
@@ -412,11 +433,11 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                 const int u = blk * 64 + lane;
                 if (blk < 17) {
                     const int r = (u * 241) >> 12, c = u - r * 17;
-                    dma(kp, (uint32_t)min(r, valid_ - 1) * row_bytes + (c == 16 ? 0 : c) * 16, st + blk * 1024);
+                    dma(kp, __umul24((uint32_t)min(r, valid_ - 1), row_bytes) + (c == 16 ? 0 : c) * 16, st + blk * 1024);
                 }
                 if (blk < 18) {
                     const int r = (u * 3641) >> 16, c = u - r * 18;
-                    dma(vp, (uint32_t)min(r, valid_ - 1) * row_bytes + (c >= 16 ? 0 : c) * 16,
+                    dma(vp, __umul24((uint32_t)min(r, valid_ - 1), row_bytes) + (c >= 16 ? 0 : c) * 16,
                         st + kKTileBytes + blk * 1024);
                 }
             }
@@ -432,15 +453,51 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         else { if (n == 1) vm_wait<4>(); else vm_wait<8>(); }
     };
 
+    const uint32_t lds_base =
+        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+
+    // ---- the first requests: the first key tile, the queries and mask words, two more key tiles.
+    //      Vector memory operations complete in order, so the wait for "all but the last tile
+    //      requested" further down also covers the queries and the mask words. ----
+    if (n_tiles > 0) issue_tile(t_begin, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    // Q^T operand: lane holds Q[row][16*ks + 8*half .. +8]
+    bf16x8 qreg[8];
+    // ancestor-mask words of this lane's row for the first kMaskStages tree tiles of the key range
+    const int tb0 = max(t_begin - n_cache_tiles, 0);                       // first tree tile of the range
+    const int n_stage = max(0, min(t_end - n_cache_tiles - tb0, kMaskStages));  // how many are staged in LDS
+    uint64_t mword[kMaskStages];
+    {
+        int rm, nd;
+        bool rv;
+        lane_row(rm, rv, nd);
+        const size_t rowg = (size_t)(seq * T + nd) * Hq + hk * G + (rv ? rm - nd * G : 0);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (rv) v = *reinterpret_cast<const uint4 *>(q + rowg * kHD + ks * 16 + half * 8);
+            qreg[ks] = __builtin_bit_cast(bf16x8, v);
+        }
+#pragma unroll
+        for (int i = 0; i < kMaskStages; ++i) mword[i] = (rv && i < n_stage) ? mask_row(nd)[tb0 + i] : 0ull;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (n_tiles > 1) issue_tile(t_begin + 1, 1);
+    if (n_tiles > 2) issue_tile(t_begin + 2, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    // LDS address of this lane's row in the staged mask words (both half-waves of a row read the
+    // same word); tree tile tb0 + i is kMaskStageBytes * i further on
+    auto mask_lds = [&]() __attribute__((always_inline)) {
+        int t = (int)threadIdx.x;
+        asm volatile("" : "+v"(t));
+        return lds_base + (uint32_t)(kRingBytes + ((t >> 6) << 8) + ((t & 31) << 3));
+    };
+
     // per-lane LDS read bases (bytes, relative to the tile); everything else is an immediate
     const int k_base = l32 * kKRowBytes + half * 16;  // K: row l32 (+32*kb), column 2*ks + half
     const int lm = lane & 15, dim16 = (lane >> 4) & 1;
     // V: row 4*half + lm/4 (+16*kstep, +8), dims 32*db + 16*dim16 + 4*(lm%4)
     const int v_base = kKTileBytes + (4 * half + (lm >> 2)) * kVRowBytes + 32 * dim16 + 8 * (lm & 3);
-
-    const uint32_t lds_base =
-        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
-    const int n_tiles = t_end - t_begin;
 
     // Operand staging registers: K rows of one 32-key sub-tile (8 k-steps over the head dim) and
     // V columns of one sub-tile (2 k-steps x 4 dim blocks x 2 transposing reads).
@@ -482,34 +539,58 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     auto step = [&](bool slow, floatx16 &cur, floatx16 &nxt, uint32_t (&pin)[8], uint32_t (&pout)[8],
                     uint32_t k_addr, uint32_t v_addr, int t, int kb, bool track, auto &&early) __attribute__((always_inline)) {
         lds_wait_all(kbuf, vbuf);
+        bool dark = false;  // (uniform) no row of this wave sees any key of the sub-tile
         if (slow) {
             const bool is_tree = t >= n_cache_tiles;
             const int tb = t - n_cache_tiles;
             const int valid = is_tree ? min(kKT, T - tb * kKT) : min(kKT, L - t * kKT);
+            uint32_t w32 = ~0u;
             if (is_tree || valid < kKT) {  // tree tiles and a ragged last cache tile
                 uint64_t word = ~0ull;
                 if (is_tree) {
-                    int rm, nd;
-                    bool rv;
-                    lane_row(rm, rv, nd);
-                    word = rv ? mask_row(nd)[tb] : 0ull;
+                    if (tb - tb0 < n_stage) {
+                        // staged by the prologue (zero for rows past the end); the wave has no
+                        // other LDS read in flight at this point
+                        u32x2 w2;
+                        asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)"
+                                     : "=v"(w2)
+                                     : "v"(mask_lds() + (uint32_t)((tb - tb0) * kMaskStageBytes))
+                                     : "memory");
+                        word = ((uint64_t)w2.y << 32) | w2.x;
+                    } else {
+                        int rm, nd;
+                        bool rv;
+                        lane_row(rm, rv, nd);
+                        word = rv ? mask_row(nd)[tb] : 0ull;
+                    }
                 }
                 if (valid < kKT) word &= (1ull << valid) - 1ull;
                 // this lane's keys of the sub-tile: 8 * (v / 4) + 4 * half + v % 4
-                const uint32_t w32 = (uint32_t)(word >> (32 * kb)) >> (4 * half);
+                w32 = ((uint32_t)(word >> (32 * kb)) >> (4 * half)) & 0x0F0F0F0Fu;
+                // (a tree row sees its few ancestors and itself: most (row block, sub-tile) pairs of the
+                // tree tiles are dark, and a dark sub-tile has no maximum to look at)
+                dark = __builtin_amdgcn_ballot_w64(w32 != 0u) == 0ull;
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    if (!((w32 >> ((v >> 2) * 8 + (v & 3))) & 1u)) cur[v] = -INFINITY;
+                for (int v = 0; v < 16; ++v) {
+                    // all ones where the key is visible: the score stays, else it becomes -inf (two
+                    // instructions per score, and no score of a hidden key, whatever its bits, survives)
+                    const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe((int)w32, (v >> 2) * 8 + (v & 3), 1);
+                    cur[v] = __uint_as_float((__float_as_uint(cur[v]) & keep) | (0xFF800000u & ~keep));
+                }
             }
-            float tmax = cur[0];
+            // the maximum of the sub-tile is of interest only to rows still without a reference
+            // (and to the pass that tracks the true maxima)
+            if (!dark && (track || __builtin_amdgcn_ballot_w64(m_ref == -INFINITY) != 0ull)) {
+                float tmax = cur[0];
 #pragma unroll
-            for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, cur[v]);
-            // the other half-wave holds the other 16 keys of this row
-            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax),
-                                                             false, false);
-            tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1])) * scale_log2e;
-            if (track) m_seen = fmaxf(m_seen, tmax);
-            m_ref = m_ref == -INFINITY ? tmax : m_ref;
+                for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, cur[v]);
+                // the other half-wave holds the other 16 keys of this row
+                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax),
+                                                                 false, false);
+                tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1])) * scale_log2e;
+                if (track) m_seen = fmaxf(m_seen, tmax);
+                m_ref = m_ref == -INFINITY ? tmax : m_ref;
+            }
         }
         // The reference is never moved, so the accumulators are never rescaled: exp2 arguments may
         // become positive, which fp32 and bf16 carry exactly as well as negative ones.
@@ -560,6 +641,17 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         });
     };
 
+    // The mask words go to LDS once they are there (the wave has nothing else to do meanwhile: the
+    // first key tile was requested before them).  A word is read back only by the lane that wrote
+    // it and by its twin in the other half of the same wave.
+    if (n_stage > 0 && half == 0) {
+        const uint32_t a = mask_lds();
+#pragma unroll
+        for (int i = 0; i < kMaskStages; ++i)
+            if (i < n_stage)
+                asm volatile("ds_write_b64 %0, %1 offset:%2" ::"v"(a), "v"(mword[i]), "n"(i * kMaskStageBytes) : "memory");
+    }
+
     // ---- the key range, up to three times: once normally; if some row's sum shows that its
     //      scores outgrew the reference, once more to find the true row maxima and a last time with
     //      those as references (rare) ----
@@ -575,9 +667,11 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         // Ring of four stages: while the keys of tile `it` are worked on, tile it+1 is resident
         // (its K operands are requested one sub-tile ahead), tile it+2 is in flight and tile it+3
         // is requested into the stage that tile it-1 has just left.
-        if (n_tiles > 0) issue_tile(t_begin, 0);
-        if (n_tiles > 1) issue_tile(t_begin + 1, 1);
-        if (n_tiles > 2) issue_tile(t_begin + 2, 2);
+        if (pass > 0) {  // (the first pass's tiles were requested at the top of the kernel)
+            if (n_tiles > 0) issue_tile(t_begin, 0);
+            if (n_tiles > 1) issue_tile(t_begin + 1, 1);
+            if (n_tiles > 2) issue_tile(t_begin + 2, 2);
+        }
         tiles_in_flight(n_tiles > 2 ? 1 : 0);  // tiles 0 and 1 have landed
         __syncthreads();
         if (wave_active && n_tiles > 0) {
@@ -675,7 +769,12 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     // no DMA is in flight) and leaves in whole rows, 16 bytes per lane and four rows per store.
     constexpr int kEpiRow = kHD * 2 + 16;  // bytes per staged row: 16-byte aligned, rows 4 banks apart
     static_assert(kWaves * 32 * kEpiRow <= kAttnLdsBytes, "staging fits the ring");
-    unsigned char *stg = smem + wave * (32 * kEpiRow);
+    // (lane-derived addresses are formed here, from the thread index read afresh: formed from the
+    // values at the top of the kernel they would be computed there and spilled)
+    int e_tid = (int)threadIdx.x;
+    asm volatile("" : "+v"(e_tid));
+    const int e_lane = e_tid & 63, e_l32 = e_tid & 31, e_half = (e_tid >> 5) & 1, e_wave = e_tid >> 6;
+    unsigned char *stg = smem + e_wave * (32 * kEpiRow);
     const size_t n_rows = (size_t)batch_n * T * Hq;
     {
         int e_row, e_node;
@@ -702,15 +801,15 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
-                const int dim = db * 32 + g4 * 8 + half * 4;
+                const int dim = db * 32 + g4 * 8 + e_half * 4;
                 const float a0 = o[db][4 * g4 + 0] * mul, a1 = o[db][4 * g4 + 1] * mul;
                 const float a2 = o[db][4 * g4 + 2] * mul, a3 = o[db][4 * g4 + 3] * mul;
                 uint2 val;  // bf16 for the output itself, fp16 for the partial of a key range
                 val.x = part_splits == 0 ? f2bf_pair(a0, a1) : f2h_pair(a0, a1);
                 val.y = part_splits == 0 ? f2bf_pair(a2, a3) : f2h_pair(a2, a3);
-                *reinterpret_cast<uint2 *>(stg + l32 * kEpiRow + dim * 2) = val;
+                *reinterpret_cast<uint2 *>(stg + e_l32 * kEpiRow + dim * 2) = val;
             }
-        if (part_splits != 0 && e_valid && half == 0) {
+        if (part_splits != 0 && e_valid && e_half == 0) {
             // log2-sum-exp and scale of this key range, indexed by global row
             const size_t ridx = (size_t)((seq * T + e_node) * Hq + hk * G + (e_row - e_node * G));
             lse[(size_t)split * n_rows + ridx] =
@@ -721,13 +820,13 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         }
     }
     uint16_t *dst_base = part_splits == 0 ? out : part + (size_t)split * n_rows * kHD;
-    const int chunk = lane & 15;
-    int r = m0 + wave * 32 + (lane >> 4);  // rows lane >> 4, + 4, + 8, ... of the block
-    int node = r / G, g = r - node * G;
+    const int chunk = e_lane & 15;
+    int r = m0 + e_wave * 32 + (e_lane >> 4);  // rows lane >> 4, + 4, + 8, ... of the block
+    int node = div_by(r, G, args.g_magic), g = r - node * G;
 #pragma unroll
     for (int rr = 0; rr < 8; ++rr) {
         if (r < m_end) {
-            const uint4 v = *reinterpret_cast<const uint4 *>(stg + (rr * 4 + (lane >> 4)) * kEpiRow + chunk * 16);
+            const uint4 v = *reinterpret_cast<const uint4 *>(stg + (rr * 4 + (e_lane >> 4)) * kEpiRow + chunk * 16);
             const size_t rg = (size_t)(seq * T + node) * Hq + hk * G + g;
             *reinterpret_cast<uint4 *>(dst_base + rg * kHD + chunk * 8) = v;
         }
@@ -974,10 +1073,12 @@ static int verify_attn_impl(const void *q, const void *k_cache, const void *v_ca
         return DDTREE_ERR_ARG;
     if (dtype != DDTREE_DTYPE_BF16 && dtype != DDTREE_DTYPE_FP32) return DDTREE_ERR_ARG;
     if (!(softmax_scale > 0.0f) || !(softmax_scale < 1e30f)) return DDTREE_ERR_ARG;
-    AttnArgs args;
+    AttnArgs args{};
     {
         const uint32_t G = (uint32_t)(Hq / Hkv);
-        args.g_magic = G >= 2 ? (uint32_t)((0x100000000ull + G - 1) / G) : 0u;
+        args.group_size = (int32_t)G;
+        args.g_magic = magic_of(G, (uint64_t)T * G);
+        args.per_grp_magic = args.main_tiles_magic = args.hkv_magic = args.splits_magic[0] = args.splits_magic[1] = 0u;
     }
     long long sum_L = 0;
     for (int s = 0; s < batch; ++s) {
@@ -990,7 +1091,7 @@ static int verify_attn_impl(const void *q, const void *k_cache, const void *v_ca
     if (sum_L > 0 && (!k_cache || !v_cache)) return DDTREE_ERR_ARG;
     hipStream_t st = as_stream(stream);
 
-    if (dtype == DDTREE_DTYPE_BF16 && D == kHD) {
+    if (mfma_shape(dtype, D, Hkv)) {
         AttnPlan p = attn_plan(batch, T, Hq, Hkv, D, sum_L, dtype);
         if (!ws_ok(workspace, workspace_bytes, p.bytes)) return DDTREE_ERR_WORKSPACE;
         char *wsb = static_cast<char *>(workspace);
@@ -1006,10 +1107,26 @@ static int verify_attn_impl(const void *q, const void *k_cache, const void *v_ca
         const long long per_seq = (long long)Hkv * (main_tiles * p.splits + p.tail_splits);
         const long long total = per_seq * batch;
         if (total > (1ll << 28)) return DDTREE_ERR_ARG;
-        for (int i = 0; i < batch; ++i) args.order[i] = i;
-        std::stable_sort(args.order, args.order + batch, [&](int32_t a, int32_t b) {
-            return kv_len[a] > kv_len[b];
-        });
+        {
+            long long max_len = 0;
+            for (int i = 0; i < batch; ++i) max_len = std::max<long long>(max_len, kv_len[i]);
+            const uint64_t per_grp = (uint64_t)(main_tiles * p.splits + p.tail_splits);
+            const uint64_t nt_max = (uint64_t)((max_len + kKT - 1) / kKT + (T + kKT - 1) / kKT);
+            args.per_grp_magic = magic_of(per_grp, (uint64_t)total);
+            args.main_tiles_magic = magic_of((uint64_t)main_tiles, per_grp);
+            args.hkv_magic = magic_of((uint64_t)Hkv, (uint64_t)batch * Hkv);
+            args.splits_magic[0] = magic_of((uint64_t)p.splits, nt_max * p.splits + p.splits);
+            args.splits_magic[1] = magic_of((uint64_t)p.tail_splits, nt_max * p.tail_splits + p.tail_splits);
+        }
+        int32_t order[DDTREE_MAX_BATCH];
+        for (int i = 0; i < batch; ++i) order[i] = i;
+        std::stable_sort(order, order + batch, [&](int32_t a, int32_t b) { return kv_len[a] > kv_len[b]; });
+        for (int i = 0; i < batch; ++i) {
+            args.by_length[i][0] = order[i];
+            args.by_length[i][1] = kv_start[order[i]];
+            args.by_length[i][2] = kv_len[order[i]];
+            args.by_length[i][3] = 0;
+        }
         long long work_total = 0;
         for (int i = 0; i < batch; ++i) work_total += per_seq * ((long long)kv_len[i] + T);
         {
@@ -1018,7 +1135,7 @@ static int verify_attn_impl(const void *q, const void *k_cache, const void *v_ca
             args.xcd_start[0] = 0;
             while (x < 8) {
                 const long long target = (work_total * x + 7) / 8;
-                const int sq = args.order[pos];
+                const int sq = order[pos];
                 const long long w = (long long)kv_len[sq] + T;
                 if (pos < batch - 1 && done + per_seq * w < target) {
                     done += per_seq * w;
