@@ -612,6 +612,27 @@ def test_attn_batched_ragged():
         assert attn_err(got[b], refs[b]) < 1e-2
 
 
+def test_attn_key_range_with_many_tree_tiles():
+    """Eight sequences of 1024 rows on eight KV heads: 256 workgroups with the key range unsplit, so
+    each walks all 16 tree tiles (more than the kernel keeps mask words for on chip: the later ones
+    are fetched as it goes), behind short, empty and ragged caches."""
+    batch, T, Hq, Hkv, D = 8, 1024, 8, 8, 128
+    Ls = [100, 0, 64, 7, 129, 1, 63, 200]
+    off = np.concatenate([[0], np.cumsum(Ls)]).astype(np.int32)
+    rng = np.random.default_rng(1025)
+    qs, kcs, vcs, kts, vts, ms = [], [], [], [], [], []
+    for b in range(batch):
+        q, kc, vc, kt, vt, mask = _attn_case(170 + b, T, Ls[b], Hq, Hkv, D, "bf16")
+        qs.append(q); kcs.append(kc); vcs.append(vc); kts.append(kt); vts.append(vt); ms.append(mask)
+    got = gu.gpu_attn(np.concatenate(qs), np.concatenate(kcs), np.concatenate(vcs),
+                      np.concatenate(kts), np.concatenate(vts), np.stack(ms), off, batch, T, "bf16")
+    for b in range(batch):
+        nodes = np.concatenate([[0, 1, 63, 64, 511, 512, 513, 575, 576, 577, 960, 1022, 1023], rng.integers(0, T, 30)])
+        pairs = np.stack([nodes, rng.integers(0, Hq, nodes.size)], axis=1).astype(np.int32)
+        ref = oracle.verify_attn(qs[b], kcs[b], vcs[b], kts[b], vts[b], ms[b], pairs=pairs)
+        assert attn_err(got[b][pairs[:, 0], pairs[:, 1]], ref) < 1e-2, b
+
+
 def test_attn_randomized_shapes():
     # seeded sweep over head layouts, row counts, ragged batches and cache lengths (every tiling
     # and key split the planner can choose), checked on sampled (node, head) pairs
