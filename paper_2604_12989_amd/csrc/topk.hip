@@ -12,6 +12,8 @@
 //
 // Every candidate is the 64-bit composite (key << 32) | ~token_id, so all composites of a row
 // are distinct and "larger composite" is exactly "larger logit, or equal logit and smaller id".
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace ddt {
@@ -286,9 +288,12 @@ __device__ bool block_bucket_rank(const float (&x)[NS], Comp comp, uint32_t acti
     return true;
 }
 
-// exp(y) for y <= 0 in fp64, about 1 ulp: y = (64 n + j) ln2/64 + r with |r| <= ln2/128, so
-// exp(y) = 2^n * 2^(j/64) * exp(r); 2^(j/64) comes from a 64-entry table and exp(r) from its
-// Taylor polynomial of degree 5 (remainder below 4e-17).  Returns 0 below the fp64 range.
+// exp(y) for y <= 0 in fp64 to a relative error below 4e-11: y = (64 n + j) ln2/64 + r with
+// |r| <= ln2/128, so exp(y) = 2^n * 2^(j/64) * exp(r); 2^(j/64) comes from a 64-entry table and
+// exp(r) from its Taylor polynomial of degree 3 (remainder r^4/24 < 3.6e-11; the reduction by one
+// fp64 multiple of ln2/64 is off by less than 6e-14).  The row's log-sum-exp needs its sum to some
+// 1e-8 for a log-probability that is right to the last fp32 bit; every fp64 instruction here is
+// paid 9.7 million times a step.  Returns 0 below the fp64 range.
 __device__ const double kExp2Table[64] = {
     0x1.0000000000000p+0, 0x1.02c9a3e778061p+0, 0x1.059b0d3158574p+0, 0x1.0874518759bc8p+0,
     0x1.0b5586cf9890fp+0, 0x1.0e3ec32d3d1a2p+0, 0x1.11301d0125b51p+0, 0x1.1429aaea92de0p+0,
@@ -309,12 +314,9 @@ __device__ const double kExp2Table[64] = {
 __device__ __forceinline__ double exp_nonpositive(double y, const double *s_tab)
 {
     const double k = rint(y * 92.33248261689366);              // 64 / ln 2
-    double r = fma(k, -0x1.62e42fefa0000p-7, y);               // ln2/64, leading 36 bits
-    r = fma(k, -0x1.cf79abc9e3b3ap-46, r);                     // ln2/64, remainder
+    const double r = fma(k, -0x1.62e42fefa39efp-7, y);         // ln2/64
     const int ki = (int)k;
-    double p = fma(r, 1.0 / 120.0, 1.0 / 24.0);
-    p = fma(r, p, 1.0 / 6.0);
-    p = fma(r, p, 0.5);
+    double p = fma(r, 1.0 / 6.0, 0.5);
     p = fma(r, p, 1.0);
     p = fma(r, p, 1.0);
     const double v = ldexp(s_tab[ki & 63] * p, ki >> 6);
@@ -459,10 +461,34 @@ __global__ __launch_bounds__(kChunkThreads) void topk_chunk_kernel(
     //      stays accurate when one token holds nearly all the probability (its log-probability
     //      is -log1p(tiny), and a sum that starts at 1 would have rounded the tiny part away).
     //      Elements equal to the maximum are counted, not added.
+    //      (The four elements of a 16-byte load go through the exponential side by side, in one
+    //      basic block: taken one slot at a time behind a test of its own, each exponential is a
+    //      chain of dependent fp64 instructions and an LDS read with nothing to overlap it.)
     double acc = 0.0;
     int neq = 0;
+    static_assert(kVecPerThread == 3, "the grouping below is written for three loads per thread");
+    auto exp_slots = [&](auto First, auto Count) {
+        constexpr int s0 = decltype(First)::value, cnt = decltype(Count)::value;
+        double e[cnt];
 #pragma unroll
-    for (int s = 0; s < kSlots; ++s)
+        for (int j = 0; j < cnt; ++j) e[j] = exp_nonpositive((double)x[s0 + j] - (double)cmax, s_exp2);
+#pragma unroll
+        for (int j = 0; j < cnt; ++j) {
+            const bool eq = x[s0 + j] == cmax;
+            neq += eq ? 1 : 0;
+            acc += eq ? 0.0 : e[j];
+        }
+    };
+    // (the four slots of a load are active together; the first two loads of a wave mostly both are)
+    if ((active & 0xFFu) == 0xFFu) {
+        exp_slots(std::integral_constant<int, 0>{}, std::integral_constant<int, 8>{});
+    } else {
+        if (active & 0x1u) exp_slots(std::integral_constant<int, 0>{}, std::integral_constant<int, 4>{});
+        if (active & 0x10u) exp_slots(std::integral_constant<int, 4>{}, std::integral_constant<int, 4>{});
+    }
+    if (active & 0x100u) exp_slots(std::integral_constant<int, 8>{}, std::integral_constant<int, 4>{});
+#pragma unroll
+    for (int s = 4 * kVecPerThread; s < kSlots; ++s)
         if ((active >> s) & 1u) {
             const bool eq = x[s] == cmax;
             neq += eq ? 1 : 0;
