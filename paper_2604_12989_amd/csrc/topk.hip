@@ -564,10 +564,14 @@ __global__ __launch_bounds__(kChunkThreads) void topk_chunk_kernel(
 constexpr int kMergeThreads = 1024;
 constexpr int kMergeWaves = kMergeThreads / 64;
 constexpr int kMergeLoads = (kTopkMergeMaxCand + kMergeThreads - 1) / kMergeThreads;
+// The kernel is built for 4, 8 and kMergeLoads candidates per thread and the host takes the
+// smallest that holds the row's chunks * kc candidates (config 3: 4096 = 4 per thread): the
+// per-slot code of the ranking is issued by all sixteen waves whether a slot holds anything or not.
 
 // Every chunk's list arrives sorted, so the q-th entry of each (q = ceil(K / chunks)) bounds
 // the row's K-th largest from below: T = the smallest of them is reached by at least
 // chunks * q >= K candidates.  Only candidates >= T (a little more than K) are ranked.
+template <int NS>
 __global__ __launch_bounds__(kMergeThreads) void topk_merge_kernel(
     const uint64_t *__restrict__ cand, const double *__restrict__ stat, int K, int kc, int chunks,
     int32_t *__restrict__ topk_tok, float *__restrict__ topk_lp)
@@ -600,16 +604,16 @@ __global__ __launch_bounds__(kMergeThreads) void topk_merge_kernel(
     // candidates of the row (at most kTopkMergeMaxCand): loads issued back to back
     const int wave_base = __builtin_amdgcn_readfirstlane(tid & ~63);
     uint32_t active = 0;
-    uint64_t cv[kMergeLoads];
+    uint64_t cv[NS];
 #pragma unroll
-    for (int u = 0; u < kMergeLoads; ++u) {
+    for (int u = 0; u < NS; ++u) {
         const int i = tid + u * kMergeThreads;
         cv[u] = i < n ? in[i] : 0ull;
         if (wave_base + u * kMergeThreads < n) active |= 1u << u;
     }
-    float xv[kMergeLoads];  // candidate values, -inf where there is none
+    float xv[NS];  // candidate values, -inf where there is none
 #pragma unroll
-    for (int u = 0; u < kMergeLoads; ++u)
+    for (int u = 0; u < NS; ++u)
         xv[u] = cv[u] != 0ull ? key_float((uint32_t)(cv[u] >> 32)) : -INFINITY;
     // per-chunk entries: statistics, first (largest) and q-th candidate
     const int q = (K + chunks - 1) / chunks;
@@ -665,13 +669,13 @@ __global__ __launch_bounds__(kMergeThreads) void topk_merge_kernel(
     };
     BucketScratch bs{s_cnt, s_start, s_list, s_wave, s_misc};
     int m;
-    if (lo > -INFINITY && block_bucket_rank<kMergeThreads, kMergeLoads>(
+    if (lo > -INFINITY && block_bucket_rank<kMergeThreads, NS>(
                               xv, [&](int u) { return cv[u]; }, active, lo, hi, K, bs, &m, emit))
         return;
     __syncthreads();  // s_lse is complete
     // heavy ties: exact radix select over all candidates staged in LDS
 #pragma unroll
-    for (int u = 0; u < kMergeLoads; ++u) {
+    for (int u = 0; u < NS; ++u) {
         const int i = tid + u * kMergeThreads;
         if (i < n) s_cand[i] = cv[u];
     }
@@ -971,17 +975,29 @@ extern "C" int ddtree_topk(const float *logits, int batch, int B, int V, int K, 
                    st, logits, V, K, topk_tok, topk_lp);
         return launch_status();
     }
-    static std::atomic<bool> chunk_lds_allowed{false}, merge_lds_allowed{false};
+    static std::atomic<bool> chunk_lds_allowed{false}, merge_lds_allowed[3] = {{false}, {false}, {false}};
     const size_t lds_chunk = (size_t)p.chunk_len * 4 + kHistBins * 4;
     const size_t lds_merge = (size_t)p.chunks * p.kc * 8 + kHistBins * 4;
     if (!allow_dynamic_lds(reinterpret_cast<const void *>(topk_chunk_kernel), kTopkChunkMax * 4 + kHistBins * 4,
                            chunk_lds_allowed) ||
-        !allow_dynamic_lds(reinterpret_cast<const void *>(topk_merge_kernel), kTopkMergeMaxCand * 8 + kHistBins * 4,
-                           merge_lds_allowed))
+        !allow_dynamic_lds(reinterpret_cast<const void *>(topk_merge_kernel<4>), kTopkMergeMaxCand * 8 + kHistBins * 4,
+                           merge_lds_allowed[0]) ||
+        !allow_dynamic_lds(reinterpret_cast<const void *>(topk_merge_kernel<8>), kTopkMergeMaxCand * 8 + kHistBins * 4,
+                           merge_lds_allowed[1]) ||
+        !allow_dynamic_lds(reinterpret_cast<const void *>(topk_merge_kernel<kMergeLoads>),
+                           kTopkMergeMaxCand * 8 + kHistBins * 4, merge_lds_allowed[2]))
         return DDTREE_ERR_HIP;
     DDT_LAUNCH(DDTREE_KERNEL_TOPK_CHUNK, st, topk_chunk_kernel, dim3(p.chunks, B, batch), dim3(kChunkThreads), lds_chunk, st,
                        logits, V, p.chunk_len, p.kc, p.chunks, cand, stat);
-    DDT_LAUNCH(DDTREE_KERNEL_TOPK_MERGE, st, topk_merge_kernel, dim3(B, batch), dim3(kMergeThreads), lds_merge, st, cand,
-                       stat, K, p.kc, p.chunks, topk_tok, topk_lp);
+    const long long per_thread = ((long long)p.chunks * p.kc + kMergeThreads - 1) / kMergeThreads;
+    if (per_thread <= 4)
+        DDT_LAUNCH(DDTREE_KERNEL_TOPK_MERGE, st, topk_merge_kernel<4>, dim3(B, batch), dim3(kMergeThreads), lds_merge,
+                   st, cand, stat, K, p.kc, p.chunks, topk_tok, topk_lp);
+    else if (per_thread <= 8)
+        DDT_LAUNCH(DDTREE_KERNEL_TOPK_MERGE, st, topk_merge_kernel<8>, dim3(B, batch), dim3(kMergeThreads), lds_merge,
+                   st, cand, stat, K, p.kc, p.chunks, topk_tok, topk_lp);
+    else
+        DDT_LAUNCH(DDTREE_KERNEL_TOPK_MERGE, st, topk_merge_kernel<kMergeLoads>, dim3(B, batch), dim3(kMergeThreads),
+                   lds_merge, st, cand, stat, K, p.kc, p.chunks, topk_tok, topk_lp);
     return launch_status();
 }
