@@ -21,8 +21,9 @@
 // The softmax reference of a row is fixed by its first visible key, so the accumulators are
 // never rescaled; a row whose scores outgrow its reference by more than 2^64 (rare) makes the
 // workgroup redo its key range once with the true row maxima as references.
-// K and V tiles sit in LDS as [key][dim], rows padded (272 B / 288 B) so that the 16-byte K
-// reads and the transposing V reads are free of bank conflicts.
+// K and V tiles sit in LDS as [key][dim]: K rows padded to 272 B, V rows of 256 B with their
+// 64-byte blocks swizzled by the row, so that the 16-byte K reads and the transposing V reads are
+// free of bank conflicts.
 // The ancestor mask touches only the tree tiles (the last ceil(T/64) tiles): one 64-bit word per
 // (row, tile), bit test per score.  Cache tiles carry no mask work at all.
 #include <algorithm>
@@ -50,9 +51,9 @@ constexpr int kHD = 128;       // head dim of the MFMA path
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kAttnStages = 4;  // a power of two: the stage of tile i is i & 3
 constexpr int kKRowBytes = 272;                  // K tile row in LDS: 256 B + 16 B pad (17 chunks)
-constexpr int kVRowBytes = 288;                  // V tile row in LDS: 256 B + 32 B pad (18 chunks)
+constexpr int kVRowBytes = 256;                  // V tile row in LDS: no pad, 64-byte blocks swizzled by the row
 constexpr int kKTileBytes = kKT * kKRowBytes;    // 17408 = 17 DMA blocks of 1 KB
-constexpr int kVTileBytes = kKT * kVRowBytes;    // 18432 = 18 DMA blocks of 1 KB
+constexpr int kVTileBytes = kKT * kVRowBytes;    // 16384 = 16 DMA blocks of 1 KB
 constexpr int kStageBytes = kKTileBytes + kVTileBytes;
 constexpr int kRingBytes = kAttnStages * kStageBytes;
 // Behind the ring: the ancestor-mask words of the workgroup's rows for up to kMaskStages tree tiles
@@ -60,7 +61,7 @@ constexpr int kRingBytes = kAttnStages * kStageBytes;
 // masked steps read LDS and no global load sits in the key loop.
 constexpr int kMaskStages = 8;
 constexpr int kMaskStageBytes = kWaves * 32 * 8;
-constexpr int kAttnLdsBytes = kRingBytes + kMaskStages * kMaskStageBytes;
+constexpr int kAttnLdsBytes = 256 + kRingBytes + kMaskStages * kMaskStageBytes;  // 256: the ring starts on a 256-byte boundary
 static_assert(kAttnLdsBytes <= 160 * 1024, "fits the LDS of a compute unit");
 
 struct AttnArgs {
@@ -287,11 +288,17 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 {
     // LDS: kAttnStages stages of {K tile, V tile}, filled by direct global->LDS loads.  One wave
     // instruction writes 64 x 16 B contiguously, but every lane may fetch any 16-byte chunk, so
-    // the tiles keep a padded row-major layout: K rows of 17 chunks (272 B), V rows of 18 chunks
-    // (288 B); the lanes that land on padding fetch a dummy chunk.  With these strides the 16-byte
-    // K reads and the transposing V reads are free of bank conflicts and every read address is
-    // one per-lane base plus an immediate.
-    extern __shared__ __align__(16) unsigned char smem[];
+    // the layout within a tile is free.  K rows are padded to 17 chunks (272 B; the lanes that
+    // land on padding fetch a dummy chunk): the 16-byte K reads are free of bank conflicts and
+    // every read address is one per-lane base plus an immediate.  V rows are 256 B with their four
+    // 64-byte blocks stored at position (block ^ (row & 3)): a transposing V read takes, in each
+    // half-wave, two 32-byte pieces of one block from four consecutive rows, and the swizzle
+    // spreads those over all 64 banks (rows padded to 288 B put the two pieces of row r and of
+    // row r + 1 on the same 8 banks: 2 conflict cycles per read by the counters).  The block a
+    // lane reads is (db ^ (row & 3)): an exclusive-or of the per-lane base with db * 64.
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    unsigned char *const smem =
+        smem_raw + ((0u - (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw) & 255u);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
@@ -370,8 +377,8 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     const unsigned char *const vt0 = reinterpret_cast<const unsigned char *>(v_tree) + ((size_t)seq * T * Hkv + hk) * (kHD * 2);
     const uint32_t tile_bytes = (uint32_t)kKT * row_bytes;
     const int n_tiles = t_end - t_begin;
-    // ---- tile loads: a K tile is 17 and a V tile 18 DMA blocks of 1 KB of LDS; lane l of block b fills
-    //      16-byte slot u = 64*b + l, i.e. row u / chunks_per_row, chunk u % chunks_per_row.
+    // ---- tile loads: a K tile is 17 and a V tile 16 DMA blocks of 1 KB of LDS; lane l of block b fills
+    //      16-byte slot u = 64*b + l, i.e. row u / chunks_per_row, chunk position u % chunks_per_row.
     //      The blocks are dealt round-robin to the n_dma loading waves: all eight, or, in a workgroup
     //      where at most two waves have query rows (the small tail tile), the six or seven waves
     //      without any, so that the waves that compute issue no loads at all.  A loading wave
@@ -383,7 +390,7 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     const int n_dma = offload ? kWaves - n_active : kWaves;
     const int dma_rank = offload ? wave_u - n_active : wave_u;  // negative: this wave loads nothing
     const bool k_third = dma_rank >= 0 && 2 * n_dma + dma_rank < 17;
-    const bool v_third = dma_rank >= 0 && 2 * n_dma + dma_rank < 18;
+    const bool v_third = dma_rank >= 0 && 2 * n_dma + dma_rank < 16;
     const int dma_loads = dma_rank < 0 ? 0 : 4 + (k_third ? 1 : 0) + (v_third ? 1 : 0);
     uint32_t k_src[3], v_src[3];   // of block n_dma*i + dma_rank
 #pragma unroll
@@ -394,9 +401,8 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         // (24-bit multiplies: a row index below 64 times a row pitch below 2^24 -- the full multiply-add
         // leaves its result in a register pair, and six such pairs were kept through the kernel)
         k_src[i] = __umul24((uint32_t)min(rk, kKT - 1), row_bytes) + (ck == 16 ? 0 : ck) * 16;  // padding slot: any chunk
-        const int rv = (u * 3641) >> 16;  // u / 18 for u < 2048
-        const int cv = u - rv * 18;
-        v_src[i] = __umul24((uint32_t)min(rv, kKT - 1), row_bytes) + (cv >= 16 ? 0 : cv) * 16;
+        const int rv = u >> 4, cv = (u & 15) ^ ((rv & 3) << 2);  // slot (row, position) holds chunk position ^ 4 (row & 3)
+        v_src[i] = __umul24((uint32_t)min(rv, kKT - 1), row_bytes) + cv * 16;
     }
     auto issue_tile = [&](int tt, int stage) __attribute__((always_inline)) {
         const bool cache = tt < n_cache_tiles;
@@ -435,10 +441,9 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                     const int r = (u * 241) >> 12, c = u - r * 17;
                     dma(kp, __umul24((uint32_t)min(r, valid_ - 1), row_bytes) + (c == 16 ? 0 : c) * 16, st + blk * 1024);
                 }
-                if (blk < 18) {
-                    const int r = (u * 3641) >> 16, c = u - r * 18;
-                    dma(vp, __umul24((uint32_t)min(r, valid_ - 1), row_bytes) + (c >= 16 ? 0 : c) * 16,
-                        st + kKTileBytes + blk * 1024);
+                if (blk < 16) {
+                    const int r = u >> 4, c = (u & 15) ^ ((r & 3) << 2);
+                    dma(vp, __umul24((uint32_t)min(r, valid_ - 1), row_bytes) + c * 16, st + kKTileBytes + blk * 1024);
                 }
             }
         }
@@ -453,8 +458,9 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         else { if (n == 1) vm_wait<4>(); else vm_wait<8>(); }
     };
 
-    const uint32_t lds_base =
-        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    // Everything in LDS is addressed from a 256-byte boundary: the V operand addresses below take
+    // an exclusive-or on bits 6 and 7.
+    const uint32_t lds_base = ((uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw + 255u) & ~255u;
 
     // ---- the first requests: the first key tile, the queries and mask words, two more key tiles.
     //      Vector memory operations complete in order, so the wait for "all but the last tile
@@ -496,8 +502,12 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     // per-lane LDS read bases (bytes, relative to the tile); everything else is an immediate
     const int k_base = l32 * kKRowBytes + half * 16;  // K: row l32 (+32*kb), column 2*ks + half
     const int lm = lane & 15, dim16 = (lane >> 4) & 1;
-    // V: row 4*half + lm/4 (+16*kstep, +8), dims 32*db + 16*dim16 + 4*(lm%4)
-    const int v_base = kKTileBytes + (4 * half + (lm >> 2)) * kVRowBytes + 32 * dim16 + 8 * (lm & 3);
+    // V: row 4*half + lm/4 (+16*kstep, +8), dims 32*db + 16*dim16 + 4*(lm%4); the 64-byte block db of
+    // a row sits at position db ^ (row & 3), and row & 3 = lm / 4 for every row this lane reads: the
+    // base points at block (row & 3), the position of db = 0, and a read takes base ^ (db * 64)
+    const int v_base = kKTileBytes + (4 * half + (lm >> 2)) * kVRowBytes + ((lm >> 2) << 6) + 32 * dim16 + 8 * (lm & 3);
+    static_assert((kKTileBytes & 0xFF) == 0 && (kStageBytes & 0xFF) == 0 && (kVRowBytes & 0xFF) == 0,
+                  "bits 6 and 7 of a V operand address come from the block position alone");
 
     // Operand staging registers: K rows of one 32-key sub-tile (8 k-steps over the head dim) and
     // V columns of one sub-tile (2 k-steps x 4 dim blocks x 2 transposing reads).
@@ -624,8 +634,8 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                     bf16x8, (u32x4){pin[4 * t2], pin[4 * t2 + 1], pin[4 * t2 + 2], pin[4 * t2 + 3]});
                 o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, o[db], 0, 0, 0);
                 if constexpr (db == 3) l_acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sel, b, l_acc, 0, 0, 0);
-                lds_rdtr<t2 * 16 * kVRowBytes + db * 64>(vbuf[t2][db][0], v_addr);
-                lds_rdtr<(t2 * 16 + 8) * kVRowBytes + db * 64>(vbuf[t2][db][1], v_addr);
+                lds_rdtr<t2 * 16 * kVRowBytes>(vbuf[t2][db][0], v_addr ^ (uint32_t)(db * 64));
+                lds_rdtr<(t2 * 16 + 8) * kVRowBytes>(vbuf[t2][db][1], v_addr ^ (uint32_t)(db * 64));
             }
             const float e1 = __builtin_amdgcn_exp2f(fmaf(cur[2 * i + 1], scale_log2e, -m_use));
             pout[i] = f2bf_pair(e0, e1);
@@ -694,8 +704,8 @@ void attn_mfma_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             });
             static_for<0, 8>([&](auto I) {
                 constexpr int t2 = decltype(I)::value / 4, db = decltype(I)::value % 4;
-                lds_rdtr<t2 * 16 * kVRowBytes + db * 64>(vbuf[t2][db][0], lds_base + v_base);
-                lds_rdtr<(t2 * 16 + 8) * kVRowBytes + db * 64>(vbuf[t2][db][1], lds_base + v_base);
+                lds_rdtr<t2 * 16 * kVRowBytes>(vbuf[t2][db][0], (lds_base + v_base) ^ (uint32_t)(db * 64));
+                lds_rdtr<(t2 * 16 + 8) * kVRowBytes>(vbuf[t2][db][1], (lds_base + v_base) ^ (uint32_t)(db * 64));
             });
         }
         for (int it = 0; it < n_tiles; ++it) {

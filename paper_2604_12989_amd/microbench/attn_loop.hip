@@ -5,6 +5,11 @@
 // instructions).  Not part of the library; build and run by hand:
 //   hipcc --offload-arch=gfx950 -O3 -std=c++17 -Xclang -target-feature -Xclang -packed-fp32-ops \
 //       paper_2604_12989_amd/microbench/attn_loop.hip -o /tmp/attn_loop && /tmp/attn_loop
+// "/tmp/attn_loop lds" runs the eight-wave loop on 256 workgroups in variants that differ in
+// their LDS traffic only -- K operand reads alone, V operand reads alone, both, and both with the
+// tile loads of the real kernel (LDS-DMA from a buffer that stays in L2 into a ring of four
+// stages, one barrier per tile) -- one kernel name each, for per-kernel counters:
+//   rocprofv3 --pmc SQ_LDS_BANK_CONFLICT SQ_ACTIVE_INST_LDS SQ_INSTS_LDS SQ_WAVE_CYCLES -- /tmp/attn_loop lds
 #include <hip/hip_runtime.h>
 #include <cstdio>
 #include <cstdint>
@@ -36,16 +41,24 @@ __device__ __forceinline__ void static_for(F &&f)
     if constexpr (B < E) { f(IC<B>{}); static_for<B + 1, E>(f); }
 }
 
-template <int CB, int WAVES, bool BAR>
-__global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(WAVES / 4, WAVES / 4))) void k(float *out, int iters, float scale, uint64_t *cyc)
+constexpr int kStage = 17408 + 18432;  // one K tile (64 rows of 272 B) and one V tile (64 rows of 288 B)
+
+// RD: bit 0 = K operand reads, bit 1 = V operand reads.  DMA: the tile loads as well (a ring of
+// four stages; needs 4 * kStage bytes of LDS and gsrc, kStage bytes of global memory).
+// SWZ: V rows of 256 B without padding, the four 64-byte column blocks of a row stored at
+// position (block ^ (row & 3)) -- the layout of the kernel; otherwise rows padded to 288 B.
+template <int CB, int WAVES, bool BAR, int RD = 3, bool DMA = false, bool SWZ = false>
+__global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(WAVES / 4, WAVES / 4))) void k(float *out, int iters, float scale, uint64_t *cyc, const unsigned char *gsrc = nullptr)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    for (int i = threadIdx.x; i < 36 * 1024 / 4; i += 64 * WAVES) ((unsigned *)smem)[i] = 0x3c003c00u + (i & 7);
+    for (int i = threadIdx.x; i < (DMA ? 4 * kStage : 36 * 1024) / 4; i += 64 * WAVES) ((unsigned *)smem)[i] = 0x3c003c00u + (i & 7);
     __syncthreads();
     const int lane = threadIdx.x & 63;
     const unsigned base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
     const unsigned ka = base + (lane & 31) * 272 + (lane >> 5) * 16;
-    const unsigned va = base + 17408 + (4 * (lane >> 5) + ((lane & 15) >> 2)) * 288 + 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
+    constexpr int VR = SWZ ? 256 : 288;
+    const unsigned va = base + 17408 + (4 * (lane >> 5) + ((lane & 15) >> 2)) * VR + 32 * ((lane >> 4) & 1) + 8 * (lane & 3) +
+                        (SWZ ? ((lane & 15) >> 2) * 64 : 0);
     floatx16 o[CB][4], sa[CB], sb[CB];
     for (int c = 0; c < CB; ++c) {
         for (int i = 0; i < 4; ++i) for (int v = 0; v < 16; ++v) o[c][i][v] = 0.f;
@@ -66,7 +79,7 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(WAVE
     uint64_t t0;
     asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t0)::"memory");
 
-    auto step = [&](floatx16 (&cur)[CB], floatx16 (&nxt)[CB], uint32_t (&pin)[CB][8], uint32_t (&pout)[CB][8]) __attribute__((always_inline)) {
+    auto step = [&](floatx16 (&cur)[CB], floatx16 (&nxt)[CB], uint32_t (&pin)[CB][8], uint32_t (&pout)[CB][8], unsigned ka, unsigned va) __attribute__((always_inline)) {
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         static_for<0, 8>([&](auto I) {
             constexpr int i = decltype(I)::value;
@@ -81,7 +94,7 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(WAVE
                 } else {
                     nxt[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, q[c][i], nxt[c], 0, 0, 0);
                 }
-                if (c == CB - 1) lds_rd128<i * 32>(kbuf[i], ka);
+                if (c == CB - 1 && (RD & 1)) lds_rd128<i * 32>(kbuf[i], ka);
                 e0[c] = __builtin_amdgcn_exp2f(fmaf(cur[c][2 * i], scale, -mref));
                 lsum[c] += e0[c];
                 __builtin_amdgcn_sched_barrier(0);
@@ -92,9 +105,15 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(WAVE
             for (int c = 0; c < CB; ++c) {
                 const bf16x8 pp = __builtin_bit_cast(bf16x8, (u32x4){pin[c][4 * t2], pin[c][4 * t2 + 1], pin[c][4 * t2 + 2], pin[c][4 * t2 + 3]});
                 o[c][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va_, pp, o[c][db], 0, 0, 0);
-                if (c == CB - 1) {
-                    lds_rdtr<(t2 * 16) * 288 + db * 64>(vbuf[t2][db][0], va);
-                    lds_rdtr<(t2 * 16 + 8) * 288 + db * 64>(vbuf[t2][db][1], va);
+                if (c == CB - 1 && (RD & 2)) {
+                    if constexpr (SWZ) {
+                        const unsigned vx = va ^ (unsigned)(db * 64);
+                        lds_rdtr<(t2 * 16) * 256>(vbuf[t2][db][0], vx);
+                        lds_rdtr<(t2 * 16 + 8) * 256>(vbuf[t2][db][1], vx);
+                    } else {
+                        lds_rdtr<(t2 * 16) * 288 + db * 64>(vbuf[t2][db][0], va);
+                        lds_rdtr<(t2 * 16 + 8) * 288 + db * 64>(vbuf[t2][db][1], va);
+                    }
                 }
                 e1[c] = __builtin_amdgcn_exp2f(fmaf(cur[c][2 * i + 1], scale, -mref));
                 lsum[c] += e1[c];
@@ -103,11 +122,44 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(WAVE
             }
         });
     };
-    for (int it = 0; it < iters; ++it) {
-        step(sa, sb, pa, pb);
-        step(sb, sa, pb, pa);
-        if (BAR) __syncthreads();
+    // tile loads as the attention kernel issues them: 17 + 18 blocks of 1 KB per tile, dealt
+    // round-robin to the eight waves (4 or 5 loads each), lane l of a block fetching 16 bytes
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    auto issue_tile = [&](int stage) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            const int blk = WAVES * i + wave;
+            uint32_t off = (uint32_t)(blk * 64 + lane) * 16;
+            asm volatile("" : "+v"(off));
+            if (blk < 17)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gsrc + off),
+                                                 (__attribute__((address_space(3))) void *)(smem + stage * kStage + blk * 1024), 16, 0, 0);
+            if (blk < 18)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gsrc + 17408 + off),
+                                                 (__attribute__((address_space(3))) void *)(smem + stage * kStage + 17408 + blk * 1024), 16, 0, 0);
+        }
+    };
+    if (DMA) {
+        issue_tile(1);
+        issue_tile(2);
     }
+    for (int it = 0; it < iters; ++it) {
+        if (DMA) {
+            // (as in the kernel: everything but the tile requested last has landed, then the barrier)
+            if (wave == 0) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            __syncthreads();
+            issue_tile((it + 3) & 3);
+            const unsigned so = (unsigned)(it & 3) * kStage;
+            step(sa, sb, pa, pb, ka + so, va + so);
+            step(sb, sa, pb, pa, ka + so + 32 * 272, va + so + 32 * 288);
+        } else {
+            step(sa, sb, pa, pb, ka, va);
+            step(sb, sa, pb, pa, ka, va);
+            if (BAR) __syncthreads();
+        }
+    }
+    if (DMA) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     uint64_t t1;
     asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t1)::"memory");
     float s = 0.f;
@@ -145,8 +197,37 @@ void run(const char *what, int grid)
            (double)mx / (ms * 1e3));
     (void)hipFree(out); (void)hipFree(cyc);
 }
-int main()
+// The eight-wave loop on 256 workgroups with K reads, V reads, both, and both plus tile loads.
+template <int RD, bool DMA, bool SWZ = false>
+void run_lds(const char *what)
 {
+    float *out; uint64_t *cyc; unsigned char *gsrc;
+    (void)hipMalloc(&out, (size_t)256 * 512 * 4); (void)hipMalloc(&cyc, 256 * 8 * 8); (void)hipMalloc(&gsrc, kStage);
+    (void)hipMemset(gsrc, 0x3c, kStage);
+    const int lds = DMA ? 4 * kStage : 40 * 1024, iters = 1000;
+    (void)hipFuncSetAttribute((const void *)k<1, 8, true, RD, DMA, SWZ>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    k<1, 8, true, RD, DMA, SWZ><<<256, 512, lds>>>(out, 10, 0.125f, cyc, gsrc);
+    (void)hipDeviceSynchronize();
+    k<1, 8, true, RD, DMA, SWZ><<<256, 512, lds>>>(out, iters, 0.125f, cyc, gsrc);
+    (void)hipDeviceSynchronize();
+    uint64_t h[8];
+    (void)hipMemcpy(h, cyc, sizeof(h), hipMemcpyDeviceToHost);
+    uint64_t mx = 0; for (int i = 0; i < 8; ++i) mx = h[i] > mx ? h[i] : mx;
+    printf("%-44s %7.1f clk per 64-key tile (workgroup 0)\n", what, (double)mx / iters);
+    (void)hipFree(out); (void)hipFree(cyc); (void)hipFree(gsrc);
+}
+int main(int argc, char **argv)
+{
+    if (argc > 1 && argv[1][0] == 'l') {
+        run_lds<1, false>("K operand reads only");
+        run_lds<2, false>("V operand reads only");
+        run_lds<3, false>("K and V operand reads");
+        run_lds<3, true>("K and V operand reads + tile loads (LDS-DMA)");
+        run_lds<0, true>("tile loads only");
+        run_lds<2, false, true>("V operand reads only, swizzled rows of 256 B");
+        run_lds<3, false, true>("K and V operand reads, V swizzled");
+        return 0;
+    }
     for (int grid : {1, 256}) {
         run<1, 8, true>("CB=1, 8 waves, barrier per tile", grid);
         run<1, 8, false>("CB=1, 8 waves, no barrier", grid);
