@@ -47,7 +47,8 @@ constexpr int kStage = 17408 + 18432;  // one K tile (64 rows of 272 B) and one 
 // four stages; needs 4 * kStage bytes of LDS and gsrc, kStage bytes of global memory).
 // SWZ: V rows of 256 B without padding, the four 64-byte column blocks of a row stored at
 // position (block ^ (row & 3)) -- the layout of the kernel; otherwise rows padded to 288 B.
-template <int CB, int WAVES, bool BAR, int RD = 3, bool DMA = false, bool SWZ = false>
+// STG: the two waves of a SIMD (w and w + 4) issue their tile loads in different halves of the tile.
+template <int CB, int WAVES, bool BAR, int RD = 3, bool DMA = false, bool SWZ = false, bool STG = false>
 __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(WAVES / 4, WAVES / 4))) void k(float *out, int iters, float scale, uint64_t *cyc, const unsigned char *gsrc = nullptr)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -149,9 +150,10 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(WAVE
             if (wave == 0) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
             else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
             __syncthreads();
-            issue_tile((it + 3) & 3);
+            if (!STG || wave < 4) issue_tile((it + 3) & 3);
             const unsigned so = (unsigned)(it & 3) * kStage;
             step(sa, sb, pa, pb, ka + so, va + so);
+            if (STG && wave >= 4) issue_tile((it + 3) & 3);
             step(sb, sa, pb, pa, ka + so + 32 * 272, va + so + 32 * 288);
         } else {
             step(sa, sb, pa, pb, ka, va);
@@ -198,17 +200,17 @@ void run(const char *what, int grid)
     (void)hipFree(out); (void)hipFree(cyc);
 }
 // The eight-wave loop on 256 workgroups with K reads, V reads, both, and both plus tile loads.
-template <int RD, bool DMA, bool SWZ = false>
+template <int RD, bool DMA, bool SWZ = false, bool STG = false>
 void run_lds(const char *what)
 {
     float *out; uint64_t *cyc; unsigned char *gsrc;
     (void)hipMalloc(&out, (size_t)256 * 512 * 4); (void)hipMalloc(&cyc, 256 * 8 * 8); (void)hipMalloc(&gsrc, kStage);
     (void)hipMemset(gsrc, 0x3c, kStage);
     const int lds = DMA ? 4 * kStage : 40 * 1024, iters = 1000;
-    (void)hipFuncSetAttribute((const void *)k<1, 8, true, RD, DMA, SWZ>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    k<1, 8, true, RD, DMA, SWZ><<<256, 512, lds>>>(out, 10, 0.125f, cyc, gsrc);
+    (void)hipFuncSetAttribute((const void *)k<1, 8, true, RD, DMA, SWZ, STG>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    k<1, 8, true, RD, DMA, SWZ, STG><<<256, 512, lds>>>(out, 10, 0.125f, cyc, gsrc);
     (void)hipDeviceSynchronize();
-    k<1, 8, true, RD, DMA, SWZ><<<256, 512, lds>>>(out, iters, 0.125f, cyc, gsrc);
+    k<1, 8, true, RD, DMA, SWZ, STG><<<256, 512, lds>>>(out, iters, 0.125f, cyc, gsrc);
     (void)hipDeviceSynchronize();
     uint64_t h[8];
     (void)hipMemcpy(h, cyc, sizeof(h), hipMemcpyDeviceToHost);
@@ -226,6 +228,7 @@ int main(int argc, char **argv)
         run_lds<0, true>("tile loads only");
         run_lds<2, false, true>("V operand reads only, swizzled rows of 256 B");
         run_lds<3, false, true>("K and V operand reads, V swizzled");
+        run_lds<3, true, false, true>("K and V reads + tile loads, the waves of a SIMD staggered");
         return 0;
     }
     for (int grid : {1, 256}) {
