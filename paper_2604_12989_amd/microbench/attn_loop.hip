@@ -48,7 +48,11 @@ constexpr int kStage = 17408 + 18432;  // one K tile (64 rows of 272 B) and one 
 // SWZ: V rows of 256 B without padding, the four 64-byte column blocks of a row stored at
 // position (block ^ (row & 3)) -- the layout of the kernel; otherwise rows padded to 288 B.
 // STG: the two waves of a SIMD (w and w + 4) issue their tile loads in different halves of the tile.
-template <int CB, int WAVES, bool BAR, int RD = 3, bool DMA = false, bool SWZ = false, bool STG = false>
+// VAR (with DMA): 1 = no wait for the loads inside the loop (what the operand reads find is then
+// whatever has landed: timing only); 2 = K tiles only; 3 = the loads of a tile are issued by four
+// waves, one per SIMD: waves 0-3 for even tiles, 4-7 for odd ones; 4 = all loads of a tile by one
+// wave, the eight waves taking turns; 5 = by two waves (w and w + 4 of one SIMD... no: w and w + 1), in turns.
+template <int CB, int WAVES, bool BAR, int RD = 3, bool DMA = false, bool SWZ = false, bool STG = false, int VAR = 0>
 __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(WAVES / 4, WAVES / 4))) void k(float *out, int iters, float scale, uint64_t *cyc, const unsigned char *gsrc = nullptr)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -128,14 +132,14 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(WAVE
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
     auto issue_tile = [&](int stage) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < 3; ++i) {
-            const int blk = WAVES * i + wave;
+        for (int i = 0; i < (VAR == 4 ? 18 : VAR == 5 ? 9 : VAR == 3 ? 5 : 3); ++i) {
+            const int blk = VAR == 4 ? i : VAR == 5 ? 2 * i + (wave & 1) : VAR == 3 ? 4 * i + (wave & 3) : WAVES * i + wave;
             uint32_t off = (uint32_t)(blk * 64 + lane) * 16;
             asm volatile("" : "+v"(off));
             if (blk < 17)
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gsrc + off),
                                                  (__attribute__((address_space(3))) void *)(smem + stage * kStage + blk * 1024), 16, 0, 0);
-            if (blk < 18)
+            if (blk < 18 && VAR != 2)
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gsrc + 17408 + off),
                                                  (__attribute__((address_space(3))) void *)(smem + stage * kStage + 17408 + blk * 1024), 16, 0, 0);
         }
@@ -147,10 +151,24 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(WAVE
     for (int it = 0; it < iters; ++it) {
         if (DMA) {
             // (as in the kernel: everything but the tile requested last has landed, then the barrier)
-            if (wave == 0) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            if (VAR == 0 || VAR == 2) {
+                if (VAR == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+                else if (wave == 0) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            } else if (VAR == 3) {
+                // this wave's previous tile (two iterations back) was its last but one request
+                asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+            } else if (VAR >= 4) {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // (its last request is at least four tiles old)
+            }
             __syncthreads();
-            if (!STG || wave < 4) issue_tile((it + 3) & 3);
+            if (VAR == 3) {
+                if ((wave >> 2) == (it & 1)) issue_tile((it + 3) & 3);
+            } else if (VAR == 4) {
+                if (wave == (it & 7)) issue_tile((it + 3) & 3);
+            } else if (VAR == 5) {
+                if ((wave >> 1) == (it & 3)) issue_tile((it + 3) & 3);
+            } else if (!STG || wave < 4) issue_tile((it + 3) & 3);
             const unsigned so = (unsigned)(it & 3) * kStage;
             step(sa, sb, pa, pb, ka + so, va + so);
             if (STG && wave >= 4) issue_tile((it + 3) & 3);
@@ -200,17 +218,17 @@ void run(const char *what, int grid)
     (void)hipFree(out); (void)hipFree(cyc);
 }
 // The eight-wave loop on 256 workgroups with K reads, V reads, both, and both plus tile loads.
-template <int RD, bool DMA, bool SWZ = false, bool STG = false>
+template <int RD, bool DMA, bool SWZ = false, bool STG = false, int VAR = 0>
 void run_lds(const char *what)
 {
     float *out; uint64_t *cyc; unsigned char *gsrc;
     (void)hipMalloc(&out, (size_t)256 * 512 * 4); (void)hipMalloc(&cyc, 256 * 8 * 8); (void)hipMalloc(&gsrc, kStage);
     (void)hipMemset(gsrc, 0x3c, kStage);
     const int lds = DMA ? 4 * kStage : 40 * 1024, iters = 1000;
-    (void)hipFuncSetAttribute((const void *)k<1, 8, true, RD, DMA, SWZ, STG>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    k<1, 8, true, RD, DMA, SWZ, STG><<<256, 512, lds>>>(out, 10, 0.125f, cyc, gsrc);
+    (void)hipFuncSetAttribute((const void *)k<1, 8, true, RD, DMA, SWZ, STG, VAR>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    k<1, 8, true, RD, DMA, SWZ, STG, VAR><<<256, 512, lds>>>(out, 10, 0.125f, cyc, gsrc);
     (void)hipDeviceSynchronize();
-    k<1, 8, true, RD, DMA, SWZ, STG><<<256, 512, lds>>>(out, iters, 0.125f, cyc, gsrc);
+    k<1, 8, true, RD, DMA, SWZ, STG, VAR><<<256, 512, lds>>>(out, iters, 0.125f, cyc, gsrc);
     (void)hipDeviceSynchronize();
     uint64_t h[8];
     (void)hipMemcpy(h, cyc, sizeof(h), hipMemcpyDeviceToHost);
@@ -229,6 +247,11 @@ int main(int argc, char **argv)
         run_lds<2, false, true>("V operand reads only, swizzled rows of 256 B");
         run_lds<3, false, true>("K and V operand reads, V swizzled");
         run_lds<3, true, false, true>("K and V reads + tile loads, the waves of a SIMD staggered");
+        run_lds<3, true, false, false, 1>("K and V reads + tile loads, no wait for the loads");
+        run_lds<3, true, false, false, 2>("K and V reads + K tile loads only");
+        run_lds<3, true, false, false, 3>("K and V reads + tile loads by one wave per SIMD, alternating");
+        run_lds<3, true, false, false, 4>("K and V reads + tile loads by one wave, in turns");
+        run_lds<3, true, false, false, 5>("K and V reads + tile loads by two waves, in turns");
         return 0;
     }
     for (int grid : {1, 256}) {
