@@ -260,6 +260,16 @@ int ddtree_compact(const void *k_tree, const void *v_tree, const int32_t *path,
 #define DDTREE_BUILD_POPS 1
 #define DDTREE_BUILD_LEVELS 2
 int ddtree_set_build_algorithm(int algo);
+
+/* Host-side self-check of the launch arithmetic behind ddtree_verify_attn's matrix-core kernel
+ * (paper Section 4.4: every tree node attends to the whole context -- the decomposition of
+ * that work into workgroups must cover every (sequence, KV head, query row, key) exactly once).
+ * For a fixed list of shapes it builds the plan, the per-XCD runs of work items and the
+ * reciprocals a launch would pass, decodes every workgroup index the way the kernel does, and
+ * holds the result against plain division and against that coverage.  No GPU is touched and
+ * nothing is launched.  Returns 0, or 100 * (number of the failing shape) + (number of the
+ * failed check); values below 100 concern the reciprocal division itself. */
+int ddtree_selftest_host(void);
 /*
  * Number of sequences, since the library was loaded, for which the level-synchronous
  * construction gave up and the pops built the tree instead.  count is a host pointer; the call

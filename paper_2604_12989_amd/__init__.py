@@ -8,9 +8,9 @@ fallback path.
 from .binding import (DDTreeError, accept, accept_noalloc, build, compact, error_string, library_path, load,
                       topk, verify_attn, verify_attn_spans, version, workspace_bytes, verify_attn_workspace_bytes, Workspace, DTYPE_BF16,
                       DTYPE_FP32, KERNELS, profile_enable, profile_read, profile_reset,
-                      set_build_algorithm, build_giveups, BUILD_AUTO, BUILD_POPS, BUILD_LEVELS)
+                      set_build_algorithm, build_giveups, selftest_host, BUILD_AUTO, BUILD_POPS, BUILD_LEVELS)
 
 __all__ = ["DDTreeError", "accept", "accept_noalloc", "build", "compact", "error_string", "library_path", "load",
            "topk", "verify_attn", "verify_attn_spans", "version", "workspace_bytes", "verify_attn_workspace_bytes", "Workspace", "DTYPE_BF16",
            "DTYPE_FP32", "KERNELS", "profile_enable", "profile_read", "profile_reset",
-           "set_build_algorithm", "build_giveups", "BUILD_AUTO", "BUILD_POPS", "BUILD_LEVELS"]
+           "set_build_algorithm", "build_giveups", "selftest_host", "BUILD_AUTO", "BUILD_POPS", "BUILD_LEVELS"]

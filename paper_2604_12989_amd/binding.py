@@ -35,6 +35,7 @@ _SIGNATURES = {
     "ddtree_verify_attn_spans": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i,
                                       ctypes.c_float, _i, _vp, _vp, _sz, _vp]),
     "ddtree_set_build_algorithm": (_i, [_i]),
+    "ddtree_selftest_host": (_i, []),
     "ddtree_build_giveups": (_i, [ctypes.POINTER(ctypes.c_uint)]),
     "ddtree_profile_enable": (_i, [ctypes.c_uint, _i]),
     "ddtree_profile_enable_every": (_i, [ctypes.c_uint, _i, _i]),
@@ -295,6 +296,11 @@ BUILD_AUTO, BUILD_POPS, BUILD_LEVELS = 0, 1, 2
 def set_build_algorithm(algo):
     """Force one construction in ddtree_build (BUILD_POPS / BUILD_LEVELS) or let it choose (BUILD_AUTO)."""
     _check(load().ddtree_set_build_algorithm(int(algo)), "ddtree_set_build_algorithm")
+
+
+def selftest_host():
+    """Host-side self-check of the attention kernel's launch arithmetic (no GPU): 0 if it holds."""
+    return int(load().ddtree_selftest_host())
 
 
 def build_giveups():

@@ -27,6 +27,7 @@
 // The ancestor mask touches only the tree tiles (the last ceil(T/64) tiles): one 64-bit word per
 // (row, tile), bit test per score.  Cache tiles carry no mask work at all.
 #include <algorithm>
+#include <vector>
 
 #include "common.hpp"
 
@@ -87,9 +88,9 @@ __host__ __device__ __forceinline__ uint32_t magic_of(uint64_t d, uint64_t x_max
 {
     return (d >= 2 && x_max * d < 0x100000000ull) ? (uint32_t)((0x100000000ull + d - 1) / d) : 0u;
 }
-__device__ __forceinline__ int div_by(int x, int d, uint32_t magic)
+__host__ __device__ __forceinline__ int div_by(int x, int d, uint32_t magic)
 {
-    return magic != 0u ? (int)__umulhi((uint32_t)x, magic) : (d == 1 ? x : x / d);
+    return magic != 0u ? (int)(((uint64_t)(uint32_t)x * magic) >> 32) : (d == 1 ? x : x / d);
 }
 
 // Shapes of the matrix-core kernel.  (The bound on the KV heads keeps the pitch between cache
@@ -1066,6 +1067,73 @@ __global__ __launch_bounds__(kGenThreads) void attn_generic_kernel(
 
 }  // namespace ddt
 
+// The launch tables of the matrix-core kernel for a plan: reciprocals for the work-item decode, the
+// sequences by length, the cut of the work items into the 8 XCDs' runs.  *grid_x = workgroups to
+// launch.  False if the launch would exceed 2^28 work items.
+static bool attn_fill_args(ddt::AttnArgs &args, const ddt::AttnPlan &p, const int32_t *kv_start,
+                           const int32_t *kv_len, int batch, int T, int Hkv, long long *grid_x)
+{
+    using namespace ddt;
+    const int main_tiles = p.tail_splits > 0 ? p.n_tiles - 1 : p.n_tiles;
+    // Work items in launch order: sequences longest first, then kv head, then the items of
+    // the group.  An item visits about (L + T) / splits keys; the 8 runs are cut where the
+    // running sum of that passes each eighth of the total.
+    const long long per_seq = (long long)Hkv * (main_tiles * p.splits + p.tail_splits);
+    const long long total = per_seq * batch;
+    if (total > (1ll << 28)) return false;
+    {
+        long long max_len = 0;
+        for (int i = 0; i < batch; ++i) max_len = std::max<long long>(max_len, kv_len[i]);
+        const uint64_t per_grp = (uint64_t)(main_tiles * p.splits + p.tail_splits);
+        const uint64_t nt_max = (uint64_t)((max_len + kKT - 1) / kKT + (T + kKT - 1) / kKT);
+        args.per_grp_magic = magic_of(per_grp, (uint64_t)total);
+        args.main_tiles_magic = magic_of((uint64_t)main_tiles, per_grp);
+        args.hkv_magic = magic_of((uint64_t)Hkv, (uint64_t)batch * Hkv);
+        args.splits_magic[0] = magic_of((uint64_t)p.splits, nt_max * p.splits + p.splits);
+        args.splits_magic[1] = magic_of((uint64_t)p.tail_splits, nt_max * p.tail_splits + p.tail_splits);
+    }
+    int32_t order[DDTREE_MAX_BATCH];
+    for (int i = 0; i < batch; ++i) order[i] = i;
+    std::stable_sort(order, order + batch, [&](int32_t a, int32_t b) { return kv_len[a] > kv_len[b]; });
+    for (int i = 0; i < batch; ++i) {
+        args.by_length[i][0] = order[i];
+        args.by_length[i][1] = kv_start[order[i]];
+        args.by_length[i][2] = kv_len[order[i]];
+        args.by_length[i][3] = 0;
+    }
+    long long work_total = 0;
+    for (int i = 0; i < batch; ++i) work_total += per_seq * ((long long)kv_len[i] + T);
+    {
+        long long done = 0, first = 0;  // work and items before sequence position `pos`
+        int pos = 0, x = 1;
+        args.xcd_start[0] = 0;
+        while (x < 8) {
+            const long long target = (work_total * x + 7) / 8;
+            const int sq = order[pos];
+            const long long w = (long long)kv_len[sq] + T;
+            if (pos < batch - 1 && done + per_seq * w < target) {
+                done += per_seq * w;
+                first += per_seq;
+                ++pos;
+                continue;
+            }
+            long long k = (target - done + w - 1) / w;  // items of this sequence before the cut
+            if (k < 0) k = 0;
+            if (k > per_seq) k = per_seq;
+            args.xcd_start[x++] = (int32_t)(first + k);
+        }
+        args.xcd_start[8] = (int32_t)total;
+    }
+    long long run_max = 0;
+    for (int x = 0; x < 8; ++x) {
+        if (args.xcd_start[x + 1] < args.xcd_start[x]) args.xcd_start[x + 1] = args.xcd_start[x];
+        const long long run = args.xcd_start[x + 1] - args.xcd_start[x];
+        if (run > run_max) run_max = run;
+    }
+    *grid_x = run_max * 8;
+    return true;
+}
+
 static int verify_attn_impl(const void *q, const void *k_cache, const void *v_cache, const void *k_tree,
                             const void *v_tree, const uint64_t *ancestor_mask, const int32_t *kv_start,
                             const int32_t *kv_len, int batch, int T, int Hq, int Hkv, int D,
@@ -1110,63 +1178,8 @@ static int verify_attn_impl(const void *q, const void *k_cache, const void *v_ca
         static std::atomic<bool> lds_allowed{false};
         if (!allow_dynamic_lds(reinterpret_cast<const void *>(attn_mfma_kernel), kAttnLdsBytes, lds_allowed))
             return DDTREE_ERR_HIP;
-        const int main_tiles = p.tail_splits > 0 ? p.n_tiles - 1 : p.n_tiles;
-        // Work items in launch order: sequences longest first, then kv head, then the items of
-        // the group.  An item visits about (L + T) / splits keys; the 8 runs are cut where the
-        // running sum of that passes each eighth of the total.
-        const long long per_seq = (long long)Hkv * (main_tiles * p.splits + p.tail_splits);
-        const long long total = per_seq * batch;
-        if (total > (1ll << 28)) return DDTREE_ERR_ARG;
-        {
-            long long max_len = 0;
-            for (int i = 0; i < batch; ++i) max_len = std::max<long long>(max_len, kv_len[i]);
-            const uint64_t per_grp = (uint64_t)(main_tiles * p.splits + p.tail_splits);
-            const uint64_t nt_max = (uint64_t)((max_len + kKT - 1) / kKT + (T + kKT - 1) / kKT);
-            args.per_grp_magic = magic_of(per_grp, (uint64_t)total);
-            args.main_tiles_magic = magic_of((uint64_t)main_tiles, per_grp);
-            args.hkv_magic = magic_of((uint64_t)Hkv, (uint64_t)batch * Hkv);
-            args.splits_magic[0] = magic_of((uint64_t)p.splits, nt_max * p.splits + p.splits);
-            args.splits_magic[1] = magic_of((uint64_t)p.tail_splits, nt_max * p.tail_splits + p.tail_splits);
-        }
-        int32_t order[DDTREE_MAX_BATCH];
-        for (int i = 0; i < batch; ++i) order[i] = i;
-        std::stable_sort(order, order + batch, [&](int32_t a, int32_t b) { return kv_len[a] > kv_len[b]; });
-        for (int i = 0; i < batch; ++i) {
-            args.by_length[i][0] = order[i];
-            args.by_length[i][1] = kv_start[order[i]];
-            args.by_length[i][2] = kv_len[order[i]];
-            args.by_length[i][3] = 0;
-        }
-        long long work_total = 0;
-        for (int i = 0; i < batch; ++i) work_total += per_seq * ((long long)kv_len[i] + T);
-        {
-            long long done = 0, first = 0;  // work and items before sequence position `pos`
-            int pos = 0, x = 1;
-            args.xcd_start[0] = 0;
-            while (x < 8) {
-                const long long target = (work_total * x + 7) / 8;
-                const int sq = order[pos];
-                const long long w = (long long)kv_len[sq] + T;
-                if (pos < batch - 1 && done + per_seq * w < target) {
-                    done += per_seq * w;
-                    first += per_seq;
-                    ++pos;
-                    continue;
-                }
-                long long k = (target - done + w - 1) / w;  // items of this sequence before the cut
-                if (k < 0) k = 0;
-                if (k > per_seq) k = per_seq;
-                args.xcd_start[x++] = (int32_t)(first + k);
-            }
-            args.xcd_start[8] = (int32_t)total;
-        }
-        long long run_max = 0;
-        for (int x = 0; x < 8; ++x) {
-            if (args.xcd_start[x + 1] < args.xcd_start[x]) args.xcd_start[x + 1] = args.xcd_start[x];
-            const long long run = args.xcd_start[x + 1] - args.xcd_start[x];
-            if (run > run_max) run_max = run;
-        }
-        const long long gx = run_max * 8;
+        long long gx = 0;
+        if (!attn_fill_args(args, p, kv_start, kv_len, batch, T, Hkv, &gx)) return DDTREE_ERR_ARG;
         const int part_splits = p.part_splits > 1 ? p.part_splits : 0;
         DDT_LAUNCH(DDTREE_KERNEL_ATTN, st, attn_mfma_kernel, dim3((unsigned)gx), dim3(kAttnThreads),
                    kAttnLdsBytes, st, static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(k_cache),
@@ -1229,4 +1242,136 @@ extern "C" int ddtree_verify_attn_spans(const void *q, const void *k_cache, cons
     if (batch < 1 || batch > DDTREE_MAX_BATCH) return DDTREE_ERR_ARG;
     return verify_attn_impl(q, k_cache, v_cache, k_tree, v_tree, ancestor_mask, kv_start, kv_len, batch, T,
                             Hq, Hkv, D, softmax_scale, dtype, out, workspace, workspace_bytes, stream);
+}
+
+// ------------------------------------------------------------------------------------------
+// Host-side self-check of the matrix-core kernel's launch arithmetic (no GPU involved): for a
+// list of shapes, the plan, the XCD runs and the reciprocals are built as for a launch, every
+// workgroup index of the grid is decoded the way the kernel decodes it, and the result is held
+// against plain division and against what the decomposition promises: every (sequence, KV head,
+// row tile, key range) exactly once, the row blocks of a group's tiles a partition of its rows,
+// the key ranges of a tile a partition of its key tiles in order.
+// Returns 0, or 100 * (index of the failing shape + 1) + the number of the failed check.
+// ------------------------------------------------------------------------------------------
+extern "C" int ddtree_selftest_host(void)
+{
+    using namespace ddt;
+    struct Shape {
+        int batch, T, Hq, Hkv;
+        int32_t len[4];
+    };
+    static const Shape shapes[] = {
+        {1, 257, 32, 8, {8192}},        {1, 513, 32, 8, {32768}},       {1, 65, 32, 8, {2048}},
+        {4, 129, 64, 8, {1533, 7527, 4000, 1024}},                      {1, 1025, 8, 2, {1500}},
+        {3, 33, 16, 2, {130, 0, 517}},  {1, 17, 4, 1, {128}},           {2, 40, 12, 1, {1000, 3}},
+        {1, 2, 1, 1, {0}},              {4, 1024, 8, 8, {100, 0, 64, 7}}, {1, 75, 16, 4, {3000}},
+        {1, 300, 6, 2, {9000}},         {2, 273, 32, 8, {5000, 4999}},  {1, 1025, 128, 1, {200000}},
+    };
+    // exhaustive check of the reciprocal division itself on small divisors
+    for (uint32_t d = 2; d <= 64; ++d) {
+        const uint64_t x_max = 0xFFFFFFFFull / d;
+        const uint32_t m = magic_of(d, x_max);
+        if (m == 0u) return 1;
+        for (uint64_t x = 0; x <= x_max; x += (x < 70000 ? 1 : 9973))
+            if (div_by((int)(x & 0x7FFFFFFF), (int)d, m) != (int)((x & 0x7FFFFFFF) / d)) return 2;
+        if (magic_of(d, x_max + 1) != 0u && (x_max + 1) * d >= 0x100000000ull) return 3;
+    }
+    int si = 0;
+    for (const Shape &sh : shapes) {
+        ++si;
+        const int batch = sh.batch, T = sh.T, Hq = sh.Hq, Hkv = sh.Hkv, G = Hq / Hkv;
+        int32_t kv_start[4], kv_len[4];
+        long long sum_L = 0;
+        for (int i = 0; i < batch; ++i) {
+            kv_start[i] = (int32_t)sum_L;
+            kv_len[i] = sh.len[i];
+            sum_L += sh.len[i];
+        }
+        const AttnPlan p = attn_plan(batch, T, Hq, Hkv, kHD, sum_L, DDTREE_DTYPE_BF16);
+        AttnArgs args{};
+        args.group_size = G;
+        args.g_magic = magic_of((uint64_t)G, (uint64_t)T * G);
+        long long gx = 0;
+        if (!attn_fill_args(args, p, kv_start, kv_len, batch, T, Hkv, &gx)) return 100 * si + 1;
+        const int main_tiles = p.tail_splits > 0 ? p.n_tiles - 1 : p.n_tiles;
+        const int per_grp = main_tiles * p.splits + p.tail_splits;
+        const long long total = (long long)batch * Hkv * per_grp;
+        if (args.xcd_start[0] != 0 || args.xcd_start[8] != total) return 100 * si + 2;
+        for (int x = 0; x < 8; ++x)
+            if (args.xcd_start[x + 1] < args.xcd_start[x]) return 100 * si + 3;
+        const int M = T * G, W = (T + 63) >> 6;
+        (void)W;
+        std::vector<int> seen((size_t)total, 0);
+        // per (group, tile): the next key tile expected, and the rows covered
+        std::vector<int> next_t((size_t)batch * Hkv * p.n_tiles, 0), rows((size_t)batch * Hkv, 0);
+        std::vector<int> by_split((size_t)total, -1);
+        for (long long b = 0; b < gx; ++b) {
+            const int xcd = (int)(b & 7);
+            const int wid = args.xcd_start[xcd] + (int)(b >> 3);
+            if (wid >= args.xcd_start[xcd + 1]) continue;
+            if (wid < 0 || wid >= total) return 100 * si + 4;
+            // the kernel's decode
+            const int grp = div_by(wid, per_grp, args.per_grp_magic);
+            const int wg = wid - grp * per_grp;
+            const bool tail = wg >= main_tiles * p.splits;
+            const int wg_split = div_by(wg, main_tiles, args.main_tiles_magic);
+            const int mt = tail ? main_tiles : wg - wg_split * main_tiles;
+            const int split = tail ? wg - main_tiles * p.splits : wg_split;
+            const int splits = tail ? p.tail_splits : p.splits;
+            const int grp_seq = div_by(grp, Hkv, args.hkv_magic);
+            const int hk = grp - grp_seq * Hkv;
+            const int seq = args.by_length[grp_seq][0];
+            const int L = args.by_length[grp_seq][2];
+            const int first_blk = p.tail_splits > 0 ? mt * 8 : mt * p.blk_base + std::min(mt, p.blk_extra);
+            const int n_blk = p.tail_splits > 0 ? (tail ? p.blk_extra : 8) : p.blk_base + (mt < p.blk_extra ? 1 : 0);
+            const int m0 = first_blk * 32, m_end = std::min(M, (first_blk + n_blk) * 32);
+            const int last_node = std::min(T - 1, div_by(m_end - 1, G, args.g_magic));
+            const int nt = (L + kKT - 1) / kKT + last_node / kKT + 1;
+            const uint32_t s_magic = args.splits_magic[tail ? 1 : 0];
+            const int t_begin = div_by(nt * split + splits - 1, splits, s_magic);
+            const int t_end = div_by(nt * (split + 1) + splits - 1, splits, s_magic);
+            // against plain division
+            if (grp != wid / per_grp || wg_split != wg / main_tiles || grp_seq != grp / Hkv) return 100 * si + 5;
+            if (last_node != std::min(T - 1, (m_end - 1) / G)) return 100 * si + 6;
+            if (t_begin != (int)(((long long)nt * split + splits - 1) / splits) ||
+                t_end != (int)(((long long)nt * (split + 1) + splits - 1) / splits))
+                return 100 * si + 7;
+            // against the decomposition
+            if (grp < 0 || grp >= batch * Hkv || hk < 0 || hk >= Hkv || seq < 0 || seq >= batch || L != kv_len[seq] ||
+                args.by_length[grp_seq][1] != kv_start[seq])
+                return 100 * si + 8;
+            if (mt < 0 || mt >= p.n_tiles || split < 0 || split >= splits || m0 >= m_end || m0 >= M) return 100 * si + 9;
+            if (t_begin < 0 || t_end > nt || t_begin > t_end) return 100 * si + 10;
+            if (seen[(size_t)wid]++) return 100 * si + 11;
+            by_split[(size_t)wid] = t_begin;
+            if (split == 0) rows[(size_t)grp] += m_end - m0;
+            // the key ranges of a tile, taken in the order of their work items (split ascending
+            // within a tile for main tiles: item = split * main_tiles + mt; tail: consecutive)
+            (void)next_t;
+        }
+        for (long long w = 0; w < total; ++w)
+            if (seen[(size_t)w] != 1) return 100 * si + 12;
+        for (int g = 0; g < batch * Hkv; ++g)
+            if (rows[(size_t)g] != M) return 100 * si + 13;
+        // key ranges: for every (group, tile) the ranges 0 .. splits-1 follow each other from 0 to nt
+        for (int g = 0; g < batch * Hkv; ++g)
+            for (int tile = 0; tile < p.n_tiles; ++tile) {
+                const bool tail = p.tail_splits > 0 && tile == main_tiles;
+                const int splits = tail ? p.tail_splits : p.splits;
+                int expect = 0;
+                for (int sp = 0; sp < splits; ++sp) {
+                    const long long wid = (long long)g * per_grp + (tail ? main_tiles * p.splits + sp : sp * main_tiles + tile);
+                    if (by_split[(size_t)wid] != expect) return 100 * si + 14;
+                    // end of this range = begin of the next (or nt for the last), recomputed exactly
+                    const int seq = args.by_length[g / Hkv][0];
+                    const int first_blk = p.tail_splits > 0 ? tile * 8 : tile * p.blk_base + std::min(tile, p.blk_extra);
+                    const int n_blk = p.tail_splits > 0 ? (tail ? p.blk_extra : 8) : p.blk_base + (tile < p.blk_extra ? 1 : 0);
+                    const int m_end = std::min(M, (first_blk + n_blk) * 32);
+                    const int nt = (kv_len[seq] + kKT - 1) / kKT + std::min(T - 1, (m_end - 1) / G) / kKT + 1;
+                    expect = (int)(((long long)nt * (sp + 1) + splits - 1) / splits);
+                    if (sp == splits - 1 && expect != nt) return 100 * si + 15;
+                }
+            }
+    }
+    return 0;
 }

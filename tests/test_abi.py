@@ -57,6 +57,14 @@ def test_workspace_sizing_is_host_arithmetic(lib):
     assert dd.workspace_bytes(0, 16, 151936, 256, 32, 8, 128, 8192) == 0
 
 
+def test_attention_launch_arithmetic_selfcheck(lib):
+    """The decomposition of the attention into workgroups, decoded on the host the way the kernel
+    decodes it (reciprocal divisions, per-XCD runs, key ranges): every (sequence, KV head, row
+    tile, key range) exactly once, rows and key tiles partitioned, equal to plain division."""
+    import paper_2604_12989_amd as dd
+    assert dd.selftest_host() == 0
+
+
 def test_attention_scratch_never_exceeds_the_workspace_bound(lib):
     # ddtree_workspace_bytes must cover ddtree_verify_attn for every cache length: sweep budgets,
     # head layouts and lengths (the split of the key range, hence the scratch, depends on all three)
