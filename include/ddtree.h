@@ -266,9 +266,12 @@ int ddtree_set_build_algorithm(int algo);
  * that work into workgroups must cover every (sequence, KV head, query row, key) exactly once).
  * For a fixed list of shapes it builds the plan, the per-XCD runs of work items and the
  * reciprocals a launch would pass, decodes every workgroup index the way the kernel does, and
- * holds the result against plain division and against that coverage.  No GPU is touched and
- * nothing is launched.  Returns 0, or 100 * (number of the failing shape) + (number of the
- * failed check); values below 100 concern the reciprocal division itself. */
+ * holds the result against plain division and against that coverage; it also checks, over a
+ * grid of sizes, that the chunks of ddtree_topk and the segments of ddtree_accept tile a logits
+ * row and that their scratch holds what the kernels index.  No GPU is touched and nothing is
+ * launched.  Returns 0, or 100 * (number of the failing shape) + (number of the failed check)
+ * for the attention (values below 100 concern the reciprocal division itself), 10000 + (number
+ * of the failed check) for the plans. */
 int ddtree_selftest_host(void);
 /*
  * Number of sequences, since the library was loaded, for which the level-synchronous

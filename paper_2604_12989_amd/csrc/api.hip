@@ -120,3 +120,58 @@ extern "C" int ddtree_profile_read(int kernel_id, float *ms_out, int max_records
             return DDTREE_ERR_HIP;
     return n;
 }
+
+// Host-side self-check (no GPU): the attention kernel's launch arithmetic (attn.hip) and the
+// invariants of the top-K and accept plans that their kernels index by.
+namespace ddt {
+int attn_selftest_host();
+}
+extern "C" int ddtree_selftest_host(void)
+{
+    using namespace ddt;
+    if (const int rc = attn_selftest_host()) return rc;
+    // top-K: chunks tile the row, stay within what a chunk workgroup holds, and their candidates
+    // fit the merge workgroup; a plan that cannot be made says so
+    const int Vs[] = {1, 2, 7, 64, 1000, 1024, 4096, 12288, 12289, 20000, 50001, 100000, 151936, 172032, 200003, 344064, 688128, 1000000};
+    const int Ks[] = {1, 2, 16, 64, 255, 256, 257, 512, 1024};
+    const int rows_[] = {1, 2, 3, 8, 16, 17, 64, 127, 128, 1024};
+    for (int V : Vs)
+        for (int K : Ks)
+            for (int rows : rows_) {
+                if (K > V) continue;
+                const TopkPlan p = topk_plan(1, rows, V, K);
+                if (!p.ok) {
+                    // only where the candidates of a row cannot fit the merge workgroup
+                    const long long c_min = (V + kTopkChunkMax - 1) / kTopkChunkMax;
+                    const long long len = ((V + c_min - 1) / c_min + 3) / 4 * 4;
+                    if (c_min * (K < len ? K : len) <= kTopkMergeMaxCand) return 10001;
+                    continue;
+                }
+                if (p.row_kernel) {
+                    if (rows < kTopkRowKernelMinRows) return 10002;
+                    continue;
+                }
+                if (rows >= kTopkRowKernelMinRows) return 10003;
+                if (p.chunk_len % 4 != 0 || p.chunk_len < 1 || p.chunk_len > kTopkChunkMax) return 10004;
+                if ((long long)(p.chunks - 1) * p.chunk_len >= V || (long long)p.chunks * p.chunk_len < V) return 10005;
+                if (p.kc != (K < p.chunk_len ? K : p.chunk_len)) return 10006;
+                if ((long long)p.chunks * p.kc > kTopkMergeMaxCand) return 10007;
+                // K candidates exist: the first chunk is whole unless it is the only one
+                const int first_len = p.chunks > 1 ? p.chunk_len : V;
+                if (p.kc < K && p.kc != p.chunk_len) return 10008;
+                if (p.kc == K && first_len < K) return 10009;
+                if (p.stat_off < (size_t)rows * p.chunks * p.kc * 8 || p.bytes < p.stat_off + (size_t)rows * p.chunks * 16) return 10010;
+                if ((p.stat_off & 255u) || (p.bytes & 255u)) return 10011;
+            }
+    // accept: segments tile the row in multiples of four, scratch holds one partial per segment
+    for (int V : Vs)
+        for (int T : {2, 17, 65, 257, 513, 1025})
+            for (int batch : {1, 16, 64})
+                for (int sampled = 0; sampled < 2; ++sampled) {
+                    const AcceptPlan p = accept_plan(batch, T, V, sampled != 0);
+                    if (p.seg_len % 4 != 0 || p.seg_len < 1 || p.splits < 1) return 10021;
+                    if ((long long)(p.splits - 1) * p.seg_len >= V || (long long)p.splits * p.seg_len < V) return 10022;
+                    if (p.bytes < (size_t)batch * T * p.splits * 8 || (p.bytes & 255u)) return 10023;
+                }
+    return 0;
+}

@@ -1253,9 +1253,9 @@ extern "C" int ddtree_verify_attn_spans(const void *q, const void *k_cache, cons
 // the key ranges of a tile a partition of its key tiles in order.
 // Returns 0, or 100 * (index of the failing shape + 1) + the number of the failed check.
 // ------------------------------------------------------------------------------------------
-extern "C" int ddtree_selftest_host(void)
+namespace ddt {
+int attn_selftest_host()
 {
-    using namespace ddt;
     struct Shape {
         int batch, T, Hq, Hkv;
         int32_t len[4];
@@ -1375,3 +1375,4 @@ extern "C" int ddtree_selftest_host(void)
     }
     return 0;
 }
+}  // namespace ddt
